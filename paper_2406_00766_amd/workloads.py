@@ -1,0 +1,489 @@
+"""Seeded synthetic workloads: block-level circuit structures, fp32 parameters and data.
+
+This module only *describes* inputs (structure, random parameters, random data).  It holds
+none of the method's arithmetic (no forward pass, no flows, no table compilation) and is the
+one module both the CPU oracle's tests and the GPU path's tests / benchmark draw inputs from.
+
+Structures follow the experimental section of the paper (Sec. 6, App. C): homogeneous HMMs
+written as circuits (footnote to Sec. 1), hidden Chow-Liu trees, and a Poon-Domingos grid
+structure with axis-aligned splits (App. C.4), optionally with whole child blocks pruned at
+random as in the block-sparse experiment (App. C.1).
+
+Block-level DAG convention (one "block" = K consecutive node slots):
+  type[u]        0 input, 1 product, 2 sum
+  n_real[u]      number of real nodes in the block (rows >= n_real are placeholders, Sec. 4.1 footnote)
+  child_ptr/child  CSR list of child blocks per block
+  param_blk[e]   for an edge out of a sum block: id of its K x K parameter block (equal ids = tied,
+                 App. A.3); -1 otherwise.  Parameter block p is stored at theta[p + 1]; theta[0] is an
+                 all-zero block used by table padding.  theta[p + 1][i][j] is the weight from sum node i
+                 of the parent block to node j of the child block.
+  in_var/in_table  for an input block: the variable it reads and its categorical table;
+                 tables[t][c][k] = P(X = c) under node k of the block (category-major).
+A product block multiplies its child blocks element-wise: node k of the block has node k of every
+child block as children.
+"""
+from __future__ import annotations
+
+import heapq
+from dataclasses import dataclass, field
+
+import numpy as np
+
+SEED_BASE = 240600766
+FLT_MIN = np.float32(np.finfo(np.float32).tiny)
+
+INPUT, PRODUCT, SUM = 0, 1, 2
+
+
+@dataclass
+class Workload:
+    name: str
+    K: int
+    n_blocks: int
+    root_block: int
+    type: np.ndarray
+    n_real: np.ndarray
+    child_ptr: np.ndarray
+    child: np.ndarray
+    param_blk: np.ndarray
+    n_param_blocks: int
+    in_var: np.ndarray
+    in_table: np.ndarray
+    n_vars: int
+    n_cats: int
+    n_tables: int
+    theta: np.ndarray          # float32 [n_param_blocks + 1, K, K], block 0 all zero
+    tables: np.ndarray         # float32 [n_tables, n_cats, K]
+    x: np.ndarray              # int32 [B, n_vars]
+    max_groups: int = 8
+    tol_permille: int = 250
+    meta: dict = field(default_factory=dict)
+
+    @property
+    def B(self) -> int:
+        return int(self.x.shape[0])
+
+    @property
+    def n_edges(self) -> int:
+        return int(self.child.shape[0])
+
+    def n_sum_edges(self) -> int:
+        """Node-level number of sum edges with a real parent row (the paper's circuit size)."""
+        tot = 0
+        for u in np.nonzero(self.type == SUM)[0]:
+            ch = self.child[self.child_ptr[u]:self.child_ptr[u + 1]]
+            tot += int(self.n_real[u]) * int(self.n_real[ch].sum())
+        return tot
+
+    def with_batch(self, x: np.ndarray) -> "Workload":
+        w = Workload(**{k: getattr(self, k) for k in self.__dataclass_fields__})
+        w.x = np.ascontiguousarray(x, dtype=np.int32)
+        return w
+
+
+class _Builder:
+    def __init__(self, K: int):
+        self.K = K
+        self.type: list[int] = []
+        self.n_real: list[int] = []
+        self.children: list[list[int]] = []
+        self.params: list[list[int]] = []
+        self.var: list[int] = []
+        self.table: list[int] = []
+
+    def add(self, typ: int, *, n_real: int | None = None, var: int = -1, table: int = -1) -> int:
+        self.type.append(typ)
+        self.n_real.append(self.K if n_real is None else n_real)
+        self.children.append([])
+        self.params.append([])
+        self.var.append(var)
+        self.table.append(table)
+        return len(self.type) - 1
+
+    def link(self, parent: int, child: int, param: int = -1) -> None:
+        self.children[parent].append(child)
+        self.params[parent].append(param)
+
+    def arrays(self):
+        n = len(self.type)
+        ptr = np.zeros(n + 1, dtype=np.int64)
+        for u in range(n):
+            ptr[u + 1] = ptr[u] + len(self.children[u])
+        child = np.fromiter((c for cs in self.children for c in cs), dtype=np.int32, count=int(ptr[-1]))
+        param = np.fromiter((p for ps in self.params for p in ps), dtype=np.int32, count=int(ptr[-1]))
+        return (np.asarray(self.type, dtype=np.uint8), np.asarray(self.n_real, dtype=np.int32), ptr, child, param,
+                np.asarray(self.var, dtype=np.int32), np.asarray(self.table, dtype=np.int32))
+
+
+def _f32_floor(a: np.ndarray) -> np.ndarray:
+    """Cast probabilities to fp32; exact zeros and subnormals become the smallest normal float."""
+    out = a.astype(np.float32)
+    np.maximum(out, FLT_MIN, out=out)
+    return out
+
+
+def _dirichlet_rows(rng: np.random.Generator, alpha: float, shape: tuple[int, int]) -> np.ndarray:
+    """Rows drawn from a symmetric Dirichlet(alpha), float64, each row normalised to sum 1."""
+    if alpha == 1.0:
+        g = rng.standard_exponential(shape)
+    else:
+        g = rng.standard_gamma(alpha, shape)
+    s = g.sum(axis=1, keepdims=True)
+    bad = (s <= 0).ravel()
+    if bad.any():                      # all draws underflowed: fall back to a uniform row
+        g[bad] = 1.0
+        s = g.sum(axis=1, keepdims=True)
+    return g / s
+
+
+def _dense_to_blocks(W: np.ndarray, K: int) -> np.ndarray:
+    """[R, C] -> [R/K * C/K, K, K], block (ib, jb) at index ib * (C/K) + jb."""
+    R, C = W.shape
+    return W.reshape(R // K, K, C // K, K).transpose(0, 2, 1, 3).reshape(-1, K, K)
+
+
+def _make(name, bld: _Builder, root, n_param_blocks, n_vars, n_cats, n_tables, theta, tables, x, meta,
+          max_groups=8, tol_permille=250) -> Workload:
+    typ, n_real, ptr, child, param, var, table = bld.arrays()
+    return Workload(name=name, K=bld.K, n_blocks=len(typ), root_block=root, type=typ, n_real=n_real,
+                    child_ptr=ptr, child=child, param_blk=param, n_param_blocks=n_param_blocks,
+                    in_var=var, in_table=table, n_vars=n_vars, n_cats=n_cats, n_tables=n_tables,
+                    theta=theta, tables=tables, x=np.ascontiguousarray(x, dtype=np.int32),
+                    max_groups=max_groups, tol_permille=tol_permille, meta=meta)
+
+
+# --------------------------------------------------------------------------------------------
+# HMM written as a circuit (footnote to Sec. 1; parameter tying across time, App. A.3)
+# --------------------------------------------------------------------------------------------
+def hmm(T: int, H: int, V: int, K: int, B: int, seed: int, *, alpha_init=1.0, alpha_trans=1.0,
+        alpha_emis=1.0, tokens="uniform", keep_dense=True, name=None) -> Workload:
+    """Hidden z_0..z_{T-1}, tokens x_0..x_{T-1}.
+
+    E_t[h]  input node on variable t with P(x_t = v | z_t = h), tied over t
+    P_t[h]  = E_t[h] * S_{t+1}[h]      (P_{T-1}[h] = E_{T-1}[h])
+    S_t[h]  = sum_h' A[h, h'] P_t[h']  for t = 1..T-1, tied over t
+    root    = sum_h pi[h] P_0[h]
+    """
+    assert H % K == 0 and T >= 1
+    nb = H // K
+    rng = np.random.Generator(np.random.PCG64(seed))
+    bld = _Builder(K)
+    E = [[bld.add(INPUT, var=t, table=j) for j in range(nb)] for t in range(T)]
+    P = [[bld.add(PRODUCT) for _ in range(nb)] for _ in range(T)]
+    S = [None] + [[bld.add(SUM) for _ in range(nb)] for _ in range(1, T)]
+    root = bld.add(SUM, n_real=1)
+    for t in range(T):
+        for j in range(nb):
+            bld.link(P[t][j], E[t][j])
+            if t + 1 < T:
+                bld.link(P[t][j], S[t + 1][j])
+    for t in range(1, T):
+        for i in range(nb):
+            for j in range(nb):
+                bld.link(S[t][i], P[t][j], i * nb + j)
+    n_A = nb * nb if T > 1 else 0
+    for j in range(nb):
+        bld.link(root, P[0][j], n_A + j)
+    n_param_blocks = n_A + nb
+
+    theta = np.zeros((n_param_blocks + 1, K, K), dtype=np.float32)
+    pi = _f32_floor(_dirichlet_rows(rng, alpha_init, (1, H)))[0]
+    A = None
+    if T > 1:
+        A = np.empty((H, H), dtype=np.float32)
+        step = max(1, min(H, (1 << 22) // H))
+        for r0 in range(0, H, step):
+            A[r0:r0 + step] = _f32_floor(_dirichlet_rows(rng, alpha_trans, (min(step, H - r0), H)))
+        theta[1:1 + n_A] = _dense_to_blocks(A, K)
+    theta[1 + n_A:, 0, :] = pi.reshape(nb, K)
+
+    tables = np.empty((nb, V, K), dtype=np.float32)
+    for j in range(nb):
+        Ej = _f32_floor(_dirichlet_rows(rng, alpha_emis, (K, V)))   # [K hidden states, V]
+        tables[j] = Ej.T
+
+    if tokens == "uniform":
+        x = rng.integers(0, V, size=(B, T))
+    elif tokens == "zipf":
+        w = (np.arange(V, dtype=np.float64) + 1.0) ** -1.1
+        cdf = np.cumsum(w / w.sum())
+        x = np.minimum(np.searchsorted(cdf, rng.random((B, T)), side="right"), V - 1)
+    else:
+        raise ValueError(tokens)
+
+    meta = {"kind": "hmm", "T": T, "H": H, "V": V, "pi": pi}
+    if keep_dense:
+        meta["A"] = A
+    return _make(name or f"hmm_T{T}_H{H}_V{V}_K{K}_B{B}", bld, root, n_param_blocks, T, V, nb, theta, tables, x, meta)
+
+
+def hmm_emission(w: Workload) -> np.ndarray:
+    """Emission matrix [H, V] (fp32) read back from the block tables of an HMM workload."""
+    nb, V, K = w.tables.shape
+    return w.tables.transpose(0, 2, 1).reshape(nb * K, V)
+
+
+# --------------------------------------------------------------------------------------------
+# Hidden Chow-Liu tree over a random spanning tree
+# --------------------------------------------------------------------------------------------
+def _prufer_tree(seq: np.ndarray, D: int) -> list[tuple[int, int]]:
+    degree = np.ones(D, dtype=np.int64)
+    for v in seq:
+        degree[v] += 1
+    leaves = [i for i in range(D) if degree[i] == 1]
+    heapq.heapify(leaves)
+    edges = []
+    for v in seq:
+        leaf = heapq.heappop(leaves)
+        edges.append((int(leaf), int(v)))
+        degree[v] -= 1
+        if degree[v] == 1:
+            heapq.heappush(leaves, int(v))
+    a = heapq.heappop(leaves)
+    b = heapq.heappop(leaves)
+    edges.append((int(a), int(b)))
+    return edges
+
+
+def random_tree(rng: np.random.Generator, D: int):
+    """Uniform random labelled tree on D vertices, rooted at 0.  Returns (parent[], bfs order)."""
+    if D == 1:
+        return np.array([-1]), [0]
+    if D == 2:
+        edges = [(0, 1)]
+    else:
+        edges = _prufer_tree(rng.integers(0, D, size=D - 2), D)
+    adj = [[] for _ in range(D)]
+    for a, b in edges:
+        adj[a].append(b)
+        adj[b].append(a)
+    parent = np.full(D, -1, dtype=np.int64)
+    order = [0]
+    seen = np.zeros(D, dtype=bool)
+    seen[0] = True
+    for v in order:
+        for c in sorted(adj[v]):
+            if not seen[c]:
+                seen[c] = True
+                parent[c] = v
+                order.append(c)
+    assert len(order) == D
+    return parent, order
+
+
+def hclt(D: int, M: int, K: int, B: int, seed: int, *, n_cats=256, data="gauss", name=None) -> Workload:
+    """Latent tree: each variable v has a latent z_v with M states.
+
+    E_v[k]  input node on variable v, own table per variable
+    P_v[k]  = E_v[k] * prod_{c child of v} S_c[k]
+    S_c[k]  = sum_k' W_c[k, k'] P_c[k']     for every non-root variable c
+    root    = sum_k pi[k] P_0[k]
+    """
+    assert M % K == 0
+    nb = M // K
+    rng = np.random.Generator(np.random.PCG64(seed))
+    parent, order = random_tree(rng, D)
+    kids = [[] for _ in range(D)]
+    for v in order[1:]:
+        kids[parent[v]].append(v)
+
+    bld = _Builder(K)
+    E = [[bld.add(INPUT, var=v, table=v * nb + j) for j in range(nb)] for v in range(D)]
+    P = [[bld.add(PRODUCT) for _ in range(nb)] for _ in range(D)]
+    S = [None] + [[bld.add(SUM) for _ in range(nb)] for _ in range(1, D)]
+    root = bld.add(SUM, n_real=1)
+    for v in range(D):
+        for j in range(nb):
+            bld.link(P[v][j], E[v][j])
+            for c in kids[v]:
+                bld.link(P[v][j], S[c][j])
+    for c in range(1, D):
+        base = (c - 1) * nb * nb
+        for i in range(nb):
+            for j in range(nb):
+                bld.link(S[c][i], P[c][j], base + i * nb + j)
+    n_W = (D - 1) * nb * nb
+    for j in range(nb):
+        bld.link(root, P[0][j], n_W + j)
+    n_param_blocks = n_W + nb
+
+    theta = np.zeros((n_param_blocks + 1, K, K), dtype=np.float32)
+    for c in range(1, D):
+        W = _f32_floor(_dirichlet_rows(rng, 1.0, (M, M)))
+        base = 1 + (c - 1) * nb * nb
+        theta[base:base + nb * nb] = _dense_to_blocks(W, K)
+    pi = _f32_floor(_dirichlet_rows(rng, 1.0, (1, M)))[0]
+    theta[1 + n_W:, 0, :] = pi.reshape(nb, K)
+
+    tables = np.empty((D * nb, n_cats, K), dtype=np.float32)
+    for v in range(D):
+        Tv = _f32_floor(_dirichlet_rows(rng, 1.0, (M, n_cats)))          # [latent state, category]
+        tables[v * nb:(v + 1) * nb] = Tv.reshape(nb, K, n_cats).transpose(0, 2, 1)
+
+    hi = n_cats - 1
+    mu = rng.uniform(0.0, float(hi), size=D)
+    std = 40.0 * n_cats / 256.0
+    if data == "gauss":
+        x = np.clip(np.rint(rng.normal(mu[None, :], std, size=(B, D))), 0, hi)
+    elif data == "gauss_corr":
+        amp = 16.0 * n_cats / 256.0
+        off = np.empty((B, D))
+        off[:, 0] = np.where(rng.random(B) < 0.5, -amp, amp)
+        flip = rng.random((B, D)) >= 0.75
+        for v in order[1:]:
+            off[:, v] = np.where(flip[:, v], -off[:, parent[v]], off[:, parent[v]])
+        x = np.clip(np.rint(rng.normal(mu[None, :] + off, std)), 0, hi)
+    elif data == "uniform":
+        x = rng.integers(0, n_cats, size=(B, D))
+    else:
+        raise ValueError(data)
+
+    meta = {"kind": "hclt", "D": D, "M": M, "parent": parent, "order": order, "pi": pi}
+    return _make(name or f"hclt_D{D}_M{M}_K{K}_B{B}", bld, root, n_param_blocks, D, n_cats, D * nb, theta, tables, x, meta)
+
+
+def hclt_edge_weights(w: Workload, c: int) -> np.ndarray:
+    """W_c [M, M] (fp32) of tree edge parent(c) -> c, read back from theta."""
+    M, K = w.meta["M"], w.K
+    nb = M // K
+    base = 1 + (c - 1) * nb * nb
+    return w.theta[base:base + nb * nb].reshape(nb, nb, K, K).transpose(0, 2, 1, 3).reshape(M, M)
+
+
+def hclt_table(w: Workload, v: int) -> np.ndarray:
+    """Emission table [M, n_cats] (fp32) of variable v."""
+    M, K = w.meta["M"], w.K
+    nb = M // K
+    return w.tables[v * nb:(v + 1) * nb].transpose(0, 2, 1).reshape(M, -1)
+
+
+# --------------------------------------------------------------------------------------------
+# Poon-Domingos region structure with axis-aligned splits, optional block pruning
+# --------------------------------------------------------------------------------------------
+def pd(grid: int, cell: int, M: int, K: int, B: int, seed: int, *, keep=1.0, n_cats=256, name=None) -> Workload:
+    """grid x grid coarse cells of cell x cell pixels.  Regions = all coarse rectangles.
+
+    leaf cell:   L[k] = prod_{pixels} E_pixel[k]; its region's sums range over L
+    other region: one block of M product nodes per two-way split, P[k] = S_left[k] * S_right[k];
+                  the region's M sums (root: one) range over the product nodes of all its splits
+    keep < 1:    each (sum block, child block) pair survives with probability `keep`
+                 (at least one child block per sum block always survives)
+    """
+    assert M % K == 0
+    nb = M // K
+    side = grid * cell
+    D = side * side
+    rng = np.random.Generator(np.random.PCG64(seed))
+    bld = _Builder(K)
+
+    E = [[bld.add(INPUT, var=v, table=v * nb + j) for j in range(nb)] for v in range(D)]
+    regions = [(x0, x1, y0, y1) for x0 in range(grid) for x1 in range(x0 + 1, grid + 1)
+               for y0 in range(grid) for y1 in range(y0 + 1, grid + 1)]
+    regions.sort(key=lambda r: ((r[1] - r[0]) + (r[3] - r[2]), r))
+    full = (0, grid, 0, grid)
+    S = {}
+    for r in regions:
+        if r == full:
+            S[r] = [bld.add(SUM, n_real=1)]
+        else:
+            S[r] = [bld.add(SUM) for _ in range(nb)]
+    root = S[full][0]
+
+    sum_children: dict = {}
+    for r in regions:
+        x0, x1, y0, y1 = r
+        prods = []
+        if x1 - x0 == 1 and y1 - y0 == 1:
+            L = [bld.add(PRODUCT) for _ in range(nb)]
+            for py in range(y0 * cell, (y0 + 1) * cell):
+                for px in range(x0 * cell, (x0 + 1) * cell):
+                    for j in range(nb):
+                        bld.link(L[j], E[py * side + px][j])
+            prods.extend(L)
+        else:
+            splits = [((x0, c, y0, y1), (c, x1, y0, y1)) for c in range(x0 + 1, x1)]
+            splits += [((x0, x1, y0, c), (x0, x1, c, y1)) for c in range(y0 + 1, y1)]
+            for a, b in splits:
+                Pb = [bld.add(PRODUCT) for _ in range(nb)]
+                for j in range(nb):
+                    bld.link(Pb[j], S[a][j])
+                    bld.link(Pb[j], S[b][j])
+                prods.extend(Pb)
+        sum_children[r] = prods
+
+    n_param_blocks = 0
+    kept: list[tuple[int, list[int]]] = []
+    for r in regions:
+        prods = sum_children[r]
+        for s in S[r]:
+            if keep >= 1.0:
+                ks = list(prods)
+            else:
+                m = rng.random(len(prods)) < keep
+                if not m.any():
+                    m[rng.integers(0, len(prods))] = True
+                ks = [p for p, f in zip(prods, m) if f]
+            for p in ks:
+                bld.link(s, p, n_param_blocks)
+                n_param_blocks += 1
+            kept.append((s, ks))
+
+    theta = np.zeros((n_param_blocks + 1, K, K), dtype=np.float32)
+    pos = 1
+    for s, ks in kept:
+        nk = len(ks)
+        rows = 1 if s == root else K
+        W = _f32_floor(_dirichlet_rows(rng, 1.0, (rows, nk * K)))
+        theta[pos:pos + nk, :rows, :] = W.reshape(rows, nk, K).transpose(1, 0, 2)
+        pos += nk
+
+    tables = np.empty((D * nb, n_cats, K), dtype=np.float32)
+    for v in range(D):
+        Tv = _f32_floor(_dirichlet_rows(rng, 1.0, (M, n_cats)))
+        tables[v * nb:(v + 1) * nb] = Tv.reshape(nb, K, n_cats).transpose(0, 2, 1)
+
+    x = rng.integers(0, n_cats, size=(B, D))
+    meta = {"kind": "pd", "grid": grid, "cell": cell, "M": M, "keep": keep}
+    return _make(name or f"pd_g{grid}_c{cell}_M{M}_K{K}_keep{keep}_B{B}", bld, root, n_param_blocks, D, n_cats,
+                 D * nb, theta, tables, x, meta)
+
+
+# --------------------------------------------------------------------------------------------
+# The five benchmark configurations and their reduced twins
+# --------------------------------------------------------------------------------------------
+DEFAULT_K = {1: 32, 2: 64, 3: 64, 4: 128, 5: 32}
+
+
+def config(idx: int, *, K: int | None = None, B: int | None = None) -> Workload:
+    """Full-size configuration `idx` (1-based).  Seed = SEED_BASE + idx."""
+    K = K or DEFAULT_K[idx]
+    seed = SEED_BASE + idx
+    if idx == 1:
+        return hmm(16, 32, 64, K, B or 128, seed, name=f"cfg1_hmm_T16_H32_V64_B{B or 128}")
+    if idx == 2:
+        return hclt(784, 128, K, B or 512, seed, data="gauss", name=f"cfg2_hclt_D784_M128_B{B or 512}")
+    if idx == 3:
+        return hclt(3072, 256, K, B or 256, seed, data="gauss_corr", name=f"cfg3_hclt_D3072_M256_B{B or 256}")
+    if idx == 4:
+        return hmm(32, 4096, 50257, K, B or 256, seed, alpha_trans=0.1, alpha_emis=0.1, tokens="zipf",
+                   keep_dense=False, name=f"cfg4_hmm_T32_H4096_V50257_B{B or 256}")
+    if idx == 5:
+        return pd(8, 4, 256, K, B or 256, seed, keep=0.25, name=f"cfg5_pd_32x32_M256_keep25_B{B or 256}")
+    raise ValueError(idx)
+
+
+def reduced(idx: int, *, K: int | None = None, B: int | None = None) -> Workload:
+    """Same structure family and value distributions as `config(idx)`, at a size a plain CPU
+    implementation finishes in seconds; still spans several blocks and a ragged batch tail."""
+    seed = SEED_BASE + 100 + idx
+    if idx == 1:
+        return hmm(6, 64, 50, K or 32, B or 77, seed)
+    if idx == 2:
+        return hclt(24, 64, K or 32, B or 100, seed, n_cats=64, data="gauss")
+    if idx == 3:
+        return hclt(40, 128, K or 64, B or 70, seed, n_cats=32, data="gauss_corr")
+    if idx == 4:
+        return hmm(5, 256, 1000, K or 64, B or 96, seed, alpha_trans=0.1, alpha_emis=0.1, tokens="zipf")
+    if idx == 5:
+        return pd(3, 2, 64, K or 32, B or 45, seed, keep=0.25, n_cats=16)
+    raise ValueError(idx)
