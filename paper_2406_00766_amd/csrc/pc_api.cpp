@@ -1,0 +1,287 @@
+// C-ABI entry points of libpc: compile + upload, inspection, forward, backward, EM step.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "pc_internal.h"
+#include "pc_kernels.h"
+
+namespace pc {
+const char *last_error_cstr();
+
+static pc_status hip_fail(hipError_t e, const char *what)
+{
+    return fail(PC_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define PC_HIP(call)                                      \
+    do {                                                  \
+        hipError_t e_ = (call);                           \
+        if (e_ != hipSuccess) return hip_fail(e_, #call); \
+    } while (0)
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// One arena for every table: sizes first, then pointers.
+static pc_status upload(pc_circuit *c, hipStream_t stream)
+{
+    size_t bytes = 0;
+    auto reserve = [&](size_t n_i32) { size_t off = bytes; bytes = align_up(bytes + n_i32 * 4, 256); return off; };
+    struct Fix { void **dst; size_t off; const void *src; size_t n; };
+    std::vector<Fix> fixes;
+    auto add = [&](int32_t **dst, const std::vector<int32_t> &v) {
+        fixes.push_back({(void **)dst, reserve(v.size()), v.data(), v.size() * 4});
+    };
+    for (auto &layer : c->layers) {
+        add(&layer.d_blk_ids, layer.blk_ids);
+        for (auto *groups : {&layer.fwd, &layer.bwd})
+            for (auto &g : *groups) { add(&g.d_ids, g.ids); add(&g.d_nbr, g.nbr); add(&g.d_par, g.par); }
+    }
+    add(&c->d_pb_group, c->pb_group); add(&c->d_pb_rows, c->pb_rows); add(&c->d_pb_cols, c->pb_cols);
+    add(&c->d_group_nch, c->group_nch);
+    const size_t zrow_off = reserve((size_t)c->n_em_groups * c->K + 1);
+    const size_t ztab_off = reserve((size_t)c->n_tables * c->K + 1);
+    PC_HIP(hipMalloc(&c->d_arena, bytes));
+    c->arena_bytes = bytes;
+    char *base = (char *)c->d_arena;
+    for (auto &f : fixes) {
+        *f.dst = base + f.off;
+        if (f.n) PC_HIP(hipMemcpyAsync(base + f.off, f.src, f.n, hipMemcpyHostToDevice, stream));
+    }
+    c->d_zrow = (float *)(base + zrow_off);
+    c->d_ztab = (float *)(base + ztab_off);
+    PC_HIP(hipStreamSynchronize(stream));
+    c->on_device = true;
+    return PC_OK;
+}
+
+static GroupDev dev(const GroupTab &g) { return GroupDev{g.n_rows, g.width, g.d_ids, g.d_nbr, g.d_par, g.tied_in_group}; }
+
+struct Ws {
+    int64_t Bs;
+    size_t l_off, f_off, n_off, r_off, mx_off, xt_off, total;
+};
+static Ws ws_layout(const pc_circuit *c, int32_t B)
+{
+    Ws w;
+    w.Bs = ((int64_t)B + 31) / 32 * 32;
+    const size_t rows = ((size_t)c->n_blocks + 1) * c->K;
+    const size_t node = align_up(rows * w.Bs * 4, 256);
+    w.l_off = 0; w.f_off = node; w.n_off = 2 * node;
+    const size_t per_block = align_up(((size_t)c->n_blocks + 1) * w.Bs * 4, 256);
+    w.r_off = 3 * node;
+    w.mx_off = w.r_off + per_block;
+    w.xt_off = w.mx_off + per_block;
+    w.total = w.xt_off + align_up((size_t)c->n_vars * w.Bs * 4, 256);
+    return w;
+}
+
+}  // namespace pc
+
+using namespace pc;
+
+extern "C" {
+
+const char *pc_last_error(void) { return last_error_cstr(); }
+
+// Host-only compilation (no GPU touched): used to check the compiled tables on machines without a GPU.
+pc_status pc_compile_host(const pc_dag *dag, pc_circuit **out)
+{
+    if (!out) return fail(PC_ERR_ARG, "out is NULL");
+    pc_circuit *c = new (std::nothrow) pc_circuit();
+    if (!c) return fail(PC_ERR_ARG, "out of host memory");
+    pc_status st = compile_host(dag, c);
+    if (st != PC_OK) { delete c; return st; }
+    *out = c;
+    return PC_OK;
+}
+
+pc_status pc_compile(const pc_dag *dag, void *stream, pc_circuit **out)
+{
+    pc_circuit *c = nullptr;
+    pc_status st = pc_compile_host(dag, &c);
+    if (st != PC_OK) return st;
+    st = upload(c, (hipStream_t)stream);
+    if (st != PC_OK) { pc_destroy(c); return st; }
+    const char *env = std::getenv("PC_FORCE_GENERIC");
+    set_force_generic(env && env[0] == '1');
+    *out = c;
+    return PC_OK;
+}
+
+void pc_destroy(pc_circuit *c)
+{
+    if (!c) return;
+    if (c->d_arena) (void)hipFree(c->d_arena);
+    delete c;
+}
+
+pc_status pc_get_sizes(const pc_circuit *c, pc_sizes *out)
+{
+    if (!c || !out) return fail(PC_ERR_ARG, "NULL argument");
+    out->K = c->K; out->n_blocks = c->n_blocks; out->n_layers = (int32_t)c->layers.size();
+    out->n_rows = ((int64_t)c->n_blocks + 1) * c->K;
+    out->theta_len = ((int64_t)c->n_param_blocks + 1) * c->K * c->K;
+    out->tables_len = (int64_t)c->n_tables * c->n_cats * c->K;
+    out->n_vars = c->n_vars; out->n_cats = c->n_cats; out->n_tables = c->n_tables;
+    return PC_OK;
+}
+
+pc_status pc_get_layer(const pc_circuit *c, int32_t layer, pc_layer_desc *out)
+{
+    if (!c || !out) return fail(PC_ERR_ARG, "NULL argument");
+    if (layer < 0 || layer >= (int32_t)c->layers.size()) return fail(PC_ERR_ARG, "layer out of range");
+    const LayerTab &L = c->layers[layer];
+    out->kind = L.kind; out->depth = L.depth;
+    out->n_fwd_groups = (int32_t)L.fwd.size(); out->n_bwd_groups = (int32_t)L.bwd.size();
+    return PC_OK;
+}
+
+static const GroupTab *find_group(const pc_circuit *c, int32_t layer, int32_t dir, int32_t group)
+{
+    if (!c || layer < 0 || layer >= (int32_t)c->layers.size() || (dir != 0 && dir != 1)) return nullptr;
+    const auto &gs = dir == 0 ? c->layers[layer].fwd : c->layers[layer].bwd;
+    if (group < 0 || group >= (int32_t)gs.size()) return nullptr;
+    return &gs[group];
+}
+
+pc_status pc_get_group(const pc_circuit *c, int32_t layer, int32_t dir, int32_t group, pc_group_desc *out)
+{
+    const GroupTab *g = find_group(c, layer, dir, group);
+    if (!g || !out) return fail(PC_ERR_ARG, "layer / dir / group out of range");
+    out->n_rows = g->n_rows; out->width = g->width;
+    out->ids = g->d_ids; out->nbr = g->d_nbr; out->par = g->d_par;
+    return PC_OK;
+}
+
+pc_status pc_copy_group(const pc_circuit *c, int32_t layer, int32_t dir, int32_t group,
+                        int32_t *ids_host, int32_t *nbr_host, int32_t *par_host)
+{
+    const GroupTab *g = find_group(c, layer, dir, group);
+    if (!g) return fail(PC_ERR_ARG, "layer / dir / group out of range");
+    const size_t n_ids = (size_t)g->n_rows * 4, n_tab = (size_t)g->n_rows * g->width * 4;
+    if (c->on_device) {                                   // what the kernels really read
+        if (ids_host && n_ids) PC_HIP(hipMemcpy(ids_host, g->d_ids, n_ids, hipMemcpyDeviceToHost));
+        if (nbr_host && n_tab) PC_HIP(hipMemcpy(nbr_host, g->d_nbr, n_tab, hipMemcpyDeviceToHost));
+        if (par_host && n_tab) PC_HIP(hipMemcpy(par_host, g->d_par, n_tab, hipMemcpyDeviceToHost));
+    } else {
+        if (ids_host) std::memcpy(ids_host, g->ids.data(), n_ids);
+        if (nbr_host) std::memcpy(nbr_host, g->nbr.data(), n_tab);
+        if (par_host) std::memcpy(par_host, g->par.data(), n_tab);
+    }
+    return PC_OK;
+}
+
+pc_status pc_workspace_layout(const pc_circuit *c, int32_t B, pc_ws_layout *out)
+{
+    if (!c || !out) return fail(PC_ERR_ARG, "NULL argument");
+    if (B < 1) return fail(PC_ERR_ARG, "B must be positive");
+    const Ws w = ws_layout(c, B);
+    out->stride = w.Bs; out->l_offset = w.l_off; out->f_offset = w.f_off; out->n_offset = w.n_off;
+    out->r_offset = w.r_off;
+    out->total_bytes = w.total;
+    return PC_OK;
+}
+
+pc_status pc_workspace_bytes(const pc_circuit *c, int32_t B, size_t *bytes)
+{
+    pc_ws_layout lay;
+    if (!bytes) return fail(PC_ERR_ARG, "NULL argument");
+    pc_status st = pc_workspace_layout(c, B, &lay);
+    if (st == PC_OK) *bytes = lay.total_bytes;
+    return st;
+}
+
+pc_status pc_forward(pc_circuit *c, const float *theta, const float *tables, const int32_t *x,
+                     const uint8_t *mask, int32_t B, void *workspace, size_t workspace_bytes,
+                     float *ll, void *stream)
+{
+    if (!c || !theta || !tables || !x || !workspace || !ll) return fail(PC_ERR_ARG, "NULL argument");
+    if (!c->on_device) return fail(PC_ERR_STATE, "circuit was compiled without a device");
+    if (B < 1) return fail(PC_ERR_ARG, "B must be positive");
+    const Ws w = ws_layout(c, B);
+    if (workspace_bytes < w.total) return fail(PC_ERR_WORKSPACE, "workspace smaller than pc_workspace_bytes");
+    hipStream_t s = (hipStream_t)stream;
+    char *base = (char *)workspace;
+    float *l = (float *)(base + w.l_off), *R = (float *)(base + w.r_off);
+    int32_t *xT = (int32_t *)(base + w.xt_off);
+    const int32_t K = c->K;
+    c->fw_B = -1;
+
+    launch_prepare_x(x, mask, B, c->n_vars, w.Bs, c->n_cats, xT, s);
+    launch_fill(l, (int64_t)K * w.Bs, 0.0f, s);                                  // null block: probability 1
+    launch_fill(R, ((int64_t)c->n_blocks + 1) * w.Bs, 0.0f, s);                  // input and null blocks: R = 0
+    for (const LayerTab &L : c->layers) {
+        if (L.kind == KIND_INPUT) {
+            launch_input_fwd(tables, xT, dev(L.fwd[0]), K, c->n_cats, w.Bs, l, s);
+        } else if (L.kind == KIND_PRODUCT) {
+            for (const GroupTab &g : L.fwd) launch_prod_fwd(l, R, dev(g), K, w.Bs, s);
+        } else {
+            for (const GroupTab &g : L.fwd) launch_sum_fwd(theta, l, R, dev(g), K, w.Bs, s);
+        }
+    }
+    launch_readout(l, R, (int64_t)(c->root_block + 1) * K, (int64_t)c->root_block + 1, w.Bs, B, ll, s);
+    PC_HIP(hipGetLastError());
+    c->fw_workspace = workspace; c->fw_theta = theta; c->fw_tables = tables; c->fw_x = x; c->fw_mask = mask;
+    c->fw_B = B;
+    return PC_OK;
+}
+
+pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, const int32_t *x,
+                      const uint8_t *mask, int32_t B, void *workspace, size_t workspace_bytes,
+                      float *theta_flow, float *table_flow, void *stream)
+{
+    if (!c || !theta || !tables || !x || !workspace) return fail(PC_ERR_ARG, "NULL argument");
+    if (!c->on_device) return fail(PC_ERR_STATE, "circuit was compiled without a device");
+    if (c->fw_B != B || c->fw_workspace != workspace || c->fw_theta != theta || c->fw_tables != tables ||
+        c->fw_x != x || c->fw_mask != mask)
+        return fail(PC_ERR_STATE, "pc_backward needs the pc_forward that just ran on the same arguments");
+    const Ws w = ws_layout(c, B);
+    if (workspace_bytes < w.total) return fail(PC_ERR_WORKSPACE, "workspace smaller than pc_workspace_bytes");
+    hipStream_t s = (hipStream_t)stream;
+    char *base = (char *)workspace;
+    float *l = (float *)(base + w.l_off), *F = (float *)(base + w.f_off), *N = (float *)(base + w.n_off);
+    float *nfmax = (float *)(base + w.mx_off);
+    const float *R = (const float *)(base + w.r_off);
+    const int32_t *xT = (const int32_t *)(base + w.xt_off);
+    const int32_t K = c->K;
+    const int64_t rows = ((int64_t)c->n_blocks + 1) * K;
+
+    launch_fill(F, rows * w.Bs, 0.0f, s);
+    launch_root_flow(l, F, (int64_t)(c->root_block + 1) * K, w.Bs, B, s);
+    for (size_t li = c->layers.size(); li-- > 0;) {
+        const LayerTab &L = c->layers[li];
+        if (L.kind == KIND_SUM) {
+            launch_lognf(l, F, N, nfmax, L.d_blk_ids, (int32_t)L.blk_ids.size(), K, w.Bs, s);
+            for (const GroupTab &g : L.bwd) launch_sum_bwd_child(theta, l, R, N, nfmax, F, dev(g), K, w.Bs, s);
+            if (theta_flow)
+                for (const GroupTab &g : L.fwd) launch_sum_bwd_param(theta, l, R, N, nfmax, theta_flow, dev(g), K, w.Bs, B, s);
+        } else if (L.kind == KIND_PRODUCT) {
+            for (const GroupTab &g : L.bwd) launch_prod_bwd(F, dev(g), K, w.Bs, s);
+        } else if (table_flow) {
+            launch_input_bwd(F, xT, dev(L.fwd[0]), K, c->n_cats, w.Bs, table_flow, s);
+        }
+    }
+    PC_HIP(hipGetLastError());
+    return PC_OK;
+}
+
+pc_status pc_em_step(pc_circuit *c, float *theta, float *tables, float *theta_flow, float *table_flow,
+                     float step, float pseudocount, void *stream)
+{
+    if (!c || !theta || !tables || !theta_flow || !table_flow) return fail(PC_ERR_ARG, "NULL argument");
+    if (!c->on_device) return fail(PC_ERR_STATE, "circuit was compiled without a device");
+    if (!(step >= 0.0f && step <= 1.0f) || !(pseudocount >= 0.0f)) return fail(PC_ERR_ARG, "step in [0,1], pseudocount >= 0");
+    EmDev em{c->n_em_groups, c->d_pb_group, c->d_pb_rows, c->d_pb_cols, c->d_group_nch, c->d_zrow, c->d_ztab};
+    launch_em(theta, tables, theta_flow, table_flow, em, c->K, c->n_param_blocks, c->n_tables, c->n_cats, step,
+              pseudocount, (hipStream_t)stream);
+    launch_fill(theta_flow, (int64_t)c->K * c->K, 0.0f, (hipStream_t)stream);     // the padding block of the flows
+    PC_HIP(hipGetLastError());
+    c->fw_B = -1;
+    return PC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,62 @@
+// Internal structures of libpc (not part of the C ABI).
+#pragma once
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "pc.h"
+
+namespace pc {
+
+enum : int { KIND_INPUT = 0, KIND_PRODUCT = 1, KIND_SUM = 2 };
+
+// One group of a layer: rows padded to a common width (Sec. 4.3).
+struct GroupTab {
+    int32_t n_rows = 0, width = 0;
+    std::vector<int32_t> ids, nbr, par;              // host copies
+    int32_t *d_ids = nullptr, *d_nbr = nullptr, *d_par = nullptr;
+    bool tied_in_group = false;                       // a parameter block occurs twice: flows need atomics
+};
+
+struct LayerTab {
+    int32_t kind = 0, depth = 0;
+    std::vector<GroupTab> fwd, bwd;
+    std::vector<int32_t> blk_ids;                     // node offsets of all blocks of the layer, ascending
+    int32_t *d_blk_ids = nullptr;
+};
+
+}  // namespace pc
+
+struct pc_circuit {
+    int32_t K = 0, n_blocks = 0, root_block = 0, n_param_blocks = 0;
+    int32_t n_vars = 0, n_cats = 0, n_tables = 0;
+    std::vector<pc::LayerTab> layers;
+
+    // EM normalisation: parameter block -> (row group, real rows, real cols); row group -> child count
+    int32_t n_em_groups = 0;
+    std::vector<int32_t> pb_group, pb_rows, pb_cols, group_nch;
+    int32_t *d_pb_group = nullptr, *d_pb_rows = nullptr, *d_pb_cols = nullptr, *d_group_nch = nullptr;
+    float *d_zrow = nullptr;                          // [n_em_groups * K] row sums of flows
+    float *d_ztab = nullptr;                          // [n_tables * K] column sums of table flows
+
+    void *d_arena = nullptr;                          // one device allocation behind every d_* above
+    size_t arena_bytes = 0;
+    bool on_device = false;
+
+    // state linking pc_backward to the preceding pc_forward
+    const void *fw_workspace = nullptr;
+    const void *fw_theta = nullptr, *fw_tables = nullptr, *fw_x = nullptr, *fw_mask = nullptr;
+    int32_t fw_B = -1;
+};
+
+namespace pc {
+
+void set_error(const std::string &msg);
+pc_status fail(pc_status st, const std::string &msg);
+
+// Host part of compilation: validation, layering, grouping, table construction, EM maps.
+pc_status compile_host(const pc_dag *dag, pc_circuit *c);
+// Alg. 2 (App. A.1): ascending group capacities for the given neighbour counts.
+std::vector<int32_t> partition_groups(const std::vector<int32_t> &counts, int32_t max_groups, int32_t tol_permille);
+
+}  // namespace pc

@@ -1,0 +1,45 @@
+// Launchers of the HIP kernels (internal).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace pc {
+
+struct GroupDev {            // device view of one table group
+    int32_t n_rows, width;
+    const int32_t *ids, *nbr, *par;
+    bool tied;
+};
+
+struct EmDev {
+    int32_t n_groups;
+    const int32_t *pb_group, *pb_rows, *pb_cols, *group_nch;
+    float *zrow, *ztab;
+};
+
+void set_force_generic(bool on);
+
+void launch_fill(float *p, int64_t n, float v, hipStream_t s);
+void launch_prepare_x(const int32_t *x, const uint8_t *mask, int32_t B, int32_t D, int64_t Bs, int32_t n_cats,
+                      int32_t *xT, hipStream_t s);
+void launch_readout(const float *l, const float *R, int64_t root_row, int64_t root_blk, int64_t Bs, int32_t B, float *ll,
+                    hipStream_t s);
+void launch_root_flow(const float *l, float *F, int64_t root_row, int64_t Bs, int32_t B, hipStream_t s);
+void launch_input_fwd(const float *tables, const int32_t *xT, const GroupDev &g, int32_t K, int32_t n_cats, int64_t Bs,
+                      float *l, hipStream_t s);
+void launch_input_bwd(const float *F, const int32_t *xT, const GroupDev &g, int32_t K, int32_t n_cats, int64_t Bs,
+                      float *table_flow, hipStream_t s);
+void launch_prod_fwd(float *l, float *R, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s);
+void launch_prod_bwd(float *F, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s);
+void launch_lognf(const float *l, const float *F, float *N, float *nfmax, const int32_t *blk_ids, int32_t n_blk,
+                  int32_t K, int64_t Bs, hipStream_t s);
+void launch_sum_fwd(const float *theta, float *l, float *R, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s);
+void launch_sum_bwd_child(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *F,
+                          const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s);
+void launch_sum_bwd_param(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *G,
+                          const GroupDev &g, int32_t K, int64_t Bs, int32_t B, hipStream_t s);
+void launch_em(float *theta, float *tables, float *theta_flow, float *table_flow, const EmDev &em, int32_t K,
+               int32_t n_param_blocks, int32_t n_tables, int32_t n_cats, float step, float pc, hipStream_t s);
+
+}  // namespace pc

@@ -1,0 +1,868 @@
+// HIP kernels (gfx950) and their launchers for the layered forward / backward passes.
+//
+// Node buffers are row-major [node offset][sample], samples contiguous (l_prod in R^{N x B},
+// l_sum in R^{M x B} of Sec. 4.3), row stride Bs = B rounded up to 32.
+//
+// Log-probabilities are kept as  log p(node, b) = R[block, b] + l[node, b]:  R is an integer-valued
+// float per (block, sample) and l a small fp32 residual.  Deep circuits reach log-probabilities of
+// -10^4 and below, where one fp32 holds only ~1e-3 absolute -- too coarse for the ratios p_c / p_n of
+// Def. 2.  Product blocks renormalise (R = sum of the children's R + round(column max), l = rest);
+// a sum block takes R = max of its children's R; differences of R are exact, so every exp() below
+// sees a small, accurately known argument.  The paper stores plain fp32 log-probabilities.
+//
+// Sum layers use v_mfma_f32_32x32x2_f32.  Operand layout of that instruction (wave64):
+//   A (32 x 2): lane holds A[i = lane % 32][k = lane / 32]
+//   B (2 x 32): lane holds B[k = lane / 32][j = lane % 32]
+//   D (32 x 32): register r of a lane holds D[i = 8 * (r / 4) + 4 * (lane / 32) + r % 4][j = lane % 32]
+// With sum nodes on i and samples on j, every lane owns one sample column, so the per-sample
+// running maximum of the log-sum-exp is a per-lane scalar.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "pc_kernels.h"
+
+namespace pc {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+#define PC_NEG_INF (-__builtin_inff())
+
+// ------------------------------------------------------------------------------------------
+// small utility kernels
+// ------------------------------------------------------------------------------------------
+__global__ void k_fill(float *p, int64_t n, float v)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
+}
+
+// xT[v][b] = category, -1 if marginalised (mask, or padding column b >= B), -2 if out of range.
+__global__ void k_prepare_x(const int32_t *__restrict__ x, const uint8_t *__restrict__ mask, int32_t B, int32_t D,
+                            int64_t Bs, int32_t n_cats, int32_t *__restrict__ xT)
+{
+    __shared__ int32_t tile[32][33];
+    const int b0 = blockIdx.x * 32, v0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;           // 256 threads: ty in 0..7
+    for (int r = ty; r < 32; r += 8) {
+        const int b = b0 + r, v = v0 + tx;
+        int32_t val = -1;
+        if (b < B && v < D) {
+            const int64_t idx = (int64_t)b * D + v;
+            val = x[idx];
+            if (val < 0 || val >= n_cats) val = -2;
+            if (mask && mask[idx]) val = -1;
+        }
+        tile[r][tx] = val;
+    }
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8) {
+        const int v = v0 + r, b = b0 + tx;
+        if (v < D && b < Bs) xT[(int64_t)v * Bs + b] = tile[tx][r];
+    }
+}
+
+__global__ void k_readout(const float *__restrict__ l, const float *__restrict__ R, int64_t root_row, int64_t root_blk,
+                          int64_t Bs, int32_t B, float *__restrict__ ll)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) ll[b] = R[root_blk * Bs + b] + l[root_row * Bs + b];
+}
+
+// F_root = 1 (Def. 2) for real samples of non-zero probability, 0 otherwise.
+__global__ void k_root_flow(const float *__restrict__ l, float *__restrict__ F, int64_t root_row, int64_t Bs, int32_t B)
+{
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < Bs) F[root_row * Bs + b] = (b < B && l[root_row * Bs + b] > PC_NEG_INF) ? 1.0f : 0.0f;
+}
+
+// ------------------------------------------------------------------------------------------
+// input layer (categorical): l[n,b] = log table[t][x_b,v][k]
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_input_fwd(const float *__restrict__ tables, const int32_t *__restrict__ xT,
+                                                   const int32_t *__restrict__ ids, const int32_t *__restrict__ var,
+                                                   const int32_t *__restrict__ tab, int32_t K, int32_t n_cats,
+                                                   int64_t Bs, float *__restrict__ l)
+{
+    const int u = blockIdx.x;
+    const int64_t b = (int64_t)blockIdx.y * 256 + threadIdx.x;
+    if (b >= Bs) return;
+    const int32_t xv = xT[(int64_t)var[u] * Bs + b];
+    float *out = l + (int64_t)ids[u] * Bs + b;
+    if (xv < 0) {
+        const float v = xv == -1 ? 0.0f : PC_NEG_INF;
+        for (int k = 0; k < K; ++k) out[(int64_t)k * Bs] = v;
+        return;
+    }
+    const float *row = tables + ((int64_t)tab[u] * n_cats + xv) * K;
+    if ((K & 3) == 0) {
+        for (int k = 0; k < K; k += 4) {
+            const float4 t = *reinterpret_cast<const float4 *>(row + k);
+            out[(int64_t)(k + 0) * Bs] = __logf(t.x);
+            out[(int64_t)(k + 1) * Bs] = __logf(t.y);
+            out[(int64_t)(k + 2) * Bs] = __logf(t.z);
+            out[(int64_t)(k + 3) * Bs] = __logf(t.w);
+        }
+    } else {
+        for (int k = 0; k < K; ++k) out[(int64_t)k * Bs] = __logf(row[k]);
+    }
+}
+
+// table_flow[t][x_b,v][k] += F[n,b] for observed variables
+__global__ __launch_bounds__(256) void k_input_bwd(const float *__restrict__ F, const int32_t *__restrict__ xT,
+                                                   const int32_t *__restrict__ ids, const int32_t *__restrict__ var,
+                                                   const int32_t *__restrict__ tab, int32_t K, int32_t n_cats,
+                                                   int64_t Bs, float *__restrict__ table_flow)
+{
+    const int u = blockIdx.x;
+    const int64_t b = (int64_t)blockIdx.y * 256 + threadIdx.x;
+    if (b >= Bs) return;
+    const int32_t xv = xT[(int64_t)var[u] * Bs + b];
+    if (xv < 0) return;
+    const float *in = F + (int64_t)ids[u] * Bs + b;
+    float *row = table_flow + ((int64_t)tab[u] * n_cats + xv) * K;
+    for (int k = 0; k < K; ++k) {
+        const float f = in[(int64_t)k * Bs];
+        if (f != 0.0f) atomicAdd(row + k, f);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// product layers: forward adds child log-probs (Sec. 3); backward adds parent flows (Def. 2)
+// ------------------------------------------------------------------------------------------
+// One workgroup = one product block x 64*V sample columns; thread (rg, lane) owns rows rg, rg+4, ...
+// of V adjacent columns.  s = sum of the children's residuals; the column maximum over the K rows is
+// rounded to an integer and moved into R.
+template <int V>
+__global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *__restrict__ R,
+                                                  const int32_t *__restrict__ ids, const int32_t *__restrict__ nbr,
+                                                  int32_t width, int32_t K, int64_t Bs)
+{
+    constexpr int RPT = 32;                                            // rows per thread (K <= 128)
+    __shared__ float red[4][64 * V];
+    const int r = blockIdx.x;
+    const int rg = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t b = ((int64_t)blockIdx.y * 64 + lane) * V;
+    const bool in = b < Bs;
+    float s[RPT][V];
+    float mx[V], rsum[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) { mx[v] = PC_NEG_INF; rsum[v] = 0.0f; }
+    const int32_t *row_nbr = nbr + (int64_t)r * width;
+    if (in) {
+#pragma unroll
+        for (int i = 0; i < RPT; ++i) {
+            const int k = rg + 4 * i;
+#pragma unroll
+            for (int v = 0; v < V; ++v) s[i][v] = 0.0f;
+            if (k < K) {
+                for (int j = 0; j < width; ++j) {
+                    const float *src = l + (int64_t)(row_nbr[j] + k) * Bs + b;
+                    if (V == 4) {
+                        const float4 t = *reinterpret_cast<const float4 *>(src);
+                        s[i][0] += t.x; s[i][1 % V] += t.y; s[i][2 % V] += t.z; s[i][3 % V] += t.w;
+                    } else {
+                        s[i][0] += src[0];
+                    }
+                }
+#pragma unroll
+                for (int v = 0; v < V; ++v) mx[v] = fmaxf(mx[v], s[i][v]);
+            }
+        }
+        if (rg == 0)
+            for (int j = 0; j < width; ++j)
+#pragma unroll
+                for (int v = 0; v < V; ++v) rsum[v] += R[(int64_t)(row_nbr[j] / K) * Bs + b + v];
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v) red[rg][lane * V + v] = mx[v];
+    __syncthreads();
+    if (!in) return;
+    float shift[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int c = lane * V + v;
+        const float m = fmaxf(fmaxf(red[0][c], red[1][c]), fmaxf(red[2][c], red[3][c]));
+        shift[v] = m > PC_NEG_INF ? rintf(m) : 0.0f;
+    }
+    const int32_t id = ids[r];
+    if (rg == 0)
+#pragma unroll
+        for (int v = 0; v < V; ++v) R[(int64_t)(id / K) * Bs + b + v] = rsum[v] + shift[v];
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+        const int k = rg + 4 * i;
+        if (k < K) {
+            float *dst = l + (int64_t)(id + k) * Bs + b;
+            if (V == 4) {
+                *reinterpret_cast<float4 *>(dst) = make_float4(s[i][0] - shift[0], s[i][1 % V] - shift[1 % V],
+                                                               s[i][2 % V] - shift[2 % V], s[i][3 % V] - shift[3 % V]);
+            } else {
+                dst[0] = s[i][0] - shift[0];
+            }
+        }
+    }
+}
+
+// rows = child blocks (sum / input blocks), neighbours = their product parents in this layer
+__global__ __launch_bounds__(256) void k_prod_bwd(float *__restrict__ F, const int32_t *__restrict__ ids,
+                                                  const int32_t *__restrict__ nbr, int32_t n_rows, int32_t width,
+                                                  int32_t K, int64_t Bs)
+{
+    const int64_t b4 = Bs >> 2;
+    const int64_t total = (int64_t)n_rows * K * b4;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = t / b4, c = t - row * b4;
+        const int32_t r = (int32_t)(row / K), k = (int32_t)(row - (int64_t)r * K);
+        float4 *dst = reinterpret_cast<float4 *>(F + (int64_t)(ids[r] + k) * Bs + 4 * c);
+        float4 s = *dst;
+        for (int j = 0; j < width; ++j) {
+            const int32_t pa = nbr[(int64_t)r * width + j];               // padding -> null block, flow 0
+            const float4 v = *reinterpret_cast<const float4 *>(F + (int64_t)(pa + k) * Bs + 4 * c);
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+        *dst = s;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// log_nf = log F - l of the sum nodes of a layer (Alg. 3 / 4) and its per-block column maximum
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_lognf(const float *__restrict__ l, const float *__restrict__ F,
+                                               float *__restrict__ N, float *__restrict__ nfmax,
+                                               const int32_t *__restrict__ blk_ids, int32_t K, int64_t Bs)
+{
+    __shared__ float red[4][64];
+    const int32_t id = blk_ids[blockIdx.x];
+    const int rg = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t b = (int64_t)blockIdx.y * 64 + lane;
+    float mx = PC_NEG_INF;
+    if (b < Bs) {
+        for (int k = rg; k < K; k += 4) {
+            const int64_t at = (int64_t)(id + k) * Bs + b;
+            const float f = F[at], lv = l[at];
+            const float nf = (f > 0.0f && lv > PC_NEG_INF) ? __logf(f) - lv : PC_NEG_INF;
+            N[at] = nf;
+            mx = fmaxf(mx, nf);
+        }
+    }
+    red[rg][lane] = mx;
+    __syncthreads();
+    if (rg == 0 && b < Bs) {
+        mx = fmaxf(fmaxf(red[0][lane], red[1][lane]), fmaxf(red[2][lane], red[3][lane]));
+        nfmax[(int64_t)(id / K) * Bs + b] = mx;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// generic sum-layer kernels (any K, one thread per output, no matrix cores) -- the node x sample
+// parallelisation of Sec. 3, kept for block sizes the MFMA kernels do not cover
+// ------------------------------------------------------------------------------------------
+__device__ inline void lse_push(float &m, float &s, float t)
+{
+    if (t > m) { s = s * __expf(m - t) + 1.0f; m = t; }
+    else s += __expf(t - m);
+}
+
+__global__ __launch_bounds__(256) void k_sum_fwd_generic(const float *__restrict__ theta, float *__restrict__ l,
+                                                         float *__restrict__ R, const int32_t *__restrict__ ids,
+                                                         const int32_t *__restrict__ nbr, const int32_t *__restrict__ par,
+                                                         int32_t n_rows, int32_t width, int32_t K, int64_t Bs)
+{
+    const int64_t total = (int64_t)n_rows * K * Bs;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = t / Bs, b = t - row * Bs;
+        const int32_t r = (int32_t)(row / K), i = (int32_t)(row - (int64_t)r * K);
+        float Rn = PC_NEG_INF;
+        for (int j = 0; j < width; ++j)
+            if (par[(int64_t)r * width + j] != 0) Rn = fmaxf(Rn, R[(int64_t)(nbr[(int64_t)r * width + j] / K) * Bs + b]);
+        float m = PC_NEG_INF, s = 0.0f;
+        for (int j = 0; j < width; ++j) {
+            const int32_t ns = nbr[(int64_t)r * width + j], ps = par[(int64_t)r * width + j];
+            if (ps == 0) continue;
+            const float d = R[(int64_t)(ns / K) * Bs + b] - Rn;
+            for (int jj = 0; jj < K; ++jj) {
+                const float th = theta[(int64_t)ps + (int64_t)i * K + jj];
+                const float v = l[(int64_t)(ns + jj) * Bs + b] + d;
+                if (th > 0.0f && v > PC_NEG_INF) lse_push(m, s, __logf(th) + v);
+            }
+        }
+        l[(int64_t)(ids[r] + i) * Bs + b] = m > PC_NEG_INF ? m + __logf(s) : PC_NEG_INF;
+        if (i == 0) R[(int64_t)(ids[r] / K) * Bs + b] = Rn;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_sum_bwd_child_generic(const float *__restrict__ theta, const float *__restrict__ l,
+                                                               const float *__restrict__ R, const float *__restrict__ N,
+                                                               float *__restrict__ F, const int32_t *__restrict__ ids,
+                                                               const int32_t *__restrict__ nbr, const int32_t *__restrict__ par,
+                                                               int32_t n_rows, int32_t width, int32_t K, int64_t Bs)
+{
+    const int64_t total = (int64_t)n_rows * K * Bs;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = t / Bs, b = t - row * Bs;
+        const int32_t r = (int32_t)(row / K), jj = (int32_t)(row - (int64_t)r * K);
+        const float Rc = R[(int64_t)(ids[r] / K) * Bs + b];
+        float m = PC_NEG_INF, s = 0.0f;
+        for (int j = 0; j < width; ++j) {
+            const int32_t ms = nbr[(int64_t)r * width + j], ps = par[(int64_t)r * width + j];
+            if (ps == 0) continue;
+            const float d = Rc - R[(int64_t)(ms / K) * Bs + b];
+            for (int i = 0; i < K; ++i) {
+                const float th = theta[(int64_t)ps + (int64_t)i * K + jj];
+                const float nf = N[(int64_t)(ms + i) * Bs + b] + d;
+                if (th > 0.0f && nf > PC_NEG_INF) lse_push(m, s, __logf(th) + nf);
+            }
+        }
+        const int64_t at = (int64_t)(ids[r] + jj) * Bs + b;
+        const float lc = l[at];
+        if (m > PC_NEG_INF && lc > PC_NEG_INF) F[at] += __expf(m + __logf(s) + lc);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_sum_bwd_param_generic(const float *__restrict__ theta, const float *__restrict__ l,
+                                                               const float *__restrict__ R, const float *__restrict__ N,
+                                                               float *__restrict__ G, const int32_t *__restrict__ ids,
+                                                               const int32_t *__restrict__ nbr, const int32_t *__restrict__ par,
+                                                               int32_t n_rows, int32_t width, int32_t K, int64_t Bs, int32_t B,
+                                                               int atomic)
+{
+    const int64_t per_row = (int64_t)width * K * K;
+    const int64_t total = (int64_t)n_rows * per_row;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t r = (int32_t)(t / per_row);
+        int64_t rem = t - (int64_t)r * per_row;
+        const int32_t j = (int32_t)(rem / ((int64_t)K * K));
+        rem -= (int64_t)j * K * K;
+        const int32_t i = (int32_t)(rem / K), jj = (int32_t)(rem - (int64_t)i * K);
+        const int32_t ns = nbr[(int64_t)r * width + j], ps = par[(int64_t)r * width + j];
+        if (ps == 0) continue;
+        const float th = theta[(int64_t)ps + (int64_t)i * K + jj];
+        if (!(th > 0.0f)) continue;
+        const float *nrow = N + (int64_t)(ids[r] + i) * Bs;
+        const float *lrow = l + (int64_t)(ns + jj) * Bs;
+        const float *Rs = R + (int64_t)(ids[r] / K) * Bs, *Rc = R + (int64_t)(ns / K) * Bs;
+        float acc = 0.0f;
+        for (int b = 0; b < B; ++b) {
+            const float nf = nrow[b], lc = lrow[b];
+            if (nf > PC_NEG_INF && lc > PC_NEG_INF) acc += __expf(nf + lc + (Rc[b] - Rs[b]));
+        }
+        float *dst = G + (int64_t)ps + (int64_t)i * K + jj;
+        if (atomic) atomicAdd(dst, th * acc); else *dst += th * acc;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// MFMA sum-layer kernels (K % 32 == 0).  Workgroup = 4 waves; a wave owns 32 sample columns.
+// ------------------------------------------------------------------------------------------
+
+// Forward (role of Alg. 1).  Tile = TM = 32*RT sum rows of one sum block x 128 samples.  Loop over the
+// child blocks of the row; each 32-child chunk: theta[TM x 32] staged in LDS (shared by the waves),
+// child log-probs loaded straight into the B-operand layout, shifted by the running per-sample
+// maximum, exponentiated in registers and multiplied on the matrix cores.  The accumulator stays in
+// linear space relative to the running maximum and is rescaled when the maximum grows (same sum as
+// the per-block log-space update of Alg. 1 line 16, one log per output instead of one per block).
+template <int K, int RT>
+__global__ __launch_bounds__(256) void k_sum_fwd_mfma(const float *__restrict__ theta, float *__restrict__ l,
+                                                      float *__restrict__ R, const int32_t *__restrict__ ids,
+                                                      const int32_t *__restrict__ nbr, const int32_t *__restrict__ par,
+                                                      int32_t width, int64_t Bs)
+{
+    constexpr int TM = 32 * RT;
+    constexpr int SUB = K / TM;
+    __shared__ float As[TM][33];
+    const int r = blockIdx.x / SUB, sub = blockIdx.x % SUB;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
+    const int64_t col0 = (int64_t)blockIdx.y * 128 + wave * 32;
+    const bool active = col0 < Bs;
+    const int64_t col = col0 + l32;
+
+    floatx16 acc[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[rt][e] = 0.0f;
+    float m = PC_NEG_INF;
+
+    float Rn = PC_NEG_INF;                                              // R of this sum block = max of its children's
+    if (active) {
+        for (int j = 0; j < width; ++j)
+            if (par[(int64_t)r * width + j] != 0) Rn = fmaxf(Rn, R[(int64_t)(nbr[(int64_t)r * width + j] / K) * Bs + col]);
+        if (sub == 0 && half == 0) R[(int64_t)(ids[r] / K) * Bs + col] = Rn;
+    }
+
+    for (int j = 0; j < width; ++j) {
+        const int32_t ns = nbr[(int64_t)r * width + j], ps = par[(int64_t)r * width + j];
+        if (ps == 0) continue;                                          // pseudo block of probability 0
+        const float d = active ? R[(int64_t)(ns / K) * Bs + col] - Rn : 0.0f;   // exact integer <= 0
+        for (int kc = 0; kc < K / 32; ++kc) {
+            __syncthreads();
+            for (int t = threadIdx.x; t < TM * 8; t += 256) {
+                const int row = t >> 3, c4 = t & 7;
+                const float4 v = *reinterpret_cast<const float4 *>(theta + (int64_t)ps + (int64_t)(sub * TM + row) * K + kc * 32 + c4 * 4);
+                As[row][c4 * 4 + 0] = v.x; As[row][c4 * 4 + 1] = v.y; As[row][c4 * 4 + 2] = v.z; As[row][c4 * 4 + 3] = v.w;
+            }
+            float v[16];
+            float cmax = PC_NEG_INF;
+            if (active) {
+                const float *src = l + (int64_t)(ns + kc * 32 + half) * Bs + col;
+#pragma unroll
+                for (int q = 0; q < 16; ++q) { v[q] = src[(int64_t)(2 * q) * Bs] + d; cmax = fmaxf(cmax, v[q]); }
+                cmax = fmaxf(cmax, __shfl_xor(cmax, 32));
+            }
+            __syncthreads();
+            if (active) {                                                // wave-uniform; no lane-dependent branch around MFMA
+                const float m_new = fmaxf(m, cmax);
+                const bool dead = !(m_new > PC_NEG_INF);                 // every term of this column so far is 0
+                const float scale = dead ? 1.0f : __expf(m - m_new);     // m = -inf -> 0, acc is 0 anyway
+                m = m_new;
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[rt][e] *= scale;
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const float p = dead ? 0.0f : __expf(v[q] - m_new);  // -inf -> 0
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt)
+                        acc[rt] = __builtin_amdgcn_mfma_f32_32x32x2f32(As[rt * 32 + l32][2 * q + half], p, acc[rt], 0, 0, 0);
+                }
+            }
+        }
+    }
+    if (active) {
+        const int64_t base = (int64_t)(ids[r] + sub * TM);
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int i = rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                const float a = acc[rt][e];
+                l[(base + i) * Bs + col] = a > 0.0f ? m + __logf(a) : PC_NEG_INF;
+            }
+    }
+}
+
+// Backward to the children (role of Alg. 4).  Rows = TM child (product) nodes of one child block,
+// loop over its parent sum blocks; B operand = exp(log_nf - running max), A operand = theta^T.
+// The per-parent-block maximum of log_nf comes precomputed (nfmax).  F_child += exp(log acc + max + l_child).
+template <int K, int RT>
+__global__ __launch_bounds__(256) void k_sum_bwd_child_mfma(const float *__restrict__ theta, const float *__restrict__ l,
+                                                            const float *__restrict__ R,
+                                                            const float *__restrict__ N, const float *__restrict__ nfmax,
+                                                            float *__restrict__ F, const int32_t *__restrict__ ids,
+                                                            const int32_t *__restrict__ nbr, const int32_t *__restrict__ par,
+                                                            int32_t width, int64_t Bs)
+{
+    constexpr int TM = 32 * RT;
+    constexpr int SUB = K / TM;
+    __shared__ float As[32][TM];                                        // [parent row s][child row c]
+    const int r = blockIdx.x / SUB, sub = blockIdx.x % SUB;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
+    const int64_t col0 = (int64_t)blockIdx.y * 128 + wave * 32;
+    const bool active = col0 < Bs;
+    const int64_t col = col0 + l32;
+
+    floatx16 acc[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[rt][e] = 0.0f;
+    float m = PC_NEG_INF;
+    const float Rc = active ? R[(int64_t)(ids[r] / K) * Bs + col] : 0.0f;
+
+    for (int j = 0; j < width; ++j) {
+        const int32_t ms = nbr[(int64_t)r * width + j], ps = par[(int64_t)r * width + j];
+        if (ps == 0) continue;
+        float d = 0.0f;                                                 // R_child - R_parent: exact integer <= 0
+        if (active) {
+            d = Rc - R[(int64_t)(ms / K) * Bs + col];
+            const float m_new = fmaxf(m, nfmax[(int64_t)(ms / K) * Bs + col] + d);
+            const float scale = m_new > PC_NEG_INF ? __expf(m - m_new) : 1.0f;
+            m = m_new;
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[rt][e] *= scale;
+        }
+        const bool dead = !(m > PC_NEG_INF);                             // per lane: nothing flows into this column yet
+        for (int kc = 0; kc < K / 32; ++kc) {
+            __syncthreads();
+            for (int t = threadIdx.x; t < 32 * (TM / 4); t += 256) {
+                const int s = t / (TM / 4), c4 = t % (TM / 4);
+                const float4 v = *reinterpret_cast<const float4 *>(theta + (int64_t)ps + (int64_t)(kc * 32 + s) * K + sub * TM + c4 * 4);
+                *reinterpret_cast<float4 *>(&As[s][c4 * 4]) = v;
+            }
+            float v[16];
+            if (active) {
+                const float *src = N + (int64_t)(ms + kc * 32 + half) * Bs + col;
+#pragma unroll
+                for (int q = 0; q < 16; ++q) v[q] = src[(int64_t)(2 * q) * Bs];
+            }
+            __syncthreads();
+            if (active) {                                                // wave-uniform
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const float p = dead ? 0.0f : __expf(v[q] + d - m);
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt)
+                        acc[rt] = __builtin_amdgcn_mfma_f32_32x32x2f32(As[2 * q + half][rt * 32 + l32], p, acc[rt], 0, 0, 0);
+                }
+            }
+        }
+    }
+    if (active && m > PC_NEG_INF) {
+        const int64_t base = (int64_t)(ids[r] + sub * TM);
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int i = rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                const float a = acc[rt][e];
+                const int64_t at = (base + i) * Bs + col;
+                const float lc = l[at];
+                if (a > 0.0f && lc > PC_NEG_INF) F[at] += __expf(__logf(a) + m + lc);
+            }
+    }
+}
+
+// Backward to the parameters (role of Alg. 3).  Output tile = TM sum rows x (4 waves x 32) child
+// columns of the row's flattened child list; reduction over the batch in chunks of 32 samples on the
+// matrix cores.  Each term exp(log_nf_s + l_c) is split into two fp32 factors around a per-sample
+// shift (any shift is valid: it only moves scale between the factors).  With a = max_s log_nf_s of
+// the sum block, the factors are exp(log_nf_s - a + 43) <= e^43 and exp(l_c + a - 43) <= e^44.3
+// (theta p_c / p_s <= 1 and theta >= FLT_MIN bound l_c + a by 87.3), so neither overflows and a
+// product is lost to underflow only when it is below e^-40.  Alg. 3 shifts by a alone, which can
+// drop products of order one when a weight is as small as FLT_MIN.
+#define PC_SPLIT 43.0f
+#define PC_SPLIT_CAP 44.5f
+template <int K, int RT>
+__global__ __launch_bounds__(256) void k_sum_bwd_param_mfma(const float *__restrict__ theta, const float *__restrict__ l,
+                                                            const float *__restrict__ R,
+                                                            const float *__restrict__ N, const float *__restrict__ nfmax,
+                                                            float *__restrict__ G, const int32_t *__restrict__ ids,
+                                                            const int32_t *__restrict__ nbr, const int32_t *__restrict__ par,
+                                                            int32_t width, int64_t Bs, int atomic)
+{
+    constexpr int TM = 32 * RT;
+    constexpr int SUB = K / TM;
+    __shared__ float Qs[TM][33];
+    __shared__ float Ps[4][32][33];
+    const int r = blockIdx.x / SUB, sub = blockIdx.x % SUB;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
+    const int64_t cidx = (int64_t)blockIdx.y * 128 + wave * 32;         // column in the flattened child list
+    const int j = (int)(cidx / K), c0 = (int)(cidx % K);
+    int32_t ns = 0, ps = 0;
+    if (j < width) { ns = nbr[(int64_t)r * width + j]; ps = par[(int64_t)r * width + j]; }
+    const bool valid = ps != 0;
+    const int32_t ms = ids[r];
+    const float *mxrow = nfmax + (int64_t)(ms / K) * Bs;
+    const float *Rs = R + (int64_t)(ms / K) * Bs, *Rc = R + (int64_t)(ns / K) * Bs;
+
+    floatx16 acc[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[rt][e] = 0.0f;
+
+    for (int64_t b0 = 0; b0 < Bs; b0 += 32) {
+        __syncthreads();
+        for (int t = threadIdx.x; t < TM * 8; t += 256) {
+            const int row = t >> 3, c4 = t & 7;
+            const float4 nf = *reinterpret_cast<const float4 *>(N + (int64_t)(ms + sub * TM + row) * Bs + b0 + c4 * 4);
+            const float4 mx = *reinterpret_cast<const float4 *>(mxrow + b0 + c4 * 4);
+            Qs[row][c4 * 4 + 0] = mx.x > PC_NEG_INF ? __expf(nf.x - mx.x + PC_SPLIT) : 0.0f;
+            Qs[row][c4 * 4 + 1] = mx.y > PC_NEG_INF ? __expf(nf.y - mx.y + PC_SPLIT) : 0.0f;
+            Qs[row][c4 * 4 + 2] = mx.z > PC_NEG_INF ? __expf(nf.z - mx.z + PC_SPLIT) : 0.0f;
+            Qs[row][c4 * 4 + 3] = mx.w > PC_NEG_INF ? __expf(nf.w - mx.w + PC_SPLIT) : 0.0f;
+        }
+        if (valid) {
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const int row = it * 8 + (lane >> 3), c4 = lane & 7;
+                const float4 lc = *reinterpret_cast<const float4 *>(l + (int64_t)(ns + c0 + row) * Bs + b0 + c4 * 4);
+                float4 mx = *reinterpret_cast<const float4 *>(mxrow + b0 + c4 * 4);
+                const float4 rs = *reinterpret_cast<const float4 *>(Rs + b0 + c4 * 4);
+                const float4 rc = *reinterpret_cast<const float4 *>(Rc + b0 + c4 * 4);
+                mx.x += rc.x - rs.x; mx.y += rc.y - rs.y; mx.z += rc.z - rs.z; mx.w += rc.w - rs.w;
+                Ps[wave][row][c4 * 4 + 0] = mx.x > PC_NEG_INF ? __expf(fminf(lc.x + mx.x - PC_SPLIT, PC_SPLIT_CAP)) : 0.0f;
+                Ps[wave][row][c4 * 4 + 1] = mx.y > PC_NEG_INF ? __expf(fminf(lc.y + mx.y - PC_SPLIT, PC_SPLIT_CAP)) : 0.0f;
+                Ps[wave][row][c4 * 4 + 2] = mx.z > PC_NEG_INF ? __expf(fminf(lc.z + mx.z - PC_SPLIT, PC_SPLIT_CAP)) : 0.0f;
+                Ps[wave][row][c4 * 4 + 3] = mx.w > PC_NEG_INF ? __expf(fminf(lc.w + mx.w - PC_SPLIT, PC_SPLIT_CAP)) : 0.0f;
+            }
+        }
+        __syncthreads();
+        if (valid) {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const float p = Ps[wave][l32][2 * q + half];
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+                    acc[rt] = __builtin_amdgcn_mfma_f32_32x32x2f32(Qs[rt * 32 + l32][2 * q + half], p, acc[rt], 0, 0, 0);
+            }
+        }
+    }
+    if (valid) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int i = sub * TM + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                const int64_t at = (int64_t)ps + (int64_t)i * K + c0 + l32;
+                const float g = theta[at] * acc[rt][e];
+                if (atomic) { if (g != 0.0f) atomicAdd(G + at, g); }
+                else G[at] += g;
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// EM update
+// ------------------------------------------------------------------------------------------
+// zrow[g*K + i] += sum of real columns of row i of parameter block pb (g = its normalisation group)
+__global__ __launch_bounds__(256) void k_em_rowsum(const float *__restrict__ G, const int32_t *__restrict__ pb_group,
+                                                   const int32_t *__restrict__ pb_rows, const int32_t *__restrict__ pb_cols,
+                                                   int32_t K, float *__restrict__ zrow)
+{
+    const int pb = blockIdx.x + 1;
+    const int g = pb_group[pb];
+    if (g < 0) return;
+    const int rows = pb_rows[pb], cols = pb_cols[pb];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int i = wave; i < rows; i += 4) {
+        float s = 0.0f;
+        for (int jj = lane; jj < cols; jj += 64) s += G[(int64_t)pb * K * K + (int64_t)i * K + jj];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+        if (lane == 0) atomicAdd(zrow + (int64_t)g * K + i, s);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_em_theta(float *__restrict__ theta, float *__restrict__ G,
+                                                  const int32_t *__restrict__ pb_group, const int32_t *__restrict__ pb_rows,
+                                                  const int32_t *__restrict__ pb_cols, const int32_t *__restrict__ group_nch,
+                                                  const float *__restrict__ zrow, int32_t K, float step, float pc)
+{
+    const int pb = blockIdx.x + 1;
+    const int g = pb_group[pb];
+    const int64_t base = (int64_t)pb * K * K;
+    if (g >= 0) {
+        const int rows = pb_rows[pb], cols = pb_cols[pb];
+        const float share = pc / (float)group_nch[g];
+        for (int t = threadIdx.x; t < K * K; t += 256) {
+            const int i = t / K, jj = t - i * K;
+            if (i < rows && jj < cols) {
+                const float z = zrow[(int64_t)g * K + i] + pc;
+                if (z > 0.0f) {
+                    const float nw = (G[base + t] + share) / z;
+                    theta[base + t] = (1.0f - step) * theta[base + t] + step * nw;
+                }
+            }
+        }
+    }
+    for (int t = threadIdx.x; t < K * K; t += 256) G[base + t] = 0.0f;
+}
+
+// ztab[t*K + k] += sum over a slab of categories of table_flow[t][c][k]
+__global__ __launch_bounds__(256) void k_em_tabsum(const float *__restrict__ Gt, int32_t K, int32_t n_cats,
+                                                   int32_t cats_per_block, float *__restrict__ ztab)
+{
+    const int t = blockIdx.x;
+    const int c0 = blockIdx.y * cats_per_block;
+    const int c1 = min(n_cats, c0 + cats_per_block);
+    for (int k = threadIdx.x; k < K; k += 256) {
+        float s = 0.0f;
+        for (int c = c0; c < c1; ++c) s += Gt[((int64_t)t * n_cats + c) * K + k];
+        atomicAdd(ztab + (int64_t)t * K + k, s);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_em_tables(float *__restrict__ tables, float *__restrict__ Gt,
+                                                   const float *__restrict__ ztab, int32_t K, int32_t n_cats,
+                                                   int64_t total, float step, float pc)
+{
+    const float share = pc / (float)n_cats;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t tc = i / K;
+        const int k = (int)(i - tc * K);
+        const int64_t t = tc / n_cats;
+        const float z = ztab[t * K + k] + pc;
+        if (z > 0.0f) {
+            const float nw = (Gt[i] + share) / z;
+            tables[i] = (1.0f - step) * tables[i] + step * nw;
+        }
+        Gt[i] = 0.0f;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// launchers
+// ------------------------------------------------------------------------------------------
+static inline int grid_for(int64_t items, int per_block = 256, int cap = 1 << 16)
+{
+    int64_t g = (items + per_block - 1) / per_block;
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return (int)g;
+}
+
+static bool g_force_generic = false;
+void set_force_generic(bool on) { g_force_generic = on; }
+static inline bool use_mfma(int32_t K) { return !g_force_generic && (K == 32 || K == 64 || K == 128); }
+
+// rows-per-tile: the largest tile that still gives the chip about two workgroups per compute unit
+static int pick_rt(int32_t K, int64_t tiles32, int64_t col_tiles)
+{
+    int rt = K / 32;
+    if (rt > 4) rt = 4;
+    while (rt > 1 && (tiles32 / rt) * col_tiles < 512) rt >>= 1;
+    return rt;
+}
+
+void launch_fill(float *p, int64_t n, float v, hipStream_t s)
+{
+    if (n <= 0) return;
+    hipLaunchKernelGGL(k_fill, dim3(grid_for(n, 256, 4096)), dim3(256), 0, s, p, n, v);
+}
+
+void launch_prepare_x(const int32_t *x, const uint8_t *mask, int32_t B, int32_t D, int64_t Bs, int32_t n_cats,
+                      int32_t *xT, hipStream_t s)
+{
+    dim3 grid((unsigned)((Bs + 31) / 32), (unsigned)((D + 31) / 32));
+    hipLaunchKernelGGL(k_prepare_x, grid, dim3(256), 0, s, x, mask, B, D, Bs, n_cats, xT);
+}
+
+void launch_readout(const float *l, const float *R, int64_t root_row, int64_t root_blk, int64_t Bs, int32_t B, float *ll,
+                    hipStream_t s)
+{
+    hipLaunchKernelGGL(k_readout, dim3((B + 255) / 256), dim3(256), 0, s, l, R, root_row, root_blk, Bs, B, ll);
+}
+
+void launch_root_flow(const float *l, float *F, int64_t root_row, int64_t Bs, int32_t B, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_root_flow, dim3((unsigned)((Bs + 255) / 256)), dim3(256), 0, s, l, F, root_row, Bs, B);
+}
+
+void launch_input_fwd(const float *tables, const int32_t *xT, const GroupDev &g, int32_t K, int32_t n_cats, int64_t Bs,
+                      float *l, hipStream_t s)
+{
+    if (g.n_rows == 0) return;
+    dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 255) / 256));
+    hipLaunchKernelGGL(k_input_fwd, grid, dim3(256), 0, s, tables, xT, g.ids, g.nbr, g.par, K, n_cats, Bs, l);
+}
+
+void launch_input_bwd(const float *F, const int32_t *xT, const GroupDev &g, int32_t K, int32_t n_cats, int64_t Bs,
+                      float *table_flow, hipStream_t s)
+{
+    if (g.n_rows == 0) return;
+    dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 255) / 256));
+    hipLaunchKernelGGL(k_input_bwd, grid, dim3(256), 0, s, F, xT, g.ids, g.nbr, g.par, K, n_cats, Bs, table_flow);
+}
+
+void launch_prod_fwd(float *l, float *R, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
+{
+    if (g.n_rows == 0) return;
+    if (Bs >= 256) {
+        dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 255) / 256));
+        hipLaunchKernelGGL(k_prod_fwd<4>, grid, dim3(256), 0, s, l, R, g.ids, g.nbr, g.width, K, Bs);
+    } else {
+        dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 63) / 64));
+        hipLaunchKernelGGL(k_prod_fwd<1>, grid, dim3(256), 0, s, l, R, g.ids, g.nbr, g.width, K, Bs);
+    }
+}
+
+void launch_prod_bwd(float *F, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
+{
+    const int64_t items = (int64_t)g.n_rows * K * (Bs / 4);
+    hipLaunchKernelGGL(k_prod_bwd, dim3(grid_for(items)), dim3(256), 0, s, F, g.ids, g.nbr, g.n_rows, g.width, K, Bs);
+}
+
+void launch_lognf(const float *l, const float *F, float *N, float *nfmax, const int32_t *blk_ids, int32_t n_blk,
+                  int32_t K, int64_t Bs, hipStream_t s)
+{
+    if (n_blk == 0) return;
+    dim3 grid((unsigned)n_blk, (unsigned)((Bs + 63) / 64));
+    hipLaunchKernelGGL(k_lognf, grid, dim3(256), 0, s, l, F, N, nfmax, blk_ids, K, Bs);
+}
+
+#define PC_DISPATCH_K_RT(KERNEL, K, RT, ...)                                                              \
+    do {                                                                                                  \
+        if (K == 32) hipLaunchKernelGGL((KERNEL<32, 1>), __VA_ARGS__);                                    \
+        else if (K == 64 && RT == 1) hipLaunchKernelGGL((KERNEL<64, 1>), __VA_ARGS__);                    \
+        else if (K == 64) hipLaunchKernelGGL((KERNEL<64, 2>), __VA_ARGS__);                               \
+        else if (K == 128 && RT == 1) hipLaunchKernelGGL((KERNEL<128, 1>), __VA_ARGS__);                  \
+        else if (K == 128 && RT == 2) hipLaunchKernelGGL((KERNEL<128, 2>), __VA_ARGS__);                  \
+        else hipLaunchKernelGGL((KERNEL<128, 4>), __VA_ARGS__);                                           \
+    } while (0)
+
+void launch_sum_fwd(const float *theta, float *l, float *R, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
+{
+    if (g.n_rows == 0) return;
+    if (use_mfma(K)) {
+        const int64_t col_tiles = (Bs + 127) / 128;
+        const int rt = pick_rt(K, (int64_t)g.n_rows * (K / 32), col_tiles);
+        dim3 grid((unsigned)(g.n_rows * (K / (32 * rt))), (unsigned)col_tiles);
+        PC_DISPATCH_K_RT(k_sum_fwd_mfma, K, rt, grid, dim3(256), 0, s, theta, l, R, g.ids, g.nbr, g.par, g.width, Bs);
+    } else {
+        const int64_t items = (int64_t)g.n_rows * K * Bs;
+        hipLaunchKernelGGL(k_sum_fwd_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, l, R, g.ids, g.nbr, g.par,
+                           g.n_rows, g.width, K, Bs);
+    }
+}
+
+void launch_sum_bwd_child(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *F,
+                          const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
+{
+    if (g.n_rows == 0) return;
+    if (use_mfma(K)) {
+        const int64_t col_tiles = (Bs + 127) / 128;
+        const int rt = pick_rt(K, (int64_t)g.n_rows * (K / 32), col_tiles);
+        dim3 grid((unsigned)(g.n_rows * (K / (32 * rt))), (unsigned)col_tiles);
+        PC_DISPATCH_K_RT(k_sum_bwd_child_mfma, K, rt, grid, dim3(256), 0, s, theta, l, R, N, nfmax, F, g.ids, g.nbr, g.par,
+                         g.width, Bs);
+    } else {
+        const int64_t items = (int64_t)g.n_rows * K * Bs;
+        hipLaunchKernelGGL(k_sum_bwd_child_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, l, R, N, F, g.ids, g.nbr,
+                           g.par, g.n_rows, g.width, K, Bs);
+    }
+}
+
+void launch_sum_bwd_param(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *G,
+                          const GroupDev &g, int32_t K, int64_t Bs, int32_t B, hipStream_t s)
+{
+    if (g.n_rows == 0) return;
+    const int atomic = g.tied ? 1 : 0;
+    if (use_mfma(K)) {
+        const int64_t col_tiles = ((int64_t)g.width * K + 127) / 128;
+        const int rt = pick_rt(K, (int64_t)g.n_rows * (K / 32), col_tiles);
+        dim3 grid((unsigned)(g.n_rows * (K / (32 * rt))), (unsigned)col_tiles);
+        PC_DISPATCH_K_RT(k_sum_bwd_param_mfma, K, rt, grid, dim3(256), 0, s, theta, l, R, N, nfmax, G, g.ids, g.nbr, g.par,
+                         g.width, Bs, atomic);
+    } else {
+        const int64_t items = (int64_t)g.n_rows * g.width * K * K;
+        hipLaunchKernelGGL(k_sum_bwd_param_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, l, R, N, G, g.ids, g.nbr,
+                           g.par, g.n_rows, g.width, K, Bs, B, atomic);
+    }
+}
+
+void launch_em(float *theta, float *tables, float *theta_flow, float *table_flow, const EmDev &em, int32_t K,
+               int32_t n_param_blocks, int32_t n_tables, int32_t n_cats, float step, float pc, hipStream_t s)
+{
+    launch_fill(em.zrow, (int64_t)em.n_groups * K, 0.0f, s);
+    launch_fill(em.ztab, (int64_t)n_tables * K, 0.0f, s);
+    if (n_param_blocks > 0) {
+        hipLaunchKernelGGL(k_em_rowsum, dim3(n_param_blocks), dim3(256), 0, s, theta_flow, em.pb_group, em.pb_rows,
+                           em.pb_cols, K, em.zrow);
+        hipLaunchKernelGGL(k_em_theta, dim3(n_param_blocks), dim3(256), 0, s, theta, theta_flow, em.pb_group, em.pb_rows,
+                           em.pb_cols, em.group_nch, em.zrow, K, step, pc);
+    }
+    const int cats_per_block = 64;
+    dim3 grid((unsigned)n_tables, (unsigned)((n_cats + cats_per_block - 1) / cats_per_block));
+    hipLaunchKernelGGL(k_em_tabsum, grid, dim3(256), 0, s, table_flow, K, n_cats, cats_per_block, em.ztab);
+    const int64_t total = (int64_t)n_tables * n_cats * K;
+    hipLaunchKernelGGL(k_em_tables, dim3(grid_for(total)), dim3(256), 0, s, tables, table_flow, em.ztab, K, n_cats, total,
+                       step, pc);
+}
+
+}  // namespace pc

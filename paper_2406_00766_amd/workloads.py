@@ -156,7 +156,7 @@ def _make(name, bld: _Builder, root, n_param_blocks, n_vars, n_cats, n_tables, t
 # HMM written as a circuit (footnote to Sec. 1; parameter tying across time, App. A.3)
 # --------------------------------------------------------------------------------------------
 def hmm(T: int, H: int, V: int, K: int, B: int, seed: int, *, alpha_init=1.0, alpha_trans=1.0,
-        alpha_emis=1.0, tokens="uniform", keep_dense=True, name=None) -> Workload:
+        alpha_emis=1.0, tokens="uniform", keep_dense=True, draw=True, name=None) -> Workload:
     """Hidden z_0..z_{T-1}, tokens x_0..x_{T-1}.
 
     E_t[h]  input node on variable t with P(x_t = v | z_t = h), tied over t
@@ -187,6 +187,9 @@ def hmm(T: int, H: int, V: int, K: int, B: int, seed: int, *, alpha_init=1.0, al
     n_param_blocks = n_A + nb
 
     theta = np.zeros((n_param_blocks + 1, K, K), dtype=np.float32)
+    if not draw:                                   # structure only: parameters and data left at zero
+        return _make(name or f"hmm_T{T}_H{H}_V{V}_K{K}_B{B}", bld, root, n_param_blocks, T, V, nb, theta,
+                     np.zeros((nb, V, K), dtype=np.float32), np.zeros((B, T), dtype=np.int32), {"kind": "hmm", "T": T, "H": H, "V": V})
     pi = _f32_floor(_dirichlet_rows(rng, alpha_init, (1, H)))[0]
     A = None
     if T > 1:
@@ -271,7 +274,7 @@ def random_tree(rng: np.random.Generator, D: int):
     return parent, order
 
 
-def hclt(D: int, M: int, K: int, B: int, seed: int, *, n_cats=256, data="gauss", name=None) -> Workload:
+def hclt(D: int, M: int, K: int, B: int, seed: int, *, n_cats=256, data="gauss", draw=True, name=None) -> Workload:
     """Latent tree: each variable v has a latent z_v with M states.
 
     E_v[k]  input node on variable v, own table per variable
@@ -308,6 +311,10 @@ def hclt(D: int, M: int, K: int, B: int, seed: int, *, n_cats=256, data="gauss",
     n_param_blocks = n_W + nb
 
     theta = np.zeros((n_param_blocks + 1, K, K), dtype=np.float32)
+    if not draw:
+        return _make(name or f"hclt_D{D}_M{M}_K{K}_B{B}", bld, root, n_param_blocks, D, n_cats, D * nb, theta,
+                     np.zeros((D * nb, n_cats, K), dtype=np.float32), np.zeros((B, D), dtype=np.int32),
+                     {"kind": "hclt", "D": D, "M": M, "parent": parent, "order": order})
     for c in range(1, D):
         W = _f32_floor(_dirichlet_rows(rng, 1.0, (M, M)))
         base = 1 + (c - 1) * nb * nb
@@ -360,7 +367,7 @@ def hclt_table(w: Workload, v: int) -> np.ndarray:
 # --------------------------------------------------------------------------------------------
 # Poon-Domingos region structure with axis-aligned splits, optional block pruning
 # --------------------------------------------------------------------------------------------
-def pd(grid: int, cell: int, M: int, K: int, B: int, seed: int, *, keep=1.0, n_cats=256, name=None) -> Workload:
+def pd(grid: int, cell: int, M: int, K: int, B: int, seed: int, *, keep=1.0, n_cats=256, draw=True, name=None) -> Workload:
     """grid x grid coarse cells of cell x cell pixels.  Regions = all coarse rectangles.
 
     leaf cell:   L[k] = prod_{pixels} E_pixel[k]; its region's sums range over L
@@ -429,6 +436,10 @@ def pd(grid: int, cell: int, M: int, K: int, B: int, seed: int, *, keep=1.0, n_c
             kept.append((s, ks))
 
     theta = np.zeros((n_param_blocks + 1, K, K), dtype=np.float32)
+    if not draw:
+        return _make(name or f"pd_g{grid}_c{cell}_M{M}_K{K}_keep{keep}_B{B}", bld, root, n_param_blocks, D, n_cats,
+                     D * nb, theta, np.zeros((D * nb, n_cats, K), dtype=np.float32), np.zeros((B, D), dtype=np.int32),
+                     {"kind": "pd", "grid": grid, "cell": cell, "M": M, "keep": keep})
     pos = 1
     for s, ks in kept:
         nk = len(ks)
@@ -454,21 +465,23 @@ def pd(grid: int, cell: int, M: int, K: int, B: int, seed: int, *, keep=1.0, n_c
 DEFAULT_K = {1: 32, 2: 64, 3: 64, 4: 128, 5: 32}
 
 
-def config(idx: int, *, K: int | None = None, B: int | None = None) -> Workload:
-    """Full-size configuration `idx` (1-based).  Seed = SEED_BASE + idx."""
+def config(idx: int, *, K: int | None = None, B: int | None = None, draw: bool = True) -> Workload:
+    """Full-size configuration `idx` (1-based).  Seed = SEED_BASE + idx.
+    draw=False builds the structure only (parameters and data all zero)."""
     K = K or DEFAULT_K[idx]
     seed = SEED_BASE + idx
     if idx == 1:
-        return hmm(16, 32, 64, K, B or 128, seed, name=f"cfg1_hmm_T16_H32_V64_B{B or 128}")
+        return hmm(16, 32, 64, K, B or 128, seed, draw=draw, name=f"cfg1_hmm_T16_H32_V64_B{B or 128}")
     if idx == 2:
-        return hclt(784, 128, K, B or 512, seed, data="gauss", name=f"cfg2_hclt_D784_M128_B{B or 512}")
+        return hclt(784, 128, K, B or 512, seed, data="gauss", draw=draw, name=f"cfg2_hclt_D784_M128_B{B or 512}")
     if idx == 3:
-        return hclt(3072, 256, K, B or 256, seed, data="gauss_corr", name=f"cfg3_hclt_D3072_M256_B{B or 256}")
+        return hclt(3072, 256, K, B or 256, seed, data="gauss_corr", draw=draw,
+                    name=f"cfg3_hclt_D3072_M256_B{B or 256}")
     if idx == 4:
         return hmm(32, 4096, 50257, K, B or 256, seed, alpha_trans=0.1, alpha_emis=0.1, tokens="zipf",
-                   keep_dense=False, name=f"cfg4_hmm_T32_H4096_V50257_B{B or 256}")
+                   keep_dense=False, draw=draw, name=f"cfg4_hmm_T32_H4096_V50257_B{B or 256}")
     if idx == 5:
-        return pd(8, 4, 256, K, B or 256, seed, keep=0.25, name=f"cfg5_pd_32x32_M256_keep25_B{B or 256}")
+        return pd(8, 4, 256, K, B or 256, seed, keep=0.25, draw=draw, name=f"cfg5_pd_32x32_M256_keep25_B{B or 256}")
     raise ValueError(idx)
 
 

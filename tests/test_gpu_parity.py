@@ -1,0 +1,232 @@
+"""GPU parity: the HIP path (through the C ABI) against the float64 oracle, element by element.
+
+Tolerances (from the build's target): log-likelihoods and node log-probabilities within 1e-4 relative;
+node and parameter flows within 1e-3 relative, plus an absolute floor of 1e-6 of the largest flow in the
+array (fp32 cannot represent flows below ~1e-38 and atomics reorder sums); compiled tables bit-exact.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import compile_oracle as co
+from oracle import pc_oracle as orc
+from paper_2406_00766_amd import binding as pcb
+from paper_2406_00766_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+LL_RTOL = 1e-4
+FLOW_RTOL = 1e-3
+FLOW_ATOL_FRAC = 1e-6
+
+
+def to_user_rows(buf, K, B):
+    """[n_rows, stride] device buffer (compiled node offsets) -> float64 [B, n_blocks*K] (user numbering)."""
+    return buf[K:, :B].double().cpu().numpy().T.copy()
+
+
+def gpu_run(w, mask=None, backward=True):
+    c = pcb.Circuit(w)
+    c.set_batch(w.x, mask)
+    ll = c.forward().double().cpu().numpy()
+    out = {"ll": ll}
+    if backward:
+        c.backward()
+    torch.cuda.synchronize()
+    l, F, R = c.node_buffers()
+    K, B = w.K, w.B
+    lp = l[:, :B].double() + R[:, :B].double().repeat_interleave(K, dim=0)
+    out["lp"] = lp[K:].cpu().numpy().T.copy()
+    if backward:
+        out["flow"] = to_user_rows(F, K, B)
+        out["theta_flow"] = c.theta_flow.double().cpu().numpy().reshape(w.theta.shape)
+        out["table_flow"] = c.table_flow.double().cpu().numpy().reshape(w.tables.shape)
+    out["circuit"] = c
+    return out
+
+
+def assert_logprob_close(got, ref, what):
+    inf = np.isneginf(ref)
+    assert np.array_equal(np.isneginf(got), inf), f"{what}: -inf pattern differs"
+    assert not np.isnan(got).any(), f"{what}: NaN"
+    g, r = got[~inf], ref[~inf]
+    err = np.abs(g - r)
+    bound = LL_RTOL * np.abs(r) + 1e-5
+    assert np.all(err <= bound), f"{what}: max err {err.max():.3e} (worst excess {np.max(err - bound):.3e})"
+
+
+def assert_flow_close(got, ref, what):
+    assert not np.isnan(got).any() and np.all(np.isfinite(got)), f"{what}: non-finite"
+    atol = FLOW_ATOL_FRAC * max(np.abs(ref).max(), 1e-30)
+    err = np.abs(got - ref)
+    bound = FLOW_RTOL * np.abs(ref) + atol
+    bad = err > bound
+    assert not bad.any(), (f"{what}: {bad.sum()} of {bad.size} off; worst rel "
+                           f"{np.max(err[bad] / np.maximum(np.abs(ref[bad]), 1e-300)):.3e} at ref {ref[bad][np.argmax(err[bad])]:.3e}")
+
+
+def oracle_run(w, mask=None):
+    ll, lp, flow, tf, gf = orc.backward(w, w.theta, w.tables, w.x, mask)
+    return {"ll": ll, "lp": lp, "flow": flow, "theta_flow": tf, "table_flow": gf}
+
+
+def check_all(w, mask=None):
+    ref = oracle_run(w, mask)
+    got = gpu_run(w, mask)
+    assert_logprob_close(got["ll"], ref["ll"], "ll")
+    assert_logprob_close(got["lp"], ref["lp"], "node log-probs")
+    assert_flow_close(got["flow"], ref["flow"], "node flows")
+    assert_flow_close(got["theta_flow"], ref["theta_flow"], "theta flows")
+    assert_flow_close(got["table_flow"], ref["table_flow"], "table flows")
+    return got, ref
+
+
+def assert_device_tables_match_oracle(handle, w):
+    ref = co.compile_tables(w)
+    got = pcb.compiled_tables(handle)
+    assert len(got) == len(ref["layers"])
+    for a, b in zip(got, ref["layers"]):
+        assert (a["kind"], a["depth"]) == (b["kind"], b["depth"])
+        for key in ("fwd", "bwd"):
+            assert len(a[key]) == len(b[key])
+            for ga, gb in zip(a[key], b[key]):
+                for xa, xb in zip(ga, gb):
+                    assert np.array_equal(xa, np.asarray(xb).reshape(xa.shape))
+
+
+# ------------------------------------------------------------------------------------------------
+REDUCED = [(i, None) for i in range(1, 6)] + [(1, 16), (2, 64), (3, 32), (3, 128), (4, 32), (4, 128)]
+
+
+@pytest.mark.parametrize("idx,K", REDUCED)
+def test_reduced_configs_match_oracle(idx, K):
+    w = W.reduced(idx, K=K)
+    print(f"case reduced({idx}, K={K}) {w.name}", flush=True)
+    got, _ = check_all(w)
+    assert_device_tables_match_oracle(got["circuit"].handle, w)
+
+
+@pytest.mark.parametrize("make", [
+    lambda: W.hmm(4, 6, 5, 3, 7, 7),                       # K = 3: generic kernels
+    lambda: W.hmm(5, 8, 9, 1, 33, 8),                      # K = 1
+    lambda: W.hclt(7, 10, 5, 40, 9, n_cats=6),             # K = 5
+    lambda: W.pd(3, 1, 8, 4, 19, 10, n_cats=3, keep=0.5),  # K = 4, block-sparse
+    lambda: W.pd(2, 2, 24, 8, 65, 11, n_cats=4),           # K = 8
+])
+def test_small_block_sizes_use_generic_kernels(make):
+    w = make()
+    print(f"case generic {w.name}", flush=True)
+    check_all(w)
+
+
+def test_config1_full_size():
+    w = W.config(1)
+    print("case cfg1 full", flush=True)
+    got, _ = check_all(w)
+    assert_device_tables_match_oracle(got["circuit"].handle, w)
+
+
+@pytest.mark.parametrize("B", [1, 31, 32, 33, 129, 300])
+def test_ragged_batches(B):
+    w = W.reduced(2, B=B)
+    print(f"case ragged B={B}", flush=True)
+    check_all(w)
+
+
+def test_marginalised_variables_and_zero_probability_samples():
+    w = W.reduced(2, B=50)
+    rng = np.random.default_rng(1)
+    mask = (rng.random(w.x.shape) < 0.3).astype(np.uint8)
+    mask[0, :] = 1                                          # fully marginalised sample: ll = 0
+    print("case mask", flush=True)
+    got, ref = check_all(w, mask)
+    assert abs(got["ll"][0]) < 1e-4
+    # zero-probability samples: category 0 made impossible in every table
+    w2 = W.reduced(1, B=40)
+    w2.tables = w2.tables.copy(); w2.tables[:, 0, :] = 0.0
+    x = np.where(w2.x == 0, 1, w2.x); x[3, 2] = 0; x[17, 0] = 0
+    w2 = w2.with_batch(x)
+    print("case zero-prob", flush=True)
+    got, ref = check_all(w2)
+    assert np.isneginf(got["ll"][3]) and np.isneginf(got["ll"][17]) and np.isfinite(got["ll"][4])
+    assert np.all(got["flow"][3] == 0.0)
+
+
+def test_flows_accumulate_over_calls_and_em_step_matches_oracle():
+    w = W.reduced(3, B=64)
+    c = pcb.Circuit(w)
+    ref_tf = ref_gf = None
+    for part in (slice(0, 40), slice(40, 64)):
+        wb = w.with_batch(w.x[part])
+        c.set_batch(wb.x)
+        c.forward(); c.backward()
+        _, _, _, ref_tf, ref_gf = orc.backward(wb, w.theta, w.tables, wb.x, None, ref_tf, ref_gf)
+    torch.cuda.synchronize()
+    assert_flow_close(c.theta_flow.double().cpu().numpy().reshape(w.theta.shape), ref_tf, "accumulated theta flows")
+    assert_flow_close(c.table_flow.double().cpu().numpy().reshape(w.tables.shape), ref_gf, "accumulated table flows")
+    for step, pc in ((1.0, 0.0), (0.3, 0.1)):
+        th0 = c.theta.cpu().numpy().reshape(w.theta.shape).copy()
+        tb0 = c.tables.cpu().numpy().reshape(w.tables.shape).copy()
+        tf = c.theta_flow.double().cpu().numpy().reshape(w.theta.shape)
+        gf = c.table_flow.double().cpu().numpy().reshape(w.tables.shape)
+        ref_th, ref_tb = orc.em_step(w, th0, tb0, tf, gf, step=step, pseudocount=pc)
+        c.em_step(step, pc)
+        torch.cuda.synchronize()
+        th = c.theta.cpu().numpy().reshape(w.theta.shape)
+        tb = c.tables.cpu().numpy().reshape(w.tables.shape)
+        assert np.allclose(th, ref_th, rtol=1e-4, atol=1e-9) and np.allclose(tb, ref_tb, rtol=1e-4, atol=1e-9)
+        assert float(c.theta_flow.abs().max()) == 0.0 and float(c.table_flow.abs().max()) == 0.0
+        assert np.all(th[0] == 0.0)
+        # next round of flows for the second EM variant
+        c.set_batch(w.x); c.forward(); c.backward()
+
+
+def test_em_on_tied_hmm_matches_oracle_and_improves_likelihood():
+    w = W.reduced(4, B=96)
+    c = pcb.Circuit(w)
+    c.set_batch(w.x)
+    ll0 = c.forward().double().sum().item()
+    c.backward()
+    tf = c.theta_flow.double().cpu().numpy().reshape(w.theta.shape)
+    gf = c.table_flow.double().cpu().numpy().reshape(w.tables.shape)
+    ref_th, ref_tb = orc.em_step(w, w.theta, w.tables, tf, gf, step=1.0, pseudocount=0.0)
+    c.em_step(1.0, 0.0)
+    torch.cuda.synchronize()
+    assert np.allclose(c.theta.cpu().numpy().reshape(w.theta.shape), ref_th, rtol=1e-4, atol=1e-9)
+    assert np.allclose(c.tables.cpu().numpy().reshape(w.tables.shape), ref_tb, rtol=1e-4, atol=1e-9)
+    ll1 = c.forward().double().sum().item()
+    assert ll1 >= ll0
+
+
+def test_forward_is_deterministic_and_state_errors():
+    w = W.reduced(5)
+    c = pcb.Circuit(w)
+    c.set_batch(w.x)
+    a = c.forward().clone()
+    b = c.forward().clone()
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)                               # no atomics on the forward path
+    # backward with a different batch size than the forward
+    with pytest.raises(pcb.PcError) as e:
+        pcb.pc_backward(c.handle, c.theta, c.tables, c.x, None, c.B - 1, c._ws, c._ws.numel(), c.theta_flow, c.table_flow)
+    assert e.value.status_name == "PC_ERR_STATE"
+    with pytest.raises(pcb.PcError) as e:
+        pcb.pc_forward(c.handle, c.theta, c.tables, c.x, None, c.B, c._ws, 1024, c.ll)
+    assert e.value.status_name == "PC_ERR_WORKSPACE"
+    with pytest.raises(pcb.PcError) as e:
+        pcb.pc_forward(c.handle, c.theta, c.tables, c.x, None, 0, c._ws, c._ws.numel(), c.ll)
+    assert e.value.status_name == "PC_ERR_ARG"
+    # EM invalidates the forward state
+    c.forward(); c.backward(); c.em_step()
+    with pytest.raises(pcb.PcError):
+        c.backward()
+
+
+def test_out_of_range_category_has_probability_zero():
+    w = W.reduced(1, B=8)
+    x = w.x.copy(); x[2, 1] = w.n_cats + 5; x[5, 0] = -3
+    c = pcb.Circuit(w)
+    c.set_batch(x)
+    ll = c.forward().cpu().numpy()
+    assert np.isneginf(ll[2]) and np.isneginf(ll[5]) and np.isfinite(ll[0])

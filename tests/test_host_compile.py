@@ -1,0 +1,131 @@
+"""CPU checks of the library: it loads, exports what include/pc.h declares, and its host compiler
+produces tables that equal the compile oracle's bit for bit (no GPU needed for these calls)."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import compile_oracle as co
+from paper_2406_00766_amd import binding as pcb
+from paper_2406_00766_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "pc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pc_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = pcb.lib()
+    names = declared_symbols()
+    assert {"pc_compile", "pc_forward", "pc_backward", "pc_em_step", "pc_destroy", "pc_last_error"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(pcb.EXPORTS) == names
+
+
+def assert_tables_equal(handle, w):
+    ref = co.compile_tables(w)
+    got = pcb.compiled_tables(handle)
+    assert len(got) == len(ref["layers"])
+    for a, b in zip(got, ref["layers"]):
+        assert (a["kind"], a["depth"]) == (b["kind"], b["depth"])
+        for key in ("fwd", "bwd"):
+            assert len(a[key]) == len(b[key]), (a["kind"], a["depth"], key)
+            for ga, gb in zip(a[key], b[key]):
+                for xa, xb in zip(ga, gb):
+                    xb = np.asarray(xb).reshape(xa.shape) if xa.size == np.asarray(xb).size else xb
+                    assert xa.dtype == np.int32 and np.array_equal(xa, xb)
+    s = pcb.pc_get_sizes(handle)
+    assert s.n_rows == ref["n_rows"] and s.K == w.K
+
+
+CASES = [lambda: W.reduced(i) for i in range(1, 6)] + \
+        [lambda: W.config(1), lambda: W.config(1, K=16), lambda: W.config(2, draw=False),
+         lambda: W.config(2, K=32, draw=False), lambda: W.config(4, draw=False), lambda: W.config(4, K=32, draw=False),
+         lambda: W.hmm(4, 6, 5, 3, 2, 7), lambda: W.pd(3, 1, 4, 1, 2, 8, n_cats=3, keep=0.5)]
+
+
+@pytest.mark.parametrize("make", CASES)
+def test_host_compile_matches_oracle_bit_for_bit(make):
+    w = make()
+    h = pcb.pc_compile(w, host_only=True)
+    try:
+        assert_tables_equal(h, w)
+    finally:
+        pcb.pc_destroy(h)
+
+
+@pytest.mark.parametrize("idx", [3, 5])
+def test_host_compile_large_configs(idx):
+    w = W.config(idx, draw=False)
+    h = pcb.pc_compile(w, host_only=True)
+    try:
+        assert_tables_equal(h, w)
+    finally:
+        pcb.pc_destroy(h)
+
+
+def test_group_tolerance_and_max_groups_are_honoured():
+    w = W.reduced(5)
+    for G, tol in [(1, 0), (2, 100), (8, 0), (8, 1000)]:
+        w.max_groups, w.tol_permille = G, tol
+        h = pcb.pc_compile(w, host_only=True)
+        try:
+            assert_tables_equal(h, w)
+        finally:
+            pcb.pc_destroy(h)
+
+
+def _expect(w, status_name):
+    with pytest.raises(pcb.PcError) as e:
+        h = pcb.pc_compile(w, host_only=True)
+        pcb.pc_destroy(h)
+    assert e.value.status_name == status_name, str(e.value)
+
+
+def test_error_paths():
+    w = W.hmm(3, 2, 3, 2, 1, 52)
+    prod1 = [b for b in range(w.n_blocks) if w.type[b] == W.PRODUCT and w.child_ptr[b + 1] - w.child_ptr[b] == 1][0]
+    bad = w.with_batch(w.x); bad.child = w.child.copy(); bad.child[w.child_ptr[prod1]] = w.root_block
+    _expect(bad, "PC_ERR_CYCLE")
+    s = int(np.nonzero(w.type == W.SUM)[0][0])
+    bad = w.with_batch(w.x); bad.child = w.child.copy()
+    bad.child[w.child_ptr[s]] = int(np.nonzero(w.type == W.INPUT)[0][0])
+    _expect(bad, "PC_ERR_NOT_ALTERNATING")
+    bad = w.with_batch(w.x); bad.K = 0
+    _expect(bad, "PC_ERR_ARG")
+    bad = w.with_batch(w.x); bad.root_block = int(np.nonzero(w.type == W.PRODUCT)[0][0])
+    _expect(bad, "PC_ERR_ARG")
+    bad = w.with_batch(w.x); bad.param_blk = w.param_blk.copy()
+    bad.param_blk[w.child_ptr[w.root_block]] = w.n_param_blocks
+    _expect(bad, "PC_ERR_ARG")
+    # partial tying: the root borrows one of the transition blocks
+    bad = w.with_batch(w.x); bad.param_blk = w.param_blk.copy()
+    bad.param_blk[w.child_ptr[w.root_block]] = 0
+    _expect(bad, "PC_ERR_TIE")
+    # duplicate (parent, child) pair
+    w2 = W.hmm(3, 4, 3, 2, 1, 53)
+    s = int(np.nonzero(w2.type == W.SUM)[0][0])
+    bad = w2.with_batch(w2.x); bad.child = w2.child.copy()
+    bad.child[w2.child_ptr[s] + 1] = bad.child[w2.child_ptr[s]]
+    _expect(bad, "PC_ERR_NOT_BLOCK_SPARSE")
+    # node offsets beyond int32
+    big = w.with_batch(w.x); big.K = 1 << 30
+    _expect(big, "PC_ERR_TOO_LARGE")
+
+
+def test_host_only_handle_refuses_device_work():
+    w = W.hmm(3, 2, 3, 2, 1, 52)
+    h = pcb.pc_compile(w, host_only=True)
+    try:
+        assert pcb.pc_workspace_bytes(h, 5) > 0
+        with pytest.raises(pcb.PcError) as e:
+            pcb.pc_forward(h, 1, 1, 1, None, 5, 1, 1 << 40, 1, stream=0)
+        assert e.value.status_name == "PC_ERR_STATE"
+    finally:
+        pcb.pc_destroy(h)
