@@ -160,6 +160,21 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
 pc_status pc_em_step(pc_circuit *c, float *theta, float *tables, float *theta_flow, float *table_flow,
                      float step, float pseudocount, void *stream);
 
+/* Per-kernel timing for benchmarks (the measurement protocol, not an operation of the paper).  While enabled,
+ * every kernel launch of forward / backward / EM is bracketed by two HIP events on the launch stream.
+ * pc_profile_read waits for the recorded events (it synchronises with the work launched so far) and returns
+ * the running totals per kernel class since pc_profile_enable; class names: pc_kernel_class_name(i),
+ * i < n_classes ("sum_fwd", "sum_bwd_child", "sum_bwd_param", "prod_fwd", ...). */
+#define PC_MAX_KERNEL_CLASSES 16
+typedef struct {
+    int32_t n_classes;
+    int64_t launches[PC_MAX_KERNEL_CLASSES];
+    double ms[PC_MAX_KERNEL_CLASSES];
+} pc_profile;
+pc_status pc_profile_enable(pc_circuit *c, int32_t on);
+pc_status pc_profile_read(pc_circuit *c, pc_profile *out);
+const char *pc_kernel_class_name(int32_t cls);
+
 #ifdef __cplusplus
 }
 #endif

@@ -56,9 +56,13 @@ class pc_ws_layout(C.Structure):
                 ("n_offset", C.c_size_t), ("r_offset", C.c_size_t), ("total_bytes", C.c_size_t)]
 
 
+class pc_profile(C.Structure):
+    _fields_ = [("n_classes", C.c_int32), ("launches", C.c_int64 * 16), ("ms", C.c_double * 16)]
+
+
 EXPORTS = ["pc_compile", "pc_compile_host", "pc_destroy", "pc_last_error", "pc_get_sizes", "pc_get_layer",
            "pc_get_group", "pc_copy_group", "pc_workspace_layout", "pc_workspace_bytes", "pc_forward",
-           "pc_backward", "pc_em_step"]
+           "pc_backward", "pc_em_step", "pc_profile_enable", "pc_profile_read", "pc_kernel_class_name"]
 
 _lib = None
 
@@ -88,6 +92,10 @@ def lib():
                                   C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
         L.pc_em_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_float, C.c_float, C.c_void_p]
+        L.pc_profile_enable.argtypes = [C.c_void_p, C.c_int32]
+        L.pc_profile_read.argtypes = [C.c_void_p, C.POINTER(pc_profile)]
+        L.pc_kernel_class_name.argtypes = [C.c_int32]
+        L.pc_kernel_class_name.restype = C.c_char_p
         _lib = L
     return _lib
 
@@ -206,6 +214,17 @@ def pc_backward(handle, theta, tables, x, mask, B, workspace, workspace_bytes, t
 def pc_em_step(handle, theta, tables, theta_flow, table_flow, step, pseudocount, stream=None):
     _check(lib().pc_em_step(handle, _ptr(theta), _ptr(tables), _ptr(theta_flow), _ptr(table_flow),
                             float(step), float(pseudocount), _stream(stream)))
+
+
+def pc_profile_enable(handle: int, on: bool):
+    _check(lib().pc_profile_enable(handle, 1 if on else 0))
+
+
+def pc_profile_read(handle: int) -> dict:
+    """{class name: (launches, total ms)} since pc_profile_enable."""
+    p = pc_profile()
+    _check(lib().pc_profile_read(handle, C.byref(p)))
+    return {lib().pc_kernel_class_name(i).decode(): (int(p.launches[i]), float(p.ms[i])) for i in range(p.n_classes)}
 
 
 def compiled_tables(handle: int) -> list[dict]:

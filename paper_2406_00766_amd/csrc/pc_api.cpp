@@ -58,6 +58,14 @@ static pc_status upload(pc_circuit *c, hipStream_t stream)
     return PC_OK;
 }
 
+struct ProfScope {                                   // installs the circuit's profiler for the calling thread
+    explicit ProfScope(pc_circuit *c) { set_profiler((Profiler *)c->profiler); }
+    ~ProfScope() { set_profiler(nullptr); }
+};
+
+static const char *const kClassNames[KC_COUNT] = {"misc", "input_fwd", "prod_fwd", "sum_fwd", "lognf", "sum_bwd_child",
+                                                  "sum_bwd_param", "prod_bwd", "input_bwd", "em"};
+
 static GroupDev dev(const GroupTab &g) { return GroupDev{g.n_rows, g.width, g.d_ids, g.d_nbr, g.d_par, g.tied_in_group}; }
 
 struct Ws {
@@ -116,6 +124,7 @@ void pc_destroy(pc_circuit *c)
 {
     if (!c) return;
     if (c->d_arena) (void)hipFree(c->d_arena);
+    delete (Profiler *)c->profiler;
     delete c;
 }
 
@@ -205,6 +214,7 @@ pc_status pc_forward(pc_circuit *c, const float *theta, const float *tables, con
     const Ws w = ws_layout(c, B);
     if (workspace_bytes < w.total) return fail(PC_ERR_WORKSPACE, "workspace smaller than pc_workspace_bytes");
     hipStream_t s = (hipStream_t)stream;
+    ProfScope prof(c);
     char *base = (char *)workspace;
     float *l = (float *)(base + w.l_off), *R = (float *)(base + w.r_off);
     int32_t *xT = (int32_t *)(base + w.xt_off);
@@ -242,6 +252,7 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
     const Ws w = ws_layout(c, B);
     if (workspace_bytes < w.total) return fail(PC_ERR_WORKSPACE, "workspace smaller than pc_workspace_bytes");
     hipStream_t s = (hipStream_t)stream;
+    ProfScope prof(c);
     char *base = (char *)workspace;
     float *l = (float *)(base + w.l_off), *F = (float *)(base + w.f_off), *N = (float *)(base + w.n_off);
     float *nfmax = (float *)(base + w.mx_off);
@@ -275,6 +286,7 @@ pc_status pc_em_step(pc_circuit *c, float *theta, float *tables, float *theta_fl
     if (!c || !theta || !tables || !theta_flow || !table_flow) return fail(PC_ERR_ARG, "NULL argument");
     if (!c->on_device) return fail(PC_ERR_STATE, "circuit was compiled without a device");
     if (!(step >= 0.0f && step <= 1.0f) || !(pseudocount >= 0.0f)) return fail(PC_ERR_ARG, "step in [0,1], pseudocount >= 0");
+    ProfScope prof(c);
     EmDev em{c->n_em_groups, c->d_pb_group, c->d_pb_rows, c->d_pb_cols, c->d_group_nch, c->d_zrow, c->d_ztab};
     launch_em(theta, tables, theta_flow, table_flow, em, c->K, c->n_param_blocks, c->n_tables, c->n_cats, step,
               pseudocount, (hipStream_t)stream);
@@ -283,5 +295,29 @@ pc_status pc_em_step(pc_circuit *c, float *theta, float *tables, float *theta_fl
     c->fw_B = -1;
     return PC_OK;
 }
+
+pc_status pc_profile_enable(pc_circuit *c, int32_t on)
+{
+    if (!c) return fail(PC_ERR_ARG, "NULL argument");
+    delete (Profiler *)c->profiler;
+    c->profiler = on ? new (std::nothrow) Profiler() : nullptr;
+    for (int k = 0; k < KC_COUNT; ++k) { c->prof_launches[k] = 0; c->prof_ms[k] = 0.0; }
+    return PC_OK;
+}
+
+pc_status pc_profile_read(pc_circuit *c, pc_profile *out)
+{
+    if (!c || !out) return fail(PC_ERR_ARG, "NULL argument");
+    if (c->profiler) ((Profiler *)c->profiler)->collect(c->prof_launches, c->prof_ms);
+    out->n_classes = KC_COUNT;
+    for (int k = 0; k < PC_MAX_KERNEL_CLASSES; ++k) {
+        out->launches[k] = k < KC_COUNT ? c->prof_launches[k] : 0;
+        out->ms[k] = k < KC_COUNT ? c->prof_ms[k] : 0.0;
+    }
+    PC_HIP(hipGetLastError());
+    return PC_OK;
+}
+
+const char *pc_kernel_class_name(int32_t cls) { return cls >= 0 && cls < KC_COUNT ? kClassNames[cls] : ""; }
 
 }  // extern "C"

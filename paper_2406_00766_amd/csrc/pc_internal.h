@@ -43,6 +43,11 @@ struct pc_circuit {
     size_t arena_bytes = 0;
     bool on_device = false;
 
+    // optional per-kernel-class timing (pc_profile_*)
+    void *profiler = nullptr;                         // pc::Profiler*, owned
+    int64_t prof_launches[16] = {0};
+    double prof_ms[16] = {0.0};
+
     // state linking pc_backward to the preceding pc_forward
     const void *fw_workspace = nullptr;
     const void *fw_theta = nullptr, *fw_tables = nullptr, *fw_x = nullptr, *fw_mask = nullptr;

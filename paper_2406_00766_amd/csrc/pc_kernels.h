@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <vector>
 
 namespace pc {
 
@@ -19,6 +20,22 @@ struct EmDev {
 };
 
 void set_force_generic(bool on);
+
+// Optional per-launch timing: when a profiler is installed, every launcher brackets its kernel with two
+// HIP events on the launch stream; totals per kernel class are summed when the profile is read.
+enum KernelClass : int {
+    KC_MISC = 0, KC_INPUT_FWD, KC_PROD_FWD, KC_SUM_FWD, KC_LOGNF, KC_SUM_BWD_CHILD, KC_SUM_BWD_PARAM, KC_PROD_BWD,
+    KC_INPUT_BWD, KC_EM, KC_COUNT
+};
+struct Profiler {
+    struct Rec { int cls; hipEvent_t a, b; };
+    std::vector<Rec> recs;
+    std::vector<hipEvent_t> pool;
+    hipEvent_t get();
+    void collect(int64_t *launches, double *ms);      // waits for the recorded events, adds to the totals
+    ~Profiler();
+};
+void set_profiler(Profiler *p);                        // nullptr switches timing off
 
 void launch_fill(float *p, int64_t n, float v, hipStream_t s);
 void launch_prepare_x(const int32_t *x, const uint8_t *mask, int32_t B, int32_t D, int64_t Bs, int32_t n_cats,

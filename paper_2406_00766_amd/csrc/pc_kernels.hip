@@ -699,6 +699,53 @@ __global__ __launch_bounds__(256) void k_em_tables(float *__restrict__ tables, f
 // ------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------
+static thread_local Profiler *g_prof = nullptr;
+void set_profiler(Profiler *p) { g_prof = p; }
+
+hipEvent_t Profiler::get()
+{
+    if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    (void)hipEventCreate(&e);
+    return e;
+}
+
+void Profiler::collect(int64_t *launches, double *ms)
+{
+    for (Rec &r : recs) {
+        float t = 0.0f;
+        if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&t, r.a, r.b) == hipSuccess) {
+            launches[r.cls] += 1;
+            ms[r.cls] += t;
+        }
+        pool.push_back(r.a);
+        pool.push_back(r.b);
+    }
+    recs.clear();
+}
+
+Profiler::~Profiler()
+{
+    for (Rec &r : recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    for (hipEvent_t e : pool) (void)hipEventDestroy(e);
+}
+
+namespace {
+struct Timed {                                                          // brackets one kernel launch
+    hipStream_t s;
+    hipEvent_t b = nullptr;
+    Timed(int cls, hipStream_t stream) : s(stream)
+    {
+        if (!g_prof) return;
+        hipEvent_t a = g_prof->get();
+        b = g_prof->get();
+        (void)hipEventRecord(a, s);
+        g_prof->recs.push_back({cls, a, b});
+    }
+    ~Timed() { if (b) (void)hipEventRecord(b, s); }
+};
+}  // namespace
+
 static inline int grid_for(int64_t items, int per_block = 256, int cap = 1 << 16)
 {
     int64_t g = (items + per_block - 1) / per_block;
@@ -722,6 +769,7 @@ static int pick_rt(int32_t K, int64_t tiles32, int64_t col_tiles)
 
 void launch_fill(float *p, int64_t n, float v, hipStream_t s)
 {
+    Timed timed(KC_MISC, s);
     if (n <= 0) return;
     hipLaunchKernelGGL(k_fill, dim3(grid_for(n, 256, 4096)), dim3(256), 0, s, p, n, v);
 }
@@ -729,6 +777,7 @@ void launch_fill(float *p, int64_t n, float v, hipStream_t s)
 void launch_prepare_x(const int32_t *x, const uint8_t *mask, int32_t B, int32_t D, int64_t Bs, int32_t n_cats,
                       int32_t *xT, hipStream_t s)
 {
+    Timed timed(KC_MISC, s);
     dim3 grid((unsigned)((Bs + 31) / 32), (unsigned)((D + 31) / 32));
     hipLaunchKernelGGL(k_prepare_x, grid, dim3(256), 0, s, x, mask, B, D, Bs, n_cats, xT);
 }
@@ -736,17 +785,20 @@ void launch_prepare_x(const int32_t *x, const uint8_t *mask, int32_t B, int32_t 
 void launch_readout(const float *l, const float *R, int64_t root_row, int64_t root_blk, int64_t Bs, int32_t B, float *ll,
                     hipStream_t s)
 {
+    Timed timed(KC_MISC, s);
     hipLaunchKernelGGL(k_readout, dim3((B + 255) / 256), dim3(256), 0, s, l, R, root_row, root_blk, Bs, B, ll);
 }
 
 void launch_root_flow(const float *l, float *F, int64_t root_row, int64_t Bs, int32_t B, hipStream_t s)
 {
+    Timed timed(KC_MISC, s);
     hipLaunchKernelGGL(k_root_flow, dim3((unsigned)((Bs + 255) / 256)), dim3(256), 0, s, l, F, root_row, Bs, B);
 }
 
 void launch_input_fwd(const float *tables, const int32_t *xT, const GroupDev &g, int32_t K, int32_t n_cats, int64_t Bs,
                       float *l, hipStream_t s)
 {
+    Timed timed(KC_INPUT_FWD, s);
     if (g.n_rows == 0) return;
     dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 255) / 256));
     hipLaunchKernelGGL(k_input_fwd, grid, dim3(256), 0, s, tables, xT, g.ids, g.nbr, g.par, K, n_cats, Bs, l);
@@ -755,6 +807,7 @@ void launch_input_fwd(const float *tables, const int32_t *xT, const GroupDev &g,
 void launch_input_bwd(const float *F, const int32_t *xT, const GroupDev &g, int32_t K, int32_t n_cats, int64_t Bs,
                       float *table_flow, hipStream_t s)
 {
+    Timed timed(KC_INPUT_BWD, s);
     if (g.n_rows == 0) return;
     dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 255) / 256));
     hipLaunchKernelGGL(k_input_bwd, grid, dim3(256), 0, s, F, xT, g.ids, g.nbr, g.par, K, n_cats, Bs, table_flow);
@@ -762,6 +815,7 @@ void launch_input_bwd(const float *F, const int32_t *xT, const GroupDev &g, int3
 
 void launch_prod_fwd(float *l, float *R, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
 {
+    Timed timed(KC_PROD_FWD, s);
     if (g.n_rows == 0) return;
     if (Bs >= 256) {
         dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 255) / 256));
@@ -774,6 +828,8 @@ void launch_prod_fwd(float *l, float *R, const GroupDev &g, int32_t K, int64_t B
 
 void launch_prod_bwd(float *F, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
 {
+    if (g.n_rows == 0) return;
+    Timed timed(KC_PROD_BWD, s);
     const int64_t items = (int64_t)g.n_rows * K * (Bs / 4);
     hipLaunchKernelGGL(k_prod_bwd, dim3(grid_for(items)), dim3(256), 0, s, F, g.ids, g.nbr, g.n_rows, g.width, K, Bs);
 }
@@ -781,6 +837,7 @@ void launch_prod_bwd(float *F, const GroupDev &g, int32_t K, int64_t Bs, hipStre
 void launch_lognf(const float *l, const float *F, float *N, float *nfmax, const int32_t *blk_ids, int32_t n_blk,
                   int32_t K, int64_t Bs, hipStream_t s)
 {
+    Timed timed(KC_LOGNF, s);
     if (n_blk == 0) return;
     dim3 grid((unsigned)n_blk, (unsigned)((Bs + 63) / 64));
     hipLaunchKernelGGL(k_lognf, grid, dim3(256), 0, s, l, F, N, nfmax, blk_ids, K, Bs);
@@ -798,6 +855,7 @@ void launch_lognf(const float *l, const float *F, float *N, float *nfmax, const 
 
 void launch_sum_fwd(const float *theta, float *l, float *R, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
 {
+    Timed timed(KC_SUM_FWD, s);
     if (g.n_rows == 0) return;
     if (use_mfma(K)) {
         const int64_t col_tiles = (Bs + 127) / 128;
@@ -814,6 +872,7 @@ void launch_sum_fwd(const float *theta, float *l, float *R, const GroupDev &g, i
 void launch_sum_bwd_child(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *F,
                           const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
 {
+    Timed timed(KC_SUM_BWD_CHILD, s);
     if (g.n_rows == 0) return;
     if (use_mfma(K)) {
         const int64_t col_tiles = (Bs + 127) / 128;
@@ -831,6 +890,7 @@ void launch_sum_bwd_child(const float *theta, const float *l, const float *R, co
 void launch_sum_bwd_param(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *G,
                           const GroupDev &g, int32_t K, int64_t Bs, int32_t B, hipStream_t s)
 {
+    Timed timed(KC_SUM_BWD_PARAM, s);
     if (g.n_rows == 0) return;
     const int atomic = g.tied ? 1 : 0;
     if (use_mfma(K)) {
@@ -851,6 +911,7 @@ void launch_em(float *theta, float *tables, float *theta_flow, float *table_flow
 {
     launch_fill(em.zrow, (int64_t)em.n_groups * K, 0.0f, s);
     launch_fill(em.ztab, (int64_t)n_tables * K, 0.0f, s);
+    Timed timed(KC_EM, s);
     if (n_param_blocks > 0) {
         hipLaunchKernelGGL(k_em_rowsum, dim3(n_param_blocks), dim3(256), 0, s, theta_flow, em.pb_group, em.pb_rows,
                            em.pb_cols, K, em.zrow);

@@ -1,0 +1,74 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times.
+
+The oracle is too slow for whole batches here, so (a) the first few samples of the full-batch GPU run are
+compared with the oracle node by node (log-probabilities and node flows are per-sample quantities), (b) the
+batch-summed parameter flows are checked through properties that hold at any size (flow conservation), and
+(c) a second GPU run on exactly the oracle's sub-batch is compared flow by flow.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import pc_oracle as orc
+from paper_2406_00766_amd import binding as pcb
+from paper_2406_00766_amd import workloads as W
+from tests.test_gpu_parity import assert_flow_close, assert_logprob_close
+
+pytestmark = pytest.mark.gpu
+
+N_ORACLE = {2: 16, 3: 4, 4: 4, 5: 4}
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4, 5])
+def test_full_size_config(idx):
+    print(f"case full-size config {idx}: generating", flush=True)
+    w = W.config(idx)
+    K, B, n = w.K, w.B, N_ORACLE[idx]
+    c = pcb.Circuit(w)
+    c.set_batch(w.x)
+    print("  gpu forward/backward at full batch", flush=True)
+    ll = c.forward().double().cpu().numpy()
+    c.backward()
+    torch.cuda.synchronize()
+    l, F, R = c.node_buffers()
+    lp_gpu = (l[K:, :n].double() + R[1:, :n].double().repeat_interleave(K, dim=0)).cpu().numpy().T
+    flow_gpu = F[K:, :n].double().cpu().numpy().T
+    tf = c.theta_flow.double().cpu().numpy().reshape(w.theta.shape)
+    gf = c.table_flow.double().cpu().numpy().reshape(w.tables.shape)
+
+    print(f"  oracle on the first {n} samples", flush=True)
+    wb = w.with_batch(w.x[:n])
+    ref_ll, ref_lp, ref_flow, ref_tf, ref_gf = orc.backward(wb, w.theta, w.tables, wb.x)
+    assert_logprob_close(ll[:n], ref_ll, "ll")
+    assert_logprob_close(lp_gpu, ref_lp, "node log-probs")
+    assert_flow_close(flow_gpu, ref_flow, "node flows")
+    assert np.all(np.isfinite(ll))
+
+    # properties of the batch-summed flows at the full batch size
+    assert np.all(np.isfinite(tf)) and np.all(np.isfinite(gf)) and tf.min() >= 0 and gf.min() >= 0
+    assert np.isclose(gf.sum(), B * w.n_vars, rtol=1e-4)
+    Fsum = F[K:, :B].double().sum(dim=1).cpu().numpy()                 # per node, summed over the batch
+    if w.meta["kind"] == "hmm":
+        H, T = w.meta["H"], w.meta["T"]
+        nb = H // K
+        assert np.isclose(tf[1:1 + nb * nb].sum(), B * (T - 1), rtol=1e-4)
+        assert np.isclose(tf[1 + nb * nb:].sum(), B, rtol=1e-4)
+    else:
+        rng = np.random.default_rng(0)
+        sums = np.nonzero(w.type == W.SUM)[0]
+        for u in rng.choice(sums, size=min(200, len(sums)), replace=False):
+            row = np.zeros(K)
+            for e in range(w.child_ptr[u], w.child_ptr[u + 1]):
+                row += tf[w.param_blk[e] + 1].sum(axis=1)
+            want = Fsum[u * K:(u + 1) * K]
+            assert np.allclose(row, want, rtol=1e-3, atol=1e-6 * max(want.max(), 1e-30))
+
+    print("  gpu on the oracle's sub-batch", flush=True)
+    c.theta_flow.zero_(); c.table_flow.zero_()
+    c.set_batch(wb.x)
+    c.forward(); c.backward()
+    torch.cuda.synchronize()
+    assert_flow_close(c.theta_flow.double().cpu().numpy().reshape(w.theta.shape), ref_tf, "theta flows")
+    assert_flow_close(c.table_flow.double().cpu().numpy().reshape(w.tables.shape), ref_gf, "table flows")
+    c.close()
