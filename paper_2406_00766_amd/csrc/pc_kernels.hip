@@ -26,6 +26,7 @@
 namespace pc {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 #define PC_NEG_INF (-__builtin_inff())
 
@@ -357,26 +358,74 @@ __global__ __launch_bounds__(256) void k_sum_bwd_param_generic(const float *__re
 // MFMA sum-layer kernels (K % 32 == 0).  Workgroup = 4 waves; a wave owns 32 sample columns.
 // ------------------------------------------------------------------------------------------
 
-// Forward (role of Alg. 1).  Tile = TM = 32*RT sum rows of one sum block x 128 samples.  Loop over the
-// child blocks of the row; each 32-child chunk: theta[TM x 32] staged in LDS (shared by the waves),
-// child log-probs loaded straight into the B-operand layout, shifted by the running per-sample
-// maximum, exponentiated in registers and multiplied on the matrix cores.  The accumulator stays in
-// linear space relative to the running maximum and is rescaled when the maximum grows (same sum as
-// the per-block log-space update of Alg. 1 line 16, one log per output instead of one per block).
-template <int K, int RT>
-__global__ __launch_bounds__(256) void k_sum_fwd_mfma(const float *__restrict__ theta, float *__restrict__ l,
-                                                      float *__restrict__ R, const int32_t *__restrict__ ids,
-                                                      const int32_t *__restrict__ nbr, const int32_t *__restrict__ par,
-                                                      int32_t width, int64_t Bs)
+// Forward (role of Alg. 1) and backward-to-children (role of Alg. 4) share one kernel.
+//
+// A wave owns a tile of TM = 32*RT rows of one node block x 32 sample columns and a share of the row's
+// neighbour chunks (KC = 32 nodes per chunk).  The rows are sum nodes (forward) or child product nodes
+// (backward).  A workgroup holds 4 waves: SPLIT of them share one output tile and take the chunks
+// round-robin (split of the reduction dimension, so that small batches still fill every SIMD with two
+// waves -- a wave cannot overlap its own VALU work with its own MFMAs, a second wave can), the other
+// factor 4/SPLIT spans adjacent column tiles.  Per chunk and wave:
+//   * the theta sub-block [TM x KC] is fetched with coalesced 16-byte loads and staged in a wave-private
+//     LDS tile only to reach the MFMA A-operand layout (LDS operations of one wave complete in order, so
+//     no barrier and no double buffer are needed), then read back whole into registers;
+//   * the KC x 32 neighbour values go straight from L2 into the MFMA B-operand layout;
+//   * loads of the wave's next chunk are issued before the arithmetic of the current one.
+//   forward : value = l (log-prob residual) + (R_child - R_sum); the chunk maximum is taken in registers
+//   backward: value = N (log F - l of the parent) + (R_child - R_parent); the block maximum is nfmax
+// Values are shifted by the running per-sample maximum, exponentiated in registers and multiplied on
+// the matrix cores (MFMA step q of a chunk pairs lanes 0-31 with node 8*(q/4) + q%4 and lanes 32-63 with
+// node 8*(q/4) + 4 + q%4, so that one 16-byte LDS read yields the A operands of four steps); the
+// accumulator stays in linear space and is rescaled when the maximum grows (the same sum as the
+// per-block log-space update of Alg. 1 line 16 / Alg. 4 line 16, with one log per output instead of one
+// per block).  Partial sums of the SPLIT waves are merged through LDS at the end.  No lane-dependent
+// branch surrounds an MFMA.
+#define PC_LOG2E 1.4426950408889634f
+template <int K, int RT, int SPLIT, bool BWD>
+__global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ theta, float *__restrict__ l,
+                                                     float *__restrict__ R, const float *__restrict__ N,
+                                                     const float *__restrict__ nfmax, float *__restrict__ F,
+                                                     const int32_t *__restrict__ ids, const int32_t *__restrict__ nbr,
+                                                     const int32_t *__restrict__ par, int32_t width, int64_t Bs)
 {
+    constexpr int KC = 32;
     constexpr int TM = 32 * RT;
     constexpr int SUB = K / TM;
-    __shared__ float As[TM][33];
+    constexpr int NQ = KC / 2;                                          // MFMA steps per chunk
+    constexpr int CPB = K / KC;                                         // chunks per neighbour block
+    constexpr int NCT = 4 / SPLIT;                                      // column tiles per workgroup
+    constexpr int NF4 = TM * KC / 4 / 64;                               // 16-byte loads per lane per chunk
+    constexpr int LDA = BWD ? TM : KC + 4;                              // LDS row stride (floats); KC+4: b128 reads conflict-free
+    constexpr int TILE = (BWD ? KC : TM) * LDA;
+    constexpr int XCH = RT * 16 * 64 + 64;                              // one partial accumulator + its maxima
+    constexpr int WSZ = TILE > XCH ? TILE : XCH;
+    static_assert(K % TM == 0 && (SPLIT == 1 || SPLIT == 2 || SPLIT == 4), "tile shape");
+    __shared__ float lds[4 * WSZ];
+
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
+    const int ct = wave / SPLIT, sp = wave % SPLIT;
     const int r = blockIdx.x / SUB, sub = blockIdx.x % SUB;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
-    const int64_t col0 = (int64_t)blockIdx.y * 128 + wave * 32;
-    const bool active = col0 < Bs;
-    const int64_t col = col0 + l32;
+    const int64_t col0 = ((int64_t)blockIdx.y * NCT + ct) * 32;
+    const bool active = col0 < Bs;                                      // wave-uniform
+    const int64_t col = (active ? col0 : 0) + l32;
+    const int32_t *row_nbr = nbr + (int64_t)r * width, *row_par = par + (int64_t)r * width;
+    const int32_t id = ids[r];
+    float *buf = lds + wave * WSZ;
+
+    int n_real = 0;                                                     // padding sits at the end of a row
+    while (n_real < width && row_par[n_real] != 0) ++n_real;
+    const int n_chunks = n_real * CPB;
+
+    // block reference of this row: forward max of the children's (and stored), backward the row's own
+    float Rrow;
+    if (BWD) {
+        Rrow = R[(int64_t)(id / K) * Bs + col];
+    } else {
+        Rrow = PC_NEG_INF;
+        for (int j = 0; j < n_real; ++j) Rrow = fmaxf(Rrow, R[(int64_t)(row_nbr[j] / K) * Bs + col]);
+        if (active && sub == 0 && sp == 0 && half == 0) R[(int64_t)(id / K) * Bs + col] = Rrow;
+    }
 
     floatx16 acc[RT];
 #pragma unroll
@@ -385,146 +434,124 @@ __global__ __launch_bounds__(256) void k_sum_fwd_mfma(const float *__restrict__ 
         for (int e = 0; e < 16; ++e) acc[rt][e] = 0.0f;
     float m = PC_NEG_INF;
 
-    float Rn = PC_NEG_INF;                                              // R of this sum block = max of its children's
-    if (active) {
-        for (int j = 0; j < width; ++j)
-            if (par[(int64_t)r * width + j] != 0) Rn = fmaxf(Rn, R[(int64_t)(nbr[(int64_t)r * width + j] / K) * Bs + col]);
-        if (sub == 0 && half == 0) R[(int64_t)(ids[r] / K) * Bs + col] = Rn;
-    }
+    floatx4 th_next[NF4];
+    float v_next[NQ];
+    float rblk_next = 0.0f, bmax_next = PC_NEG_INF;
+    const float *vsrc = BWD ? N : l;
+    const int64_t lane_off = (int64_t)(4 * half) * Bs + col;            // per-lane part of a neighbour-value address
 
-    for (int j = 0; j < width; ++j) {
-        const int32_t ns = nbr[(int64_t)r * width + j], ps = par[(int64_t)r * width + j];
-        if (ps == 0) continue;                                          // pseudo block of probability 0
-        const float d = active ? R[(int64_t)(ns / K) * Bs + col] - Rn : 0.0f;   // exact integer <= 0
-        for (int kc = 0; kc < K / 32; ++kc) {
-            __syncthreads();
-            for (int t = threadIdx.x; t < TM * 8; t += 256) {
-                const int row = t >> 3, c4 = t & 7;
-                const float4 v = *reinterpret_cast<const float4 *>(theta + (int64_t)ps + (int64_t)(sub * TM + row) * K + kc * 32 + c4 * 4);
-                As[row][c4 * 4 + 0] = v.x; As[row][c4 * 4 + 1] = v.y; As[row][c4 * 4 + 2] = v.z; As[row][c4 * 4 + 3] = v.w;
-            }
-            float v[16];
-            float cmax = PC_NEG_INF;
-            if (active) {
-                const float *src = l + (int64_t)(ns + kc * 32 + half) * Bs + col;
+    // loads of chunk C into th_next / v_next / d_next / bmax_next (a macro, so the arrays stay in registers)
+#define PC_ISSUE(C)                                                                                                   \
+    do {                                                                                                              \
+        const int j_ = (C) / CPB, kc_ = (C) % CPB;                                                                    \
+        const int32_t ns_ = row_nbr[j_], ps_ = row_par[j_];                                                           \
+        const float *tb_ = BWD ? theta + (int64_t)ps_ + (int64_t)(kc_ * KC) * K + sub * TM                            \
+                               : theta + (int64_t)ps_ + (int64_t)(sub * TM) * K + kc_ * KC;                           \
+        _Pragma("unroll") for (int i = 0; i < NF4; ++i) {                                                             \
+            const int t = lane + i * 64;                                                                              \
+            const int o_ = BWD ? (t / (TM / 4)) * K + (t % (TM / 4)) * 4 : (t / (KC / 4)) * K + (t % (KC / 4)) * 4;    \
+            th_next[i] = *reinterpret_cast<const floatx4 *>(tb_ + o_);                                                \
+        }                                                                                                             \
+        const float *src_ = vsrc + (int64_t)(ns_ + kc_ * KC) * Bs;                                                    \
+        _Pragma("unroll") for (int q = 0; q < NQ; ++q) v_next[q] = src_[(int64_t)(8 * (q / 4) + (q % 4)) * Bs + lane_off]; \
+        const int64_t blk_ = (int64_t)(ns_ / K) * Bs + col;                                                           \
+        rblk_next = R[blk_];                              /* raw: any arithmetic here would wait for the load */     \
+        if (BWD) bmax_next = nfmax[blk_];                                                                             \
+    } while (0)
+
+    if (sp < n_chunks) PC_ISSUE(sp);
+    for (int c = sp; c < n_chunks; c += SPLIT) {
 #pragma unroll
-                for (int q = 0; q < 16; ++q) { v[q] = src[(int64_t)(2 * q) * Bs] + d; cmax = fmaxf(cmax, v[q]); }
-                cmax = fmaxf(cmax, __shfl_xor(cmax, 32));
-            }
-            __syncthreads();
-            if (active) {                                                // wave-uniform; no lane-dependent branch around MFMA
-                const float m_new = fmaxf(m, cmax);
-                const bool dead = !(m_new > PC_NEG_INF);                 // every term of this column so far is 0
-                const float scale = dead ? 1.0f : __expf(m - m_new);     // m = -inf -> 0, acc is 0 anyway
-                m = m_new;
+        for (int i = 0; i < NF4; ++i) {
+            const int t = lane + i * 64;
+            const int o = BWD ? (t / (TM / 4)) * LDA + (t % (TM / 4)) * 4 : (t / (KC / 4)) * LDA + (t % (KC / 4)) * 4;
+            *reinterpret_cast<floatx4 *>(buf + o) = th_next[i];
+        }
+        float v[NQ];
+        float cmax = PC_NEG_INF;
 #pragma unroll
-                for (int rt = 0; rt < RT; ++rt)
+        for (int q = 0; q < NQ; ++q) { v[q] = v_next[q]; if (!BWD) cmax = fmaxf(cmax, v[q]); }
+        const float d = BWD ? Rrow - rblk_next : rblk_next - Rrow;      // exact integer <= 0
+        if (BWD) cmax = bmax_next + d;
+        else cmax = fmaxf(cmax, __shfl_xor(cmax, 32)) + d;
+        if (c + SPLIT < n_chunks) PC_ISSUE(c + SPLIT);
+
+        // A operands of the whole chunk into registers first, so the MFMA stream below never waits on LDS
+        float areg[NQ][RT];
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) acc[rt][e] *= scale;
+        for (int rt = 0; rt < RT; ++rt) {
+            if (BWD) {
 #pragma unroll
-                for (int q = 0; q < 16; ++q) {
-                    const float p = dead ? 0.0f : __expf(v[q] - m_new);  // -inf -> 0
+                for (int q = 0; q < NQ; ++q) areg[q][rt] = buf[(8 * (q / 4) + 4 * half + (q % 4)) * LDA + rt * 32 + l32];
+            } else {
 #pragma unroll
-                    for (int rt = 0; rt < RT; ++rt)
-                        acc[rt] = __builtin_amdgcn_mfma_f32_32x32x2f32(As[rt * 32 + l32][2 * q + half], p, acc[rt], 0, 0, 0);
+                for (int g = 0; g < NQ / 4; ++g) {
+                    const floatx4 a4 = *reinterpret_cast<const floatx4 *>(buf + (rt * 32 + l32) * LDA + 8 * g + 4 * half);
+                    areg[4 * g + 0][rt] = a4[0]; areg[4 * g + 1][rt] = a4[1]; areg[4 * g + 2][rt] = a4[2]; areg[4 * g + 3][rt] = a4[3];
                 }
             }
         }
-    }
-    if (active) {
-        const int64_t base = (int64_t)(ids[r] + sub * TM);
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int i = rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
-                const float a = acc[rt][e];
-                l[(base + i) * Bs + col] = a > 0.0f ? m + __logf(a) : PC_NEG_INF;
-            }
-    }
-}
-
-// Backward to the children (role of Alg. 4).  Rows = TM child (product) nodes of one child block,
-// loop over its parent sum blocks; B operand = exp(log_nf - running max), A operand = theta^T.
-// The per-parent-block maximum of log_nf comes precomputed (nfmax).  F_child += exp(log acc + max + l_child).
-template <int K, int RT>
-__global__ __launch_bounds__(256) void k_sum_bwd_child_mfma(const float *__restrict__ theta, const float *__restrict__ l,
-                                                            const float *__restrict__ R,
-                                                            const float *__restrict__ N, const float *__restrict__ nfmax,
-                                                            float *__restrict__ F, const int32_t *__restrict__ ids,
-                                                            const int32_t *__restrict__ nbr, const int32_t *__restrict__ par,
-                                                            int32_t width, int64_t Bs)
-{
-    constexpr int TM = 32 * RT;
-    constexpr int SUB = K / TM;
-    __shared__ float As[32][TM];                                        // [parent row s][child row c]
-    const int r = blockIdx.x / SUB, sub = blockIdx.x % SUB;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
-    const int64_t col0 = (int64_t)blockIdx.y * 128 + wave * 32;
-    const bool active = col0 < Bs;
-    const int64_t col = col0 + l32;
-
-    floatx16 acc[RT];
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[rt][e] = 0.0f;
-    float m = PC_NEG_INF;
-    const float Rc = active ? R[(int64_t)(ids[r] / K) * Bs + col] : 0.0f;
-
-    for (int j = 0; j < width; ++j) {
-        const int32_t ms = nbr[(int64_t)r * width + j], ps = par[(int64_t)r * width + j];
-        if (ps == 0) continue;
-        float d = 0.0f;                                                 // R_child - R_parent: exact integer <= 0
-        if (active) {
-            d = Rc - R[(int64_t)(ms / K) * Bs + col];
-            const float m_new = fmaxf(m, nfmax[(int64_t)(ms / K) * Bs + col] + d);
-            const float scale = m_new > PC_NEG_INF ? __expf(m - m_new) : 1.0f;
-            m = m_new;
+        const float m_new = fmaxf(m, cmax);
+        const bool dead = !(m_new > PC_NEG_INF);                        // every term of this column so far is 0
+        if (__any(m_new != m)) {
+            const float scale = dead ? 1.0f : __expf(m - m_new);        // m = -inf -> 0, acc is 0 anyway
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[rt][e] *= scale;
         }
-        const bool dead = !(m > PC_NEG_INF);                             // per lane: nothing flows into this column yet
-        for (int kc = 0; kc < K / 32; ++kc) {
-            __syncthreads();
-            for (int t = threadIdx.x; t < 32 * (TM / 4); t += 256) {
-                const int s = t / (TM / 4), c4 = t % (TM / 4);
-                const float4 v = *reinterpret_cast<const float4 *>(theta + (int64_t)ps + (int64_t)(kc * 32 + s) * K + sub * TM + c4 * 4);
-                *reinterpret_cast<float4 *>(&As[s][c4 * 4]) = v;
-            }
-            float v[16];
-            if (active) {
-                const float *src = N + (int64_t)(ms + kc * 32 + half) * Bs + col;
+        m = m_new;
+        const float sh2 = dead ? 0.0f : (d - m_new) * PC_LOG2E;        // exp(v + d - m) = exp2(v * log2e + sh2); dead: v = -inf -> 0
 #pragma unroll
-                for (int q = 0; q < 16; ++q) v[q] = src[(int64_t)(2 * q) * Bs];
-            }
-            __syncthreads();
-            if (active) {                                                // wave-uniform
+        for (int q = 0; q < NQ; ++q) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(v[q], PC_LOG2E, sh2));
 #pragma unroll
-                for (int q = 0; q < 16; ++q) {
-                    const float p = dead ? 0.0f : __expf(v[q] + d - m);
-#pragma unroll
-                    for (int rt = 0; rt < RT; ++rt)
-                        acc[rt] = __builtin_amdgcn_mfma_f32_32x32x2f32(As[2 * q + half][rt * 32 + l32], p, acc[rt], 0, 0, 0);
-                }
-            }
+            for (int rt = 0; rt < RT; ++rt) acc[rt] = __builtin_amdgcn_mfma_f32_32x32x2f32(areg[q][rt], p, acc[rt], 0, 0, 0);
         }
     }
-    if (active && m > PC_NEG_INF) {
-        const int64_t base = (int64_t)(ids[r] + sub * TM);
+#undef PC_ISSUE
+
+    if (SPLIT > 1) {                                                    // merge the partial sums of the SPLIT waves of a tile
+        __syncthreads();
+        if (sp != 0) {
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
+            for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int i = rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
-                const float a = acc[rt][e];
-                const int64_t at = (base + i) * Bs + col;
+                for (int e = 0; e < 16; ++e) buf[(rt * 16 + e) * 64 + lane] = acc[rt][e];
+            buf[RT * 16 * 64 + lane] = m;
+        }
+        __syncthreads();
+        if (sp != 0) return;
+#pragma unroll
+        for (int s = 1; s < SPLIT; ++s) {
+            const float *ob = lds + (wave + s) * WSZ;
+            const float mo = ob[RT * 16 * 64 + lane];
+            const float m_new = fmaxf(m, mo);
+            const bool dead = !(m_new > PC_NEG_INF);
+            const float s0 = dead ? 1.0f : __expf(m - m_new), s1 = dead ? 0.0f : __expf(mo - m_new);
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[rt][e] = acc[rt][e] * s0 + ob[(rt * 16 + e) * 64 + lane] * s1;
+            m = m_new;
+        }
+    }
+    if (!active) return;
+    const int64_t base = (int64_t)(id + sub * TM);
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int i = rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+            const float a = acc[rt][e];
+            const int64_t at = (base + i) * Bs + col;
+            if (BWD) {
                 const float lc = l[at];
                 if (a > 0.0f && lc > PC_NEG_INF) F[at] += __expf(__logf(a) + m + lc);
+            } else {
+                l[at] = a > 0.0f ? m + __logf(a) : PC_NEG_INF;
             }
-    }
+        }
 }
 
 // Backward to the parameters (role of Alg. 3).  Output tile = TM sum rows x (4 waves x 32) child
@@ -853,15 +880,44 @@ void launch_lognf(const float *l, const float *F, float *N, float *nfmax, const 
         else hipLaunchKernelGGL((KERNEL<128, 4>), __VA_ARGS__);                                           \
     } while (0)
 
+// forward / backward-to-children: (K, rows per wave tile / 32, waves sharing one tile)
+#define PC_SUM_CASE(KK, RR, SS, BWD, ...)                                                                  \
+    if (K == KK && rt == RR && split == SS) { hipLaunchKernelGGL((k_sum_mfma<KK, RR, SS, BWD>), __VA_ARGS__); break; }
+#define PC_DISPATCH_SUM(BWD, ...)                                                                         \
+    do {                                                                                                  \
+        PC_SUM_CASE(32, 1, 1, BWD, __VA_ARGS__) PC_SUM_CASE(32, 1, 2, BWD, __VA_ARGS__) PC_SUM_CASE(32, 1, 4, BWD, __VA_ARGS__)    \
+        PC_SUM_CASE(64, 1, 1, BWD, __VA_ARGS__) PC_SUM_CASE(64, 1, 2, BWD, __VA_ARGS__) PC_SUM_CASE(64, 1, 4, BWD, __VA_ARGS__)    \
+        PC_SUM_CASE(64, 2, 1, BWD, __VA_ARGS__) PC_SUM_CASE(64, 2, 2, BWD, __VA_ARGS__) PC_SUM_CASE(64, 2, 4, BWD, __VA_ARGS__)    \
+        PC_SUM_CASE(128, 1, 1, BWD, __VA_ARGS__) PC_SUM_CASE(128, 1, 2, BWD, __VA_ARGS__) PC_SUM_CASE(128, 1, 4, BWD, __VA_ARGS__) \
+        PC_SUM_CASE(128, 2, 1, BWD, __VA_ARGS__) PC_SUM_CASE(128, 2, 2, BWD, __VA_ARGS__) PC_SUM_CASE(128, 2, 4, BWD, __VA_ARGS__) \
+        PC_SUM_CASE(128, 4, 1, BWD, __VA_ARGS__) PC_SUM_CASE(128, 4, 2, BWD, __VA_ARGS__) PC_SUM_CASE(128, 4, 4, BWD, __VA_ARGS__) \
+    } while (0)
+
+// Tile shape for the forward / backward-to-children kernel: the largest row tile (least exp work and
+// neighbour traffic per flop) that still leaves two waves per SIMD (2048 waves on 256 CUs), splitting
+// the reduction over up to four waves when rows x columns alone are too few.
+static void pick_sum_shape(int32_t K, int32_t n_rows, int32_t width, int64_t Bs, int &rt, int &split)
+{
+    const int64_t col_tiles = (Bs + 31) / 32;
+    const int64_t want = 2048;
+    rt = K / 32 > 4 ? 4 : K / 32;
+    while (rt > 1 && (int64_t)n_rows * (K / (32 * rt)) * col_tiles * 4 < want) rt >>= 1;
+    const int64_t tiles = (int64_t)n_rows * (K / (32 * rt)) * col_tiles;
+    split = 1;
+    while (split < 4 && tiles * split < want && (int64_t)width * (K / 32) >= 2 * split) split <<= 1;
+}
+
 void launch_sum_fwd(const float *theta, float *l, float *R, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
 {
     Timed timed(KC_SUM_FWD, s);
     if (g.n_rows == 0) return;
     if (use_mfma(K)) {
-        const int64_t col_tiles = (Bs + 127) / 128;
-        const int rt = pick_rt(K, (int64_t)g.n_rows * (K / 32), col_tiles);
-        dim3 grid((unsigned)(g.n_rows * (K / (32 * rt))), (unsigned)col_tiles);
-        PC_DISPATCH_K_RT(k_sum_fwd_mfma, K, rt, grid, dim3(256), 0, s, theta, l, R, g.ids, g.nbr, g.par, g.width, Bs);
+        int rt, split;
+        pick_sum_shape(K, g.n_rows, g.width, Bs, rt, split);
+        const int64_t cols_per_wg = 32 * (4 / split);
+        dim3 grid((unsigned)(g.n_rows * (K / (32 * rt))), (unsigned)((Bs + cols_per_wg - 1) / cols_per_wg));
+        PC_DISPATCH_SUM(false, grid, dim3(256), 0, s, theta, l, R, (const float *)nullptr, (const float *)nullptr,
+                        (float *)nullptr, g.ids, g.nbr, g.par, g.width, Bs);
     } else {
         const int64_t items = (int64_t)g.n_rows * K * Bs;
         hipLaunchKernelGGL(k_sum_fwd_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, l, R, g.ids, g.nbr, g.par,
@@ -875,11 +931,12 @@ void launch_sum_bwd_child(const float *theta, const float *l, const float *R, co
     Timed timed(KC_SUM_BWD_CHILD, s);
     if (g.n_rows == 0) return;
     if (use_mfma(K)) {
-        const int64_t col_tiles = (Bs + 127) / 128;
-        const int rt = pick_rt(K, (int64_t)g.n_rows * (K / 32), col_tiles);
-        dim3 grid((unsigned)(g.n_rows * (K / (32 * rt))), (unsigned)col_tiles);
-        PC_DISPATCH_K_RT(k_sum_bwd_child_mfma, K, rt, grid, dim3(256), 0, s, theta, l, R, N, nfmax, F, g.ids, g.nbr, g.par,
-                         g.width, Bs);
+        int rt, split;
+        pick_sum_shape(K, g.n_rows, g.width, Bs, rt, split);
+        const int64_t cols_per_wg = 32 * (4 / split);
+        dim3 grid((unsigned)(g.n_rows * (K / (32 * rt))), (unsigned)((Bs + cols_per_wg - 1) / cols_per_wg));
+        PC_DISPATCH_SUM(true, grid, dim3(256), 0, s, theta, const_cast<float *>(l), const_cast<float *>(R), N, nfmax,
+                        F, g.ids, g.nbr, g.par, g.width, Bs);
     } else {
         const int64_t items = (int64_t)g.n_rows * K * Bs;
         hipLaunchKernelGGL(k_sum_bwd_child_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, l, R, N, F, g.ids, g.nbr,
