@@ -42,6 +42,7 @@ static pc_status upload(pc_circuit *c, hipStream_t stream)
     }
     add(&c->d_pb_group, c->pb_group); add(&c->d_pb_rows, c->pb_rows); add(&c->d_pb_cols, c->pb_cols);
     add(&c->d_group_nch, c->group_nch);
+    add(&c->d_pf_pb, c->pf_pb); add(&c->d_pf_ptr, c->pf_ptr); add(&c->d_pf_sum, c->pf_sum); add(&c->d_pf_child, c->pf_child);
     const size_t zrow_off = reserve((size_t)c->n_em_groups * c->K + 1);
     const size_t ztab_off = reserve((size_t)c->n_tables * c->K + 1);
     PC_HIP(hipMalloc(&c->d_arena, bytes));
@@ -261,6 +262,9 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
     const int32_t K = c->K;
     const int64_t rows = ((int64_t)c->n_blocks + 1) * K;
 
+    // MFMA block sizes: parameter flows of the whole circuit in one launch after the sweep (N and nfmax of
+    // every sum layer stay valid until then); other block sizes: layer by layer
+    const bool batched_params = param_flow_uses_mfma(K);
     launch_fill(F, rows * w.Bs, 0.0f, s);
     launch_root_flow(l, F, (int64_t)(c->root_block + 1) * K, w.Bs, B, s);
     for (size_t li = c->layers.size(); li-- > 0;) {
@@ -268,13 +272,17 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
         if (L.kind == KIND_SUM) {
             launch_lognf(l, F, N, nfmax, L.d_blk_ids, (int32_t)L.blk_ids.size(), K, w.Bs, s);
             for (const GroupTab &g : L.bwd) launch_sum_bwd_child(theta, l, R, N, nfmax, F, dev(g), K, w.Bs, s);
-            if (theta_flow)
-                for (const GroupTab &g : L.fwd) launch_sum_bwd_param(theta, l, R, N, nfmax, theta_flow, dev(g), K, w.Bs, B, s);
+            if (theta_flow && !batched_params)
+                for (const GroupTab &g : L.fwd) launch_sum_bwd_param_generic(theta, l, R, N, theta_flow, dev(g), K, w.Bs, B, s);
         } else if (L.kind == KIND_PRODUCT) {
             for (const GroupTab &g : L.bwd) launch_prod_bwd(F, dev(g), K, w.Bs, s);
         } else if (table_flow) {
             launch_input_bwd(F, xT, dev(L.fwd[0]), K, c->n_cats, w.Bs, table_flow, s);
         }
+    }
+    if (theta_flow && batched_params) {
+        ParamFlowDev pf{(int32_t)c->pf_pb.size(), c->d_pf_pb, c->d_pf_ptr, c->d_pf_sum, c->d_pf_child};
+        launch_param_flow(theta, l, R, N, nfmax, theta_flow, pf, K, w.Bs, s);
     }
     PC_HIP(hipGetLastError());
     return PC_OK;

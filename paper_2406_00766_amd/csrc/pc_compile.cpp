@@ -300,6 +300,22 @@ pc_status compile_host(const pc_dag *d, pc_circuit *c)
         }
     }
     c->n_em_groups = (int32_t)group_list.size();
+
+    // Parameter-centric flow tables (App. A.3): every (sum block, child block) pair that uses a parameter
+    // block, so that the flows of tied edges are reduced together; pairs in ascending sum-block order.
+    std::vector<std::vector<std::pair<int32_t, int32_t>>> users(P);
+    for (int32_t u = 0; u < n; ++u) {
+        if (d->type[u] != KIND_SUM) continue;
+        for (int64_t e = d->child_ptr[u]; e < d->child_ptr[u + 1]; ++e)
+            users[d->param_blk[e]].emplace_back((u + 1) * K, (d->child[e] + 1) * K);
+    }
+    c->pf_pb.clear(); c->pf_ptr.assign(1, 0); c->pf_sum.clear(); c->pf_child.clear();
+    for (int32_t p = 0; p < P; ++p) {
+        if (users[p].empty()) continue;
+        c->pf_pb.push_back((p + 1) * K * K);
+        for (auto &sc : users[p]) { c->pf_sum.push_back(sc.first); c->pf_child.push_back(sc.second); }
+        c->pf_ptr.push_back((int32_t)c->pf_sum.size());
+    }
     return PC_OK;
 }
 

@@ -39,6 +39,10 @@ struct pc_circuit {
     float *d_zrow = nullptr;                          // [n_em_groups * K] row sums of flows
     float *d_ztab = nullptr;                          // [n_tables * K] column sums of table flows
 
+    // parameter-centric flow tables: parameter block offset -> CSR list of (sum block, child block) node offsets
+    std::vector<int32_t> pf_pb, pf_ptr, pf_sum, pf_child;
+    int32_t *d_pf_pb = nullptr, *d_pf_ptr = nullptr, *d_pf_sum = nullptr, *d_pf_child = nullptr;
+
     void *d_arena = nullptr;                          // one device allocation behind every d_* above
     size_t arena_bytes = 0;
     bool on_device = false;

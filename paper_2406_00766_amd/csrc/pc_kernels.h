@@ -13,6 +13,11 @@ struct GroupDev {            // device view of one table group
     bool tied;
 };
 
+struct ParamFlowDev {        // parameter blocks with the (sum block, child block) pairs that use them
+    int32_t n_pb;
+    const int32_t *pb, *ptr, *sum, *child;
+};
+
 struct EmDev {
     int32_t n_groups;
     const int32_t *pb_group, *pb_rows, *pb_cols, *group_nch;
@@ -54,8 +59,11 @@ void launch_lognf(const float *l, const float *F, float *N, float *nfmax, const 
 void launch_sum_fwd(const float *theta, float *l, float *R, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s);
 void launch_sum_bwd_child(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *F,
                           const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s);
-void launch_sum_bwd_param(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *G,
-                          const GroupDev &g, int32_t K, int64_t Bs, int32_t B, hipStream_t s);
+void launch_sum_bwd_param_generic(const float *theta, const float *l, const float *R, const float *N, float *G,
+                                  const GroupDev &g, int32_t K, int64_t Bs, int32_t B, hipStream_t s);
+bool param_flow_uses_mfma(int32_t K);
+void launch_param_flow(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *G,
+                       const ParamFlowDev &pf, int32_t K, int64_t Bs, hipStream_t s);
 void launch_em(float *theta, float *tables, float *theta_flow, float *table_flow, const EmDev &em, int32_t K,
                int32_t n_param_blocks, int32_t n_tables, int32_t n_cats, float step, float pc, hipStream_t s);
 

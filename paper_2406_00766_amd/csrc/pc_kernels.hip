@@ -554,94 +554,142 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
         }
 }
 
-// Backward to the parameters (role of Alg. 3).  Output tile = TM sum rows x (4 waves x 32) child
-// columns of the row's flattened child list; reduction over the batch in chunks of 32 samples on the
-// matrix cores.  Each term exp(log_nf_s + l_c) is split into two fp32 factors around a per-sample
-// shift (any shift is valid: it only moves scale between the factors).  With a = max_s log_nf_s of
-// the sum block, the factors are exp(log_nf_s - a + 43) <= e^43 and exp(l_c + a - 43) <= e^44.3
-// (theta p_c / p_s <= 1 and theta >= FLT_MIN bound l_c + a by 87.3), so neither overflows and a
-// product is lost to underflow only when it is below e^-40.  Alg. 3 shifts by a alone, which can
-// drop products of order one when a weight is as small as FLT_MIN.
+// Backward to the parameters (role of Alg. 3), organised by PARAMETER BLOCK instead of by layer: one launch
+// covers every parameter block of the circuit after the backward sweep.  A wave owns a TMW x TNW tile
+// (up to 64 x 64) of one K x K parameter block and reduces over the batch of every (sum block, child
+// block) pair that uses the block -- all tied instances, e.g. the T-1 transition layers of an HMM
+// (App. A.3) -- in registers, so each flow element is read-modified-written once per call, without
+// atomics and without the per-layer accumulation of Alg. 3 line 21.
+//
+// Each term exp(log_nf_s + l_c) is split into two fp32 factors around a per-sample shift (any shift is
+// valid: it only moves scale between the factors).  With a = max_s log_nf_s of the sum block, the
+// factors are exp(log_nf_s - a + 43) <= e^43 and exp(l_c + a - 43) <= e^44.3 (theta p_c / p_s <= 1 and
+// theta >= FLT_MIN bound l_c + a by 87.3), so neither overflows and a product is lost to underflow only
+// when it is below e^-40.  Alg. 3 shifts by a alone, which can drop products of order one when a weight
+// is as small as FLT_MIN.
+//
+// Per chunk of 32 samples a wave fetches its TMW rows of N and TNW rows of l with 16-byte loads along
+// the batch, applies the exponentials, and stages both tiles in wave-private LDS (row stride 36 floats)
+// to reach the MFMA operand layouts (batch index on k: step q pairs lanes 0-31 with sample 8*(q/4) + q%4
+// and lanes 32-63 with sample 8*(q/4) + 4 + q%4); loads of the next chunk are issued before the
+// arithmetic of the current one.
 #define PC_SPLIT 43.0f
 #define PC_SPLIT_CAP 44.5f
-template <int K, int RT>
-__global__ __launch_bounds__(256) void k_sum_bwd_param_mfma(const float *__restrict__ theta, const float *__restrict__ l,
-                                                            const float *__restrict__ R,
-                                                            const float *__restrict__ N, const float *__restrict__ nfmax,
-                                                            float *__restrict__ G, const int32_t *__restrict__ ids,
-                                                            const int32_t *__restrict__ nbr, const int32_t *__restrict__ par,
-                                                            int32_t width, int64_t Bs, int atomic)
+template <int K, int RT, int CT>
+__global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restrict__ theta, const float *__restrict__ l,
+                                                            const float *__restrict__ R, const float *__restrict__ N,
+                                                            const float *__restrict__ nfmax, float *__restrict__ G,
+                                                            const int32_t *__restrict__ pf_pb, const int32_t *__restrict__ pf_ptr,
+                                                            const int32_t *__restrict__ pf_sum, const int32_t *__restrict__ pf_child,
+                                                            int32_t n_pb, int64_t Bs)
 {
-    constexpr int TM = 32 * RT;
-    constexpr int SUB = K / TM;
-    __shared__ float Qs[TM][33];
-    __shared__ float Ps[4][32][33];
-    const int r = blockIdx.x / SUB, sub = blockIdx.x % SUB;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
-    const int64_t cidx = (int64_t)blockIdx.y * 128 + wave * 32;         // column in the flattened child list
-    const int j = (int)(cidx / K), c0 = (int)(cidx % K);
-    int32_t ns = 0, ps = 0;
-    if (j < width) { ns = nbr[(int64_t)r * width + j]; ps = par[(int64_t)r * width + j]; }
-    const bool valid = ps != 0;
-    const int32_t ms = ids[r];
-    const float *mxrow = nfmax + (int64_t)(ms / K) * Bs;
-    const float *Rs = R + (int64_t)(ms / K) * Bs, *Rc = R + (int64_t)(ns / K) * Bs;
+    constexpr int TMW = 32 * RT, TNW = 32 * CT;
+    constexpr int TPB = (K / TMW) * (K / TNW);                          // wave tiles per parameter block
+    constexpr int LD = 36;                                              // LDS row stride: 16-byte rows, b128 reads conflict-free
+    constexpr int NA4 = TMW * 8 / 64, NB4 = TNW * 8 / 64;               // 16-byte loads per lane per chunk
+    __shared__ float lds[4 * (TMW + TNW) * LD];
 
-    floatx16 acc[RT];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
+    const int64_t tile = (int64_t)blockIdx.x * 4 + wave;
+    const int pidx = (int)(tile / TPB), tin = (int)(tile % TPB);
+    if (pidx >= n_pb) return;                                           // wave-uniform; no workgroup barrier below
+    const int r0 = (tin / (K / TNW)) * TMW, c0 = (tin % (K / TNW)) * TNW;
+    const int32_t pb = pf_pb[pidx];
+    const int i0 = pf_ptr[pidx], i1 = pf_ptr[pidx + 1];
+    float *Qs = lds + wave * (TMW + TNW) * LD, *Ps = Qs + TMW * LD;
+    const int srow = lane >> 3, sc4 = (lane & 7) * 4;                   // staging: 8 lanes x 16 bytes per row of 32 samples
+
+    floatx16 acc[RT][CT];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[rt][e] = 0.0f;
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[rt][ct][e] = 0.0f;
 
-    for (int64_t b0 = 0; b0 < Bs; b0 += 32) {
-        __syncthreads();
-        for (int t = threadIdx.x; t < TM * 8; t += 256) {
-            const int row = t >> 3, c4 = t & 7;
-            const float4 nf = *reinterpret_cast<const float4 *>(N + (int64_t)(ms + sub * TM + row) * Bs + b0 + c4 * 4);
-            const float4 mx = *reinterpret_cast<const float4 *>(mxrow + b0 + c4 * 4);
-            Qs[row][c4 * 4 + 0] = mx.x > PC_NEG_INF ? __expf(nf.x - mx.x + PC_SPLIT) : 0.0f;
-            Qs[row][c4 * 4 + 1] = mx.y > PC_NEG_INF ? __expf(nf.y - mx.y + PC_SPLIT) : 0.0f;
-            Qs[row][c4 * 4 + 2] = mx.z > PC_NEG_INF ? __expf(nf.z - mx.z + PC_SPLIT) : 0.0f;
-            Qs[row][c4 * 4 + 3] = mx.w > PC_NEG_INF ? __expf(nf.w - mx.w + PC_SPLIT) : 0.0f;
-        }
-        if (valid) {
+    const int chunks_per_inst = (int)(Bs / 32);
+    const int n_chunks = (i1 - i0) * chunks_per_inst;
+    floatx4 nf_next[NA4], lc_next[NB4], mx_next, rs_next, rc_next;
+
+#define PC_ISSUE(C)                                                                                                   \
+    do {                                                                                                              \
+        const int inst_ = i0 + (C) / chunks_per_inst;                                                                 \
+        const int64_t b0_ = (int64_t)((C) % chunks_per_inst) * 32 + sc4;                                              \
+        const int32_t ms_ = pf_sum[inst_], ns_ = pf_child[inst_];                                                     \
+        const float *np_ = N + (int64_t)(ms_ + r0 + srow) * Bs + b0_;                                                 \
+        const float *lp_ = l + (int64_t)(ns_ + c0 + srow) * Bs + b0_;                                                 \
+        _Pragma("unroll") for (int i = 0; i < NA4; ++i) nf_next[i] = *reinterpret_cast<const floatx4 *>(np_ + (int64_t)(8 * i) * Bs); \
+        _Pragma("unroll") for (int i = 0; i < NB4; ++i) lc_next[i] = *reinterpret_cast<const floatx4 *>(lp_ + (int64_t)(8 * i) * Bs); \
+        mx_next = *reinterpret_cast<const floatx4 *>(nfmax + (int64_t)(ms_ / K) * Bs + b0_);                          \
+        rs_next = *reinterpret_cast<const floatx4 *>(R + (int64_t)(ms_ / K) * Bs + b0_);                              \
+        rc_next = *reinterpret_cast<const floatx4 *>(R + (int64_t)(ns_ / K) * Bs + b0_);                              \
+    } while (0)
+
+    if (n_chunks > 0) PC_ISSUE(0);
+    for (int c = 0; c < n_chunks; ++c) {
+        // exponentials of the fetched chunk, staged in the wave's LDS tiles
+        floatx4 qa, qb;                                                 // per-sample shifts in log2 units
 #pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                const int row = it * 8 + (lane >> 3), c4 = lane & 7;
-                const float4 lc = *reinterpret_cast<const float4 *>(l + (int64_t)(ns + c0 + row) * Bs + b0 + c4 * 4);
-                float4 mx = *reinterpret_cast<const float4 *>(mxrow + b0 + c4 * 4);
-                const float4 rs = *reinterpret_cast<const float4 *>(Rs + b0 + c4 * 4);
-                const float4 rc = *reinterpret_cast<const float4 *>(Rc + b0 + c4 * 4);
-                mx.x += rc.x - rs.x; mx.y += rc.y - rs.y; mx.z += rc.z - rs.z; mx.w += rc.w - rs.w;
-                Ps[wave][row][c4 * 4 + 0] = mx.x > PC_NEG_INF ? __expf(fminf(lc.x + mx.x - PC_SPLIT, PC_SPLIT_CAP)) : 0.0f;
-                Ps[wave][row][c4 * 4 + 1] = mx.y > PC_NEG_INF ? __expf(fminf(lc.y + mx.y - PC_SPLIT, PC_SPLIT_CAP)) : 0.0f;
-                Ps[wave][row][c4 * 4 + 2] = mx.z > PC_NEG_INF ? __expf(fminf(lc.z + mx.z - PC_SPLIT, PC_SPLIT_CAP)) : 0.0f;
-                Ps[wave][row][c4 * 4 + 3] = mx.w > PC_NEG_INF ? __expf(fminf(lc.w + mx.w - PC_SPLIT, PC_SPLIT_CAP)) : 0.0f;
-            }
+        for (int e = 0; e < 4; ++e) {
+            const bool live = mx_next[e] > PC_NEG_INF;
+            qa[e] = live ? (PC_SPLIT - mx_next[e]) * PC_LOG2E : PC_NEG_INF;              // dead sample: both factors 0
+            qb[e] = live ? (mx_next[e] + (rc_next[e] - rs_next[e]) - PC_SPLIT) * PC_LOG2E : PC_NEG_INF;
         }
-        __syncthreads();
-        if (valid) {
 #pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const float p = Ps[wave][l32][2 * q + half];
+        for (int i = 0; i < NA4; ++i) {
+            floatx4 q;
 #pragma unroll
-                for (int rt = 0; rt < RT; ++rt)
-                    acc[rt] = __builtin_amdgcn_mfma_f32_32x32x2f32(Qs[rt * 32 + l32][2 * q + half], p, acc[rt], 0, 0, 0);
-            }
+            for (int e = 0; e < 4; ++e) q[e] = __builtin_amdgcn_exp2f(fmaf(nf_next[i][e], PC_LOG2E, qa[e]));
+            *reinterpret_cast<floatx4 *>(Qs + (8 * i + srow) * LD + sc4) = q;
         }
-    }
-    if (valid) {
+#pragma unroll
+        for (int i = 0; i < NB4; ++i) {
+            floatx4 p;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                p[e] = __builtin_amdgcn_exp2f(fminf(fmaf(lc_next[i][e], PC_LOG2E, qb[e]), PC_SPLIT_CAP * PC_LOG2E));
+            *reinterpret_cast<floatx4 *>(Ps + (8 * i + srow) * LD + sc4) = p;
+        }
+        if (c + 1 < n_chunks) PC_ISSUE(c + 1);
+
+        // operands of the whole chunk into registers (LDS operations of one wave complete in order)
+        float areg[16][RT], breg[16][CT];
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int i = sub * TM + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
-                const int64_t at = (int64_t)ps + (int64_t)i * K + c0 + l32;
-                const float g = theta[at] * acc[rt][e];
-                if (atomic) { if (g != 0.0f) atomicAdd(G + at, g); }
-                else G[at] += g;
+            for (int g = 0; g < 4; ++g) {
+                const floatx4 a4 = *reinterpret_cast<const floatx4 *>(Qs + (rt * 32 + l32) * LD + 8 * g + 4 * half);
+                areg[4 * g + 0][rt] = a4[0]; areg[4 * g + 1][rt] = a4[1]; areg[4 * g + 2][rt] = a4[2]; areg[4 * g + 3][rt] = a4[3];
             }
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const floatx4 b4 = *reinterpret_cast<const floatx4 *>(Ps + (ct * 32 + l32) * LD + 8 * g + 4 * half);
+                breg[4 * g + 0][ct] = b4[0]; breg[4 * g + 1][ct] = b4[1]; breg[4 * g + 2][ct] = b4[2]; breg[4 * g + 3][ct] = b4[3];
+            }
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct)
+                    acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(areg[q][rt], breg[q][ct], acc[rt][ct], 0, 0, 0);
     }
+#undef PC_ISSUE
+
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int i = r0 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                const int64_t at = (int64_t)pb + (int64_t)i * K + c0 + ct * 32 + l32;
+                const float th = theta[at];
+                if (th > 0.0f) G[at] += th * acc[rt][ct][e];          // theta = 0: no flow (and never 0 * inf)
+            }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -785,15 +833,6 @@ static bool g_force_generic = false;
 void set_force_generic(bool on) { g_force_generic = on; }
 static inline bool use_mfma(int32_t K) { return !g_force_generic && (K == 32 || K == 64 || K == 128); }
 
-// rows-per-tile: the largest tile that still gives the chip about two workgroups per compute unit
-static int pick_rt(int32_t K, int64_t tiles32, int64_t col_tiles)
-{
-    int rt = K / 32;
-    if (rt > 4) rt = 4;
-    while (rt > 1 && (tiles32 / rt) * col_tiles < 512) rt >>= 1;
-    return rt;
-}
-
 void launch_fill(float *p, int64_t n, float v, hipStream_t s)
 {
     Timed timed(KC_MISC, s);
@@ -870,16 +909,6 @@ void launch_lognf(const float *l, const float *F, float *N, float *nfmax, const 
     hipLaunchKernelGGL(k_lognf, grid, dim3(256), 0, s, l, F, N, nfmax, blk_ids, K, Bs);
 }
 
-#define PC_DISPATCH_K_RT(KERNEL, K, RT, ...)                                                              \
-    do {                                                                                                  \
-        if (K == 32) hipLaunchKernelGGL((KERNEL<32, 1>), __VA_ARGS__);                                    \
-        else if (K == 64 && RT == 1) hipLaunchKernelGGL((KERNEL<64, 1>), __VA_ARGS__);                    \
-        else if (K == 64) hipLaunchKernelGGL((KERNEL<64, 2>), __VA_ARGS__);                               \
-        else if (K == 128 && RT == 1) hipLaunchKernelGGL((KERNEL<128, 1>), __VA_ARGS__);                  \
-        else if (K == 128 && RT == 2) hipLaunchKernelGGL((KERNEL<128, 2>), __VA_ARGS__);                  \
-        else hipLaunchKernelGGL((KERNEL<128, 4>), __VA_ARGS__);                                           \
-    } while (0)
-
 // forward / backward-to-children: (K, rows per wave tile / 32, waves sharing one tile)
 #define PC_SUM_CASE(KK, RR, SS, BWD, ...)                                                                  \
     if (K == KK && rt == RR && split == SS) { hipLaunchKernelGGL((k_sum_mfma<KK, RR, SS, BWD>), __VA_ARGS__); break; }
@@ -944,22 +973,32 @@ void launch_sum_bwd_child(const float *theta, const float *l, const float *R, co
     }
 }
 
-void launch_sum_bwd_param(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *G,
-                          const GroupDev &g, int32_t K, int64_t Bs, int32_t B, hipStream_t s)
+void launch_sum_bwd_param_generic(const float *theta, const float *l, const float *R, const float *N, float *G,
+                                  const GroupDev &g, int32_t K, int64_t Bs, int32_t B, hipStream_t s)
 {
-    Timed timed(KC_SUM_BWD_PARAM, s);
     if (g.n_rows == 0) return;
-    const int atomic = g.tied ? 1 : 0;
-    if (use_mfma(K)) {
-        const int64_t col_tiles = ((int64_t)g.width * K + 127) / 128;
-        const int rt = pick_rt(K, (int64_t)g.n_rows * (K / 32), col_tiles);
-        dim3 grid((unsigned)(g.n_rows * (K / (32 * rt))), (unsigned)col_tiles);
-        PC_DISPATCH_K_RT(k_sum_bwd_param_mfma, K, rt, grid, dim3(256), 0, s, theta, l, R, N, nfmax, G, g.ids, g.nbr, g.par,
-                         g.width, Bs, atomic);
+    Timed timed(KC_SUM_BWD_PARAM, s);
+    const int64_t items = (int64_t)g.n_rows * g.width * K * K;
+    hipLaunchKernelGGL(k_sum_bwd_param_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, l, R, N, G, g.ids, g.nbr,
+                       g.par, g.n_rows, g.width, K, Bs, B, g.tied ? 1 : 0);
+}
+
+bool param_flow_uses_mfma(int32_t K) { return use_mfma(K); }
+
+void launch_param_flow(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *G,
+                       const ParamFlowDev &pf, int32_t K, int64_t Bs, hipStream_t s)
+{
+    if (pf.n_pb == 0) return;
+    Timed timed(KC_SUM_BWD_PARAM, s);
+    if (K == 32) {
+        hipLaunchKernelGGL((k_param_flow_mfma<32, 1, 1>), dim3((unsigned)((pf.n_pb + 3) / 4)), dim3(256), 0, s, theta, l, R, N,
+                           nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, Bs);
+    } else if (K == 64) {
+        hipLaunchKernelGGL((k_param_flow_mfma<64, 2, 2>), dim3((unsigned)((pf.n_pb + 3) / 4)), dim3(256), 0, s, theta, l, R, N,
+                           nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, Bs);
     } else {
-        const int64_t items = (int64_t)g.n_rows * g.width * K * K;
-        hipLaunchKernelGGL(k_sum_bwd_param_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, l, R, N, G, g.ids, g.nbr,
-                           g.par, g.n_rows, g.width, K, Bs, B, atomic);
+        hipLaunchKernelGGL((k_param_flow_mfma<128, 2, 2>), dim3((unsigned)pf.n_pb), dim3(256), 0, s, theta, l, R, N, nfmax, G,
+                           pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, Bs);
     }
 }
 
