@@ -38,10 +38,11 @@ static pc_status upload(pc_circuit *c, hipStream_t stream)
     for (auto &layer : c->layers) {
         add(&layer.d_blk_ids, layer.blk_ids);
         for (auto *groups : {&layer.fwd, &layer.bwd})
-            for (auto &g : *groups) { add(&g.d_ids, g.ids); add(&g.d_nbr, g.nbr); add(&g.d_par, g.par); }
+            for (auto &g : *groups) { add(&g.d_ids, g.ids); add(&g.d_nbr, g.nbr); add(&g.d_par, g.par); add(&g.d_aux, g.aux); }
     }
     add(&c->d_pb_group, c->pb_group); add(&c->d_pb_rows, c->pb_rows); add(&c->d_pb_cols, c->pb_cols);
     add(&c->d_group_nch, c->group_nch);
+    add(&c->d_init_ids, c->init_ids);
     add(&c->d_pf_pb, c->pf_pb); add(&c->d_pf_ptr, c->pf_ptr); add(&c->d_pf_sum, c->pf_sum); add(&c->d_pf_child, c->pf_child);
     const size_t zrow_off = reserve((size_t)c->n_em_groups * c->K + 1);
     const size_t ztab_off = reserve((size_t)c->n_tables * c->K + 1);
@@ -67,7 +68,7 @@ struct ProfScope {                                   // installs the circuit's p
 static const char *const kClassNames[KC_COUNT] = {"misc", "input_fwd", "prod_fwd", "sum_fwd", "lognf", "sum_bwd_child",
                                                   "sum_bwd_param", "prod_bwd", "input_bwd", "em"};
 
-static GroupDev dev(const GroupTab &g) { return GroupDev{g.n_rows, g.width, g.d_ids, g.d_nbr, g.d_par, g.tied_in_group}; }
+static GroupDev dev(const GroupTab &g) { return GroupDev{g.n_rows, g.width, g.d_ids, g.d_nbr, g.d_par, g.tied_in_group, g.d_aux}; }
 
 struct Ws {
     int64_t Bs;
@@ -266,16 +267,15 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
     // every sum layer stay valid until then); other block sizes: layer by layer
     const bool batched_params = param_flow_uses_mfma(K);
     launch_fill(F, rows * w.Bs, 0.0f, s);
-    launch_root_flow(l, F, (int64_t)(c->root_block + 1) * K, w.Bs, B, s);
+    launch_init_flows(l, F, N, nfmax, c->d_init_ids, (int32_t)c->init_ids.size(), (c->root_block + 1) * K, K, w.Bs, B, s);
     for (size_t li = c->layers.size(); li-- > 0;) {
         const LayerTab &L = c->layers[li];
         if (L.kind == KIND_SUM) {
-            launch_lognf(l, F, N, nfmax, L.d_blk_ids, (int32_t)L.blk_ids.size(), K, w.Bs, s);
             for (const GroupTab &g : L.bwd) launch_sum_bwd_child(theta, l, R, N, nfmax, F, dev(g), K, w.Bs, s);
             if (theta_flow && !batched_params)
                 for (const GroupTab &g : L.fwd) launch_sum_bwd_param_generic(theta, l, R, N, theta_flow, dev(g), K, w.Bs, B, s);
         } else if (L.kind == KIND_PRODUCT) {
-            for (const GroupTab &g : L.bwd) launch_prod_bwd(F, dev(g), K, w.Bs, s);
+            for (const GroupTab &g : L.bwd) launch_prod_bwd(l, F, N, nfmax, dev(g), K, w.Bs, s);
         } else if (table_flow) {
             launch_input_bwd(F, xT, dev(L.fwd[0]), K, c->n_cats, w.Bs, table_flow, s);
         }

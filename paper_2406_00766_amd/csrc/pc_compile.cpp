@@ -205,6 +205,18 @@ pc_status compile_host(const pc_dag *d, pc_circuit *c)
     }
     if (done != n) return fail(PC_ERR_CYCLE, "the block graph has a cycle");
 
+    if (par_ptr[d->root_block + 1] != par_ptr[d->root_block]) return fail(PC_ERR_ARG, "the root block must not have parents");
+    // per block: the smallest depth among its parents (the last layer of the backward sweep that feeds it)
+    std::vector<int32_t> last_parent_depth(n, -1);
+    for (int32_t u = 0; u < n; ++u)
+        for (int32_t k = par_ptr[u]; k < par_ptr[u + 1]; ++k) {
+            const int32_t dp = depth[par_of[k]];
+            if (last_parent_depth[u] < 0 || dp < last_parent_depth[u]) last_parent_depth[u] = dp;
+        }
+    c->init_ids.clear();
+    for (int32_t u = 0; u < n; ++u)
+        if (d->type[u] == KIND_SUM && last_parent_depth[u] < 0) c->init_ids.push_back((u + 1) * K);
+
     c->K = K; c->n_blocks = n; c->root_block = d->root_block; c->n_param_blocks = d->n_param_blocks;
     c->n_vars = d->n_vars; c->n_cats = d->n_cats; c->n_tables = d->n_tables;
     c->layers.clear();
@@ -231,6 +243,9 @@ pc_status compile_host(const pc_dag *d, pc_circuit *c)
                 g.nbr.push_back(d->in_var[u]);
                 g.par.push_back(d->in_table[u]);
             }
+            std::vector<int32_t> tabs = g.par;                          // a table shared by several blocks: flows collide
+            std::sort(tabs.begin(), tabs.end());
+            g.tied_in_group = std::adjacent_find(tabs.begin(), tabs.end()) != tabs.end();
             layer.fwd.push_back(std::move(g));
         } else {
             std::vector<Row> fwd_rows;
@@ -254,6 +269,12 @@ pc_status compile_host(const pc_dag *d, pc_circuit *c)
             if (st != PC_OK) return st;
             st = build_groups(bwd_rows, d->max_groups, d->tol_permille, layer.bwd);
             if (st != PC_OK) return st;
+            if (layer.kind == KIND_PRODUCT)
+                for (GroupTab &gt : layer.bwd)
+                    for (int32_t id : gt.ids) {
+                        const int32_t ch = id / K - 1;
+                        gt.aux.push_back(d->type[ch] == KIND_SUM && last_parent_depth[ch] == layer.depth ? 1 : 0);
+                    }
         }
         c->layers.push_back(std::move(layer));
     }

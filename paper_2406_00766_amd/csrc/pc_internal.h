@@ -14,7 +14,8 @@ enum : int { KIND_INPUT = 0, KIND_PRODUCT = 1, KIND_SUM = 2 };
 struct GroupTab {
     int32_t n_rows = 0, width = 0;
     std::vector<int32_t> ids, nbr, par;              // host copies
-    int32_t *d_ids = nullptr, *d_nbr = nullptr, *d_par = nullptr;
+    std::vector<int32_t> aux;                        // per row; product backward groups: flow final in this layer
+    int32_t *d_ids = nullptr, *d_nbr = nullptr, *d_par = nullptr, *d_aux = nullptr;
     bool tied_in_group = false;                       // a parameter block occurs twice: flows need atomics
 };
 
@@ -42,6 +43,10 @@ struct pc_circuit {
     // parameter-centric flow tables: parameter block offset -> CSR list of (sum block, child block) node offsets
     std::vector<int32_t> pf_pb, pf_ptr, pf_sum, pf_child;
     int32_t *d_pf_pb = nullptr, *d_pf_ptr = nullptr, *d_pf_sum = nullptr, *d_pf_child = nullptr;
+
+    // sum blocks whose flow no product layer finalises: the root block and sum blocks without parents
+    std::vector<int32_t> init_ids;
+    int32_t *d_init_ids = nullptr;
 
     void *d_arena = nullptr;                          // one device allocation behind every d_* above
     size_t arena_bytes = 0;

@@ -11,6 +11,7 @@ struct GroupDev {            // device view of one table group
     int32_t n_rows, width;
     const int32_t *ids, *nbr, *par;
     bool tied;
+    const int32_t *aux;      // product-layer backward groups: 1 where the row's flow becomes final in this layer
 };
 
 struct ParamFlowDev {        // parameter blocks with the (sum block, child block) pairs that use them
@@ -47,15 +48,14 @@ void launch_prepare_x(const int32_t *x, const uint8_t *mask, int32_t B, int32_t 
                       int32_t *xT, hipStream_t s);
 void launch_readout(const float *l, const float *R, int64_t root_row, int64_t root_blk, int64_t Bs, int32_t B, float *ll,
                     hipStream_t s);
-void launch_root_flow(const float *l, float *F, int64_t root_row, int64_t Bs, int32_t B, hipStream_t s);
+void launch_init_flows(const float *l, float *F, float *N, float *nfmax, const int32_t *blk_ids, int32_t n_blk,
+                       int32_t root_id, int32_t K, int64_t Bs, int32_t B, hipStream_t s);
 void launch_input_fwd(const float *tables, const int32_t *xT, const GroupDev &g, int32_t K, int32_t n_cats, int64_t Bs,
                       float *l, hipStream_t s);
 void launch_input_bwd(const float *F, const int32_t *xT, const GroupDev &g, int32_t K, int32_t n_cats, int64_t Bs,
                       float *table_flow, hipStream_t s);
 void launch_prod_fwd(float *l, float *R, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s);
-void launch_prod_bwd(float *F, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s);
-void launch_lognf(const float *l, const float *F, float *N, float *nfmax, const int32_t *blk_ids, int32_t n_blk,
-                  int32_t K, int64_t Bs, hipStream_t s);
+void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s);
 void launch_sum_fwd(const float *theta, float *l, float *R, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s);
 void launch_sum_bwd_child(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *F,
                           const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s);

@@ -71,13 +71,6 @@ __global__ void k_readout(const float *__restrict__ l, const float *__restrict__
     if (b < B) ll[b] = R[root_blk * Bs + b] + l[root_row * Bs + b];
 }
 
-// F_root = 1 (Def. 2) for real samples of non-zero probability, 0 otherwise.
-__global__ void k_root_flow(const float *__restrict__ l, float *__restrict__ F, int64_t root_row, int64_t Bs, int32_t B)
-{
-    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (b < Bs) F[root_row * Bs + b] = (b < B && l[root_row * Bs + b] > PC_NEG_INF) ? 1.0f : 0.0f;
-}
-
 // ------------------------------------------------------------------------------------------
 // input layer (categorical): l[n,b] = log table[t][x_b,v][k]
 // ------------------------------------------------------------------------------------------
@@ -110,150 +103,251 @@ __global__ __launch_bounds__(256) void k_input_fwd(const float *__restrict__ tab
     }
 }
 
-// table_flow[t][x_b,v][k] += F[n,b] for observed variables
-__global__ __launch_bounds__(256) void k_input_bwd(const float *__restrict__ F, const int32_t *__restrict__ xT,
-                                                   const int32_t *__restrict__ ids, const int32_t *__restrict__ var,
-                                                   const int32_t *__restrict__ tab, int32_t K, int32_t n_cats,
-                                                   int64_t Bs, float *__restrict__ table_flow)
+// table_flow[t][x_b,v][k] += F[n,b] for observed variables.
+// Both variants first bring a [K rows x 64 samples] tile of the flow buffer into LDS with coalesced 16-byte
+// loads along the batch, then turn it: a group of lanes owns consecutive nodes k of ONE sample, so every add
+// touches consecutive floats of one table row.
+//   hist : one workgroup per input block; the adds go into an LDS copy of the block's [n_cats x K] table slice
+//          (LDS float atomics), flushed once with coalesced read-modify-writes (atomics only if the table is
+//          shared by several blocks).  Used when the slice fits in LDS.
+//   direct: one workgroup per (block, 64 samples); global float atomics, 64 consecutive floats per wave op.
+__device__ inline void input_bwd_load_tile(const float *__restrict__ F, const int32_t *__restrict__ xT, int32_t id,
+                                           int32_t var, int32_t K, int64_t Bs, int64_t b0, float *tile, int *cats)
 {
+    for (int idx = threadIdx.x; idx < K * 16; idx += 256) {
+        const int row = idx >> 4, c4 = (idx & 15) * 4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (b0 + c4 < Bs) v = *reinterpret_cast<const float4 *>(F + (int64_t)(id + row) * Bs + b0 + c4);
+        float *dst = tile + row * 65 + c4;
+        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+    }
+    if (threadIdx.x < 64) cats[threadIdx.x] = (b0 + threadIdx.x < Bs) ? xT[(int64_t)var * Bs + b0 + threadIdx.x] : -1;
+}
+
+__global__ __launch_bounds__(256) void k_input_bwd_hist(const float *__restrict__ F, const int32_t *__restrict__ xT,
+                                                        const int32_t *__restrict__ ids, const int32_t *__restrict__ var,
+                                                        const int32_t *__restrict__ tab, int32_t K, int32_t n_cats,
+                                                        int64_t Bs, float *__restrict__ table_flow, int lps, int atomic_flush)
+{
+    extern __shared__ float smem[];
+    float *hist = smem, *tile = smem + (size_t)n_cats * K;
+    int *cats = reinterpret_cast<int *>(tile + K * 65);
     const int u = blockIdx.x;
-    const int64_t b = (int64_t)blockIdx.y * 256 + threadIdx.x;
-    if (b >= Bs) return;
-    const int32_t xv = xT[(int64_t)var[u] * Bs + b];
-    if (xv < 0) return;
-    const float *in = F + (int64_t)ids[u] * Bs + b;
-    float *row = table_flow + ((int64_t)tab[u] * n_cats + xv) * K;
-    for (int k = 0; k < K; ++k) {
-        const float f = in[(int64_t)k * Bs];
-        if (f != 0.0f) atomicAdd(row + k, f);
+    const int32_t id = ids[u];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int spi = 64 / lps;                                          // samples per wave instruction
+    const int kl = lane % lps, sl = lane / lps;
+    for (int i = threadIdx.x; i < n_cats * K; i += 256) hist[i] = 0.0f;
+    for (int64_t b0 = 0; b0 < Bs; b0 += 64) {
+        __syncthreads();
+        input_bwd_load_tile(F, xT, id, var[u], K, Bs, b0, tile, cats);
+        __syncthreads();
+        for (int s = wave * spi + sl; s < 64; s += 4 * spi) {
+            const int cat = cats[s];
+            if (cat < 0) continue;
+            for (int k = kl; k < K; k += lps) {
+                const float f = tile[k * 65 + s];
+                if (f != 0.0f) atomicAdd(hist + cat * K + k, f);
+            }
+        }
+    }
+    __syncthreads();
+    float *dst = table_flow + (int64_t)tab[u] * n_cats * K;
+    for (int i = threadIdx.x; i < n_cats * K; i += 256) {
+        const float v = hist[i];
+        if (v != 0.0f) { if (atomic_flush) atomicAdd(dst + i, v); else dst[i] += v; }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_input_bwd_direct(const float *__restrict__ F, const int32_t *__restrict__ xT,
+                                                          const int32_t *__restrict__ ids, const int32_t *__restrict__ var,
+                                                          const int32_t *__restrict__ tab, int32_t K, int32_t n_cats,
+                                                          int64_t Bs, float *__restrict__ table_flow, int lps)
+{
+    extern __shared__ float smem[];
+    float *tile = smem;
+    int *cats = reinterpret_cast<int *>(tile + K * 65);
+    const int u = blockIdx.x;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int spi = 64 / lps;
+    const int kl = lane % lps, sl = lane / lps;
+    input_bwd_load_tile(F, xT, ids[u], var[u], K, Bs, (int64_t)blockIdx.y * 64, tile, cats);
+    __syncthreads();
+    float *base = table_flow + (int64_t)tab[u] * n_cats * K;
+    for (int s = wave * spi + sl; s < 64; s += 4 * spi) {
+        const int cat = cats[s];
+        if (cat < 0) continue;
+        for (int k = kl; k < K; k += lps) {
+            const float f = tile[k * 65 + s];
+            if (f != 0.0f) atomicAdd(base + (int64_t)cat * K + k, f);
+        }
     }
 }
 
 // ------------------------------------------------------------------------------------------
 // product layers: forward adds child log-probs (Sec. 3); backward adds parent flows (Def. 2)
 // ------------------------------------------------------------------------------------------
-// One workgroup = one product block x 64*V sample columns; thread (rg, lane) owns rows rg, rg+4, ...
-// of V adjacent columns.  s = sum of the children's residuals; the column maximum over the K rows is
-// rounded to an integer and moved into R.
-template <int V>
+// Block-wise product kernels.  Workgroup = one node block x 64 sample columns; thread (rg, cl) owns rows
+// rg, rg+16, ... of 4 adjacent columns (16-byte accesses along the batch), so a K-row block is K/16 rows
+// deep per thread and all its loads are independent.  Column maxima over the K rows go through one
+// shuffle stage (4 row groups per wave) and one LDS stage (4 waves).
+__device__ inline void block_col_max(float (&mx)[4], float (*red)[64], int wave, int cl)
+{
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        mx[v] = fmaxf(mx[v], __shfl_xor(mx[v], 16));
+        mx[v] = fmaxf(mx[v], __shfl_xor(mx[v], 32));
+    }
+    if ((threadIdx.x & 63) < 16) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[wave][cl * 4 + v] = mx[v];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int c = cl * 4 + v;
+        mx[v] = fmaxf(fmaxf(red[0][c], red[1][c]), fmaxf(red[2][c], red[3][c]));
+    }
+}
+
+// forward (Sec. 3): s = sum of the children's residuals; the column maximum over the K rows is rounded to an
+// integer and moved into R
 __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *__restrict__ R,
                                                   const int32_t *__restrict__ ids, const int32_t *__restrict__ nbr,
                                                   int32_t width, int32_t K, int64_t Bs)
 {
-    constexpr int RPT = 32;                                            // rows per thread (K <= 128)
-    __shared__ float red[4][64 * V];
+    constexpr int RPT = 8;                                             // rows per thread (K <= 128)
+    __shared__ float red[4][64];
     const int r = blockIdx.x;
-    const int rg = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t b = ((int64_t)blockIdx.y * 64 + lane) * V;
-    const bool in = b < Bs;
-    float s[RPT][V];
-    float mx[V], rsum[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) { mx[v] = PC_NEG_INF; rsum[v] = 0.0f; }
+    const int rg = threadIdx.x >> 4, cl = threadIdx.x & 15, wave = threadIdx.x >> 6;
+    const int64_t b = (int64_t)blockIdx.y * 64 + cl * 4;
+    const bool in = b < Bs;                                            // Bs is a multiple of 32: b..b+3 all inside
     const int32_t *row_nbr = nbr + (int64_t)r * width;
+    float4 s[RPT];
+    float mx[4] = {PC_NEG_INF, PC_NEG_INF, PC_NEG_INF, PC_NEG_INF};
+    float4 rsum = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) s[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (in) {
+        for (int j = 0; j < width; ++j) {
+            const int32_t ch = row_nbr[j];
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) {
+                const int k = rg + 16 * i;
+                if (k < K) {
+                    const float4 t = *reinterpret_cast<const float4 *>(l + (int64_t)(ch + k) * Bs + b);
+                    s[i].x += t.x; s[i].y += t.y; s[i].z += t.z; s[i].w += t.w;
+                }
+            }
+            if (rg == 0) {
+                const float4 t = *reinterpret_cast<const float4 *>(R + (int64_t)(ch / K) * Bs + b);
+                rsum.x += t.x; rsum.y += t.y; rsum.z += t.z; rsum.w += t.w;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < RPT; ++i)
+            if (rg + 16 * i < K) {
+                mx[0] = fmaxf(mx[0], s[i].x); mx[1] = fmaxf(mx[1], s[i].y);
+                mx[2] = fmaxf(mx[2], s[i].z); mx[3] = fmaxf(mx[3], s[i].w);
+            }
+    }
+    block_col_max(mx, red, wave, cl);
+    if (!in) return;
+    float sh[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) sh[v] = mx[v] > PC_NEG_INF ? rintf(mx[v]) : 0.0f;
+    const int32_t id = ids[r];
+    if (rg == 0)
+        *reinterpret_cast<float4 *>(R + (int64_t)(id / K) * Bs + b) = make_float4(rsum.x + sh[0], rsum.y + sh[1], rsum.z + sh[2], rsum.w + sh[3]);
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+        const int k = rg + 16 * i;
+        if (k < K)
+            *reinterpret_cast<float4 *>(l + (int64_t)(id + k) * Bs + b) = make_float4(s[i].x - sh[0], s[i].y - sh[1], s[i].z - sh[2], s[i].w - sh[3]);
+    }
+}
+
+// backward (Def. 2): rows = child blocks (sum / input blocks), neighbours = their product parents in this layer;
+// F_child += sum of the parents' flows.  Where this layer is the last one that feeds a SUM block (fin != 0)
+// its flow is final, so log_nf = log F - l (Alg. 3 / 4) and its column maximum per block are produced here.
+__global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, float *__restrict__ F, float *__restrict__ N,
+                                                  float *__restrict__ nfmax, const int32_t *__restrict__ ids,
+                                                  const int32_t *__restrict__ nbr, const int32_t *__restrict__ fin,
+                                                  int32_t width, int32_t K, int64_t Bs)
+{
+    constexpr int RPT = 8;
+    __shared__ float red[4][64];
+    const int r = blockIdx.x;
+    const int rg = threadIdx.x >> 4, cl = threadIdx.x & 15, wave = threadIdx.x >> 6;
+    const int64_t b = (int64_t)blockIdx.y * 64 + cl * 4;
+    const bool in = b < Bs;
+    const int32_t *row_nbr = nbr + (int64_t)r * width;
+    const int32_t id = ids[r];
+    const bool final_flow = fin[r] != 0;                               // uniform over the workgroup
+    float4 f[RPT];
     if (in) {
 #pragma unroll
         for (int i = 0; i < RPT; ++i) {
-            const int k = rg + 4 * i;
-#pragma unroll
-            for (int v = 0; v < V; ++v) s[i][v] = 0.0f;
-            if (k < K) {
-                for (int j = 0; j < width; ++j) {
-                    const float *src = l + (int64_t)(row_nbr[j] + k) * Bs + b;
-                    if (V == 4) {
-                        const float4 t = *reinterpret_cast<const float4 *>(src);
-                        s[i][0] += t.x; s[i][1 % V] += t.y; s[i][2 % V] += t.z; s[i][3 % V] += t.w;
-                    } else {
-                        s[i][0] += src[0];
-                    }
-                }
-#pragma unroll
-                for (int v = 0; v < V; ++v) mx[v] = fmaxf(mx[v], s[i][v]);
-            }
+            const int k = rg + 16 * i;
+            f[i] = k < K ? *reinterpret_cast<const float4 *>(F + (int64_t)(id + k) * Bs + b) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
-        if (rg == 0)
-            for (int j = 0; j < width; ++j)
-#pragma unroll
-                for (int v = 0; v < V; ++v) rsum[v] += R[(int64_t)(row_nbr[j] / K) * Bs + b + v];
-    }
-#pragma unroll
-    for (int v = 0; v < V; ++v) red[rg][lane * V + v] = mx[v];
-    __syncthreads();
-    if (!in) return;
-    float shift[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) {
-        const int c = lane * V + v;
-        const float m = fmaxf(fmaxf(red[0][c], red[1][c]), fmaxf(red[2][c], red[3][c]));
-        shift[v] = m > PC_NEG_INF ? rintf(m) : 0.0f;
-    }
-    const int32_t id = ids[r];
-    if (rg == 0)
-#pragma unroll
-        for (int v = 0; v < V; ++v) R[(int64_t)(id / K) * Bs + b + v] = rsum[v] + shift[v];
-#pragma unroll
-    for (int i = 0; i < RPT; ++i) {
-        const int k = rg + 4 * i;
-        if (k < K) {
-            float *dst = l + (int64_t)(id + k) * Bs + b;
-            if (V == 4) {
-                *reinterpret_cast<float4 *>(dst) = make_float4(s[i][0] - shift[0], s[i][1 % V] - shift[1 % V],
-                                                               s[i][2 % V] - shift[2 % V], s[i][3 % V] - shift[3 % V]);
-            } else {
-                dst[0] = s[i][0] - shift[0];
-            }
-        }
-    }
-}
-
-// rows = child blocks (sum / input blocks), neighbours = their product parents in this layer
-__global__ __launch_bounds__(256) void k_prod_bwd(float *__restrict__ F, const int32_t *__restrict__ ids,
-                                                  const int32_t *__restrict__ nbr, int32_t n_rows, int32_t width,
-                                                  int32_t K, int64_t Bs)
-{
-    const int64_t b4 = Bs >> 2;
-    const int64_t total = (int64_t)n_rows * K * b4;
-    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t row = t / b4, c = t - row * b4;
-        const int32_t r = (int32_t)(row / K), k = (int32_t)(row - (int64_t)r * K);
-        float4 *dst = reinterpret_cast<float4 *>(F + (int64_t)(ids[r] + k) * Bs + 4 * c);
-        float4 s = *dst;
         for (int j = 0; j < width; ++j) {
-            const int32_t pa = nbr[(int64_t)r * width + j];               // padding -> null block, flow 0
-            const float4 v = *reinterpret_cast<const float4 *>(F + (int64_t)(pa + k) * Bs + 4 * c);
-            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+            const int32_t pa = row_nbr[j];                              // padding -> null block, flow 0
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) {
+                const int k = rg + 16 * i;
+                if (k < K) {
+                    const float4 t = *reinterpret_cast<const float4 *>(F + (int64_t)(pa + k) * Bs + b);
+                    f[i].x += t.x; f[i].y += t.y; f[i].z += t.z; f[i].w += t.w;
+                }
+            }
         }
-        *dst = s;
+#pragma unroll
+        for (int i = 0; i < RPT; ++i) {
+            const int k = rg + 16 * i;
+            if (k < K) *reinterpret_cast<float4 *>(F + (int64_t)(id + k) * Bs + b) = f[i];
+        }
     }
+    if (!final_flow) return;
+    float mx[4] = {PC_NEG_INF, PC_NEG_INF, PC_NEG_INF, PC_NEG_INF};
+    if (in) {
+#pragma unroll
+        for (int i = 0; i < RPT; ++i) {
+            const int k = rg + 16 * i;
+            if (k < K) {
+                const float4 lv = *reinterpret_cast<const float4 *>(l + (int64_t)(id + k) * Bs + b);
+                float4 nf;
+                nf.x = (f[i].x > 0.0f && lv.x > PC_NEG_INF) ? __logf(f[i].x) - lv.x : PC_NEG_INF;
+                nf.y = (f[i].y > 0.0f && lv.y > PC_NEG_INF) ? __logf(f[i].y) - lv.y : PC_NEG_INF;
+                nf.z = (f[i].z > 0.0f && lv.z > PC_NEG_INF) ? __logf(f[i].z) - lv.z : PC_NEG_INF;
+                nf.w = (f[i].w > 0.0f && lv.w > PC_NEG_INF) ? __logf(f[i].w) - lv.w : PC_NEG_INF;
+                *reinterpret_cast<float4 *>(N + (int64_t)(id + k) * Bs + b) = nf;
+                mx[0] = fmaxf(mx[0], nf.x); mx[1] = fmaxf(mx[1], nf.y); mx[2] = fmaxf(mx[2], nf.z); mx[3] = fmaxf(mx[3], nf.w);
+            }
+        }
+    }
+    block_col_max(mx, red, wave, cl);
+    if (in && rg == 0) *reinterpret_cast<float4 *>(nfmax + (int64_t)(id / K) * Bs + b) = make_float4(mx[0], mx[1], mx[2], mx[3]);
 }
 
-// ------------------------------------------------------------------------------------------
-// log_nf = log F - l of the sum nodes of a layer (Alg. 3 / 4) and its per-block column maximum
-// ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_lognf(const float *__restrict__ l, const float *__restrict__ F,
-                                               float *__restrict__ N, float *__restrict__ nfmax,
-                                               const int32_t *__restrict__ blk_ids, int32_t K, int64_t Bs)
+// Sum blocks that no product layer finalises: the root block (flow 1 on node 0 of real samples with non-zero
+// probability, Def. 2) and sum blocks without parents (flow 0).  One workgroup per listed block and 256 columns.
+__global__ __launch_bounds__(256) void k_init_flows(const float *__restrict__ l, float *__restrict__ F, float *__restrict__ N,
+                                                    float *__restrict__ nfmax, const int32_t *__restrict__ blk_ids,
+                                                    int32_t root_id, int32_t K, int64_t Bs, int32_t B)
 {
-    __shared__ float red[4][64];
     const int32_t id = blk_ids[blockIdx.x];
-    const int rg = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t b = (int64_t)blockIdx.y * 64 + lane;
-    float mx = PC_NEG_INF;
-    if (b < Bs) {
-        for (int k = rg; k < K; k += 4) {
-            const int64_t at = (int64_t)(id + k) * Bs + b;
-            const float f = F[at], lv = l[at];
-            const float nf = (f > 0.0f && lv > PC_NEG_INF) ? __logf(f) - lv : PC_NEG_INF;
-            N[at] = nf;
-            mx = fmaxf(mx, nf);
-        }
+    const int64_t b = (int64_t)blockIdx.y * 256 + threadIdx.x;
+    if (b >= Bs) return;
+    float top = PC_NEG_INF;
+    if (id == root_id) {
+        const float lv = l[(int64_t)id * Bs + b];
+        const bool live = b < B && lv > PC_NEG_INF;
+        F[(int64_t)id * Bs + b] = live ? 1.0f : 0.0f;
+        top = live ? -lv : PC_NEG_INF;
     }
-    red[rg][lane] = mx;
-    __syncthreads();
-    if (rg == 0 && b < Bs) {
-        mx = fmaxf(fmaxf(red[0][lane], red[1][lane]), fmaxf(red[2][lane], red[3][lane]));
-        nfmax[(int64_t)(id / K) * Bs + b] = mx;
-    }
+    for (int k = 0; k < K; ++k) N[(int64_t)(id + k) * Bs + b] = k == 0 ? top : PC_NEG_INF;
+    nfmax[(int64_t)(id / K) * Bs + b] = top;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -855,10 +949,13 @@ void launch_readout(const float *l, const float *R, int64_t root_row, int64_t ro
     hipLaunchKernelGGL(k_readout, dim3((B + 255) / 256), dim3(256), 0, s, l, R, root_row, root_blk, Bs, B, ll);
 }
 
-void launch_root_flow(const float *l, float *F, int64_t root_row, int64_t Bs, int32_t B, hipStream_t s)
+void launch_init_flows(const float *l, float *F, float *N, float *nfmax, const int32_t *blk_ids, int32_t n_blk,
+                       int32_t root_id, int32_t K, int64_t Bs, int32_t B, hipStream_t s)
 {
+    if (n_blk == 0) return;
     Timed timed(KC_MISC, s);
-    hipLaunchKernelGGL(k_root_flow, dim3((unsigned)((Bs + 255) / 256)), dim3(256), 0, s, l, F, root_row, Bs, B);
+    dim3 grid((unsigned)n_blk, (unsigned)((Bs + 255) / 256));
+    hipLaunchKernelGGL(k_init_flows, grid, dim3(256), 0, s, l, F, N, nfmax, blk_ids, root_id, K, Bs, B);
 }
 
 void launch_input_fwd(const float *tables, const int32_t *xT, const GroupDev &g, int32_t K, int32_t n_cats, int64_t Bs,
@@ -873,41 +970,44 @@ void launch_input_fwd(const float *tables, const int32_t *xT, const GroupDev &g,
 void launch_input_bwd(const float *F, const int32_t *xT, const GroupDev &g, int32_t K, int32_t n_cats, int64_t Bs,
                       float *table_flow, hipStream_t s)
 {
-    Timed timed(KC_INPUT_BWD, s);
     if (g.n_rows == 0) return;
-    dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 255) / 256));
-    hipLaunchKernelGGL(k_input_bwd, grid, dim3(256), 0, s, F, xT, g.ids, g.nbr, g.par, K, n_cats, Bs, table_flow);
+    Timed timed(KC_INPUT_BWD, s);
+    int lps = 1;                                                       // lanes per sample: next power of two >= K, at most 64
+    while (lps < K && lps < 64) lps <<= 1;
+    const size_t tile_bytes = ((size_t)K * 65 + 64) * 4;
+    const size_t hist_bytes = (size_t)n_cats * K * 4 + tile_bytes;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k_input_bwd_hist), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  96 * 1024);
+        attr_set = true;
+    }
+    if (hist_bytes <= 96 * 1024 && (int64_t)n_cats * 4 <= Bs) {           // many samples per category: privatise in LDS
+        hipLaunchKernelGGL(k_input_bwd_hist, dim3((unsigned)g.n_rows), dim3(256), hist_bytes, s, F, xT, g.ids, g.nbr, g.par, K,
+                           n_cats, Bs, table_flow, lps, g.tied ? 1 : 0);
+    } else {
+        dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 63) / 64));
+        hipLaunchKernelGGL(k_input_bwd_direct, grid, dim3(256), tile_bytes, s, F, xT, g.ids, g.nbr, g.par, K, n_cats, Bs,
+                           table_flow, lps);
+    }
 }
 
 void launch_prod_fwd(float *l, float *R, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
 {
-    Timed timed(KC_PROD_FWD, s);
     if (g.n_rows == 0) return;
-    if (Bs >= 256) {
-        dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 255) / 256));
-        hipLaunchKernelGGL(k_prod_fwd<4>, grid, dim3(256), 0, s, l, R, g.ids, g.nbr, g.width, K, Bs);
-    } else {
-        dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 63) / 64));
-        hipLaunchKernelGGL(k_prod_fwd<1>, grid, dim3(256), 0, s, l, R, g.ids, g.nbr, g.width, K, Bs);
-    }
+    Timed timed(KC_PROD_FWD, s);
+    dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 63) / 64));
+    hipLaunchKernelGGL(k_prod_fwd, grid, dim3(256), 0, s, l, R, g.ids, g.nbr, g.width, K, Bs);
 }
 
-void launch_prod_bwd(float *F, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
+void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
 {
     if (g.n_rows == 0) return;
     Timed timed(KC_PROD_BWD, s);
-    const int64_t items = (int64_t)g.n_rows * K * (Bs / 4);
-    hipLaunchKernelGGL(k_prod_bwd, dim3(grid_for(items)), dim3(256), 0, s, F, g.ids, g.nbr, g.n_rows, g.width, K, Bs);
+    dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 63) / 64));
+    hipLaunchKernelGGL(k_prod_bwd, grid, dim3(256), 0, s, l, F, N, nfmax, g.ids, g.nbr, g.aux, g.width, K, Bs);
 }
 
-void launch_lognf(const float *l, const float *F, float *N, float *nfmax, const int32_t *blk_ids, int32_t n_blk,
-                  int32_t K, int64_t Bs, hipStream_t s)
-{
-    Timed timed(KC_LOGNF, s);
-    if (n_blk == 0) return;
-    dim3 grid((unsigned)n_blk, (unsigned)((Bs + 63) / 64));
-    hipLaunchKernelGGL(k_lognf, grid, dim3(256), 0, s, l, F, N, nfmax, blk_ids, K, Bs);
-}
 
 // forward / backward-to-children: (K, rows per wave tile / 32, waves sharing one tile)
 #define PC_SUM_CASE(KK, RR, SS, BWD, ...)                                                                  \
