@@ -528,14 +528,18 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
         for (int e = 0; e < 16; ++e) acc[rt][e] = 0.0f;
     float m = PC_NEG_INF;
 
-    floatx4 th_next[NF4];
-    float v_next[NQ];
-    float rblk_next = 0.0f, bmax_next = PC_NEG_INF;
+    // Two register sets (A, B) hold the fetched theta sub-block, neighbour values and block scalars of two
+    // consecutive chunks of this wave: while one set is consumed the other is being loaded.
+    floatx4 thA[NF4], thB[NF4];
+    float vA[NQ], vB[NQ];
+    float rbA = 0.0f, rbB = 0.0f, bmA = PC_NEG_INF, bmB = PC_NEG_INF;
     const float *vsrc = BWD ? N : l;
-    const int64_t lane_off = (int64_t)(4 * half) * Bs + col;            // per-lane part of a neighbour-value address
+    const uint32_t lane_off = (uint32_t)((int64_t)(4 * half) * Bs + col);   // per-lane part of a neighbour-value address
 
-    // loads of chunk C into th_next / v_next / d_next / bmax_next (a macro, so the arrays stay in registers)
-#define PC_ISSUE(C)                                                                                                   \
+    // loads of chunk C (macros, so the arrays stay in registers).  Row bases are wave-uniform (scalar
+    // registers); only the 32-bit lane offset is per lane.  Nothing is computed on the loaded values here:
+    // any arithmetic would wait for the load.
+#define PC_ISSUE(C, TH, V, RB, BM)                                                                                    \
     do {                                                                                                              \
         const int j_ = (C) / CPB, kc_ = (C) % CPB;                                                                    \
         const int32_t ns_ = row_nbr[j_], ps_ = row_par[j_];                                                           \
@@ -543,67 +547,77 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
                                : theta + (int64_t)ps_ + (int64_t)(sub * TM) * K + kc_ * KC;                           \
         _Pragma("unroll") for (int i = 0; i < NF4; ++i) {                                                             \
             const int t = lane + i * 64;                                                                              \
-            const int o_ = BWD ? (t / (TM / 4)) * K + (t % (TM / 4)) * 4 : (t / (KC / 4)) * K + (t % (KC / 4)) * 4;    \
-            th_next[i] = *reinterpret_cast<const floatx4 *>(tb_ + o_);                                                \
+            const uint32_t o_ = BWD ? (t / (TM / 4)) * K + (t % (TM / 4)) * 4 : (t / (KC / 4)) * K + (t % (KC / 4)) * 4; \
+            TH[i] = *reinterpret_cast<const floatx4 *>(tb_ + o_);                                                     \
         }                                                                                                             \
         const float *src_ = vsrc + (int64_t)(ns_ + kc_ * KC) * Bs;                                                    \
-        _Pragma("unroll") for (int q = 0; q < NQ; ++q) v_next[q] = src_[(int64_t)(8 * (q / 4) + (q % 4)) * Bs + lane_off]; \
-        const int64_t blk_ = (int64_t)(ns_ / K) * Bs + col;                                                           \
-        rblk_next = R[blk_];                              /* raw: any arithmetic here would wait for the load */     \
-        if (BWD) bmax_next = nfmax[blk_];                                                                             \
+        _Pragma("unroll") for (int q = 0; q < NQ; ++q) {                                                              \
+            const float *srow_ = src_ + (int64_t)(8 * (q / 4) + (q % 4)) * Bs;                                        \
+            V[q] = srow_[lane_off];                                                                                   \
+        }                                                                                                             \
+        const float *rrow_ = R + (int64_t)(ns_ / K) * Bs;                                                             \
+        RB = rrow_[(uint32_t)col];                                                                                    \
+        if (BWD) { const float *mrow_ = nfmax + (int64_t)(ns_ / K) * Bs; BM = mrow_[(uint32_t)col]; }                 \
     } while (0)
 
-    if (sp < n_chunks) PC_ISSUE(sp);
-    for (int c = sp; c < n_chunks; c += SPLIT) {
-#pragma unroll
-        for (int i = 0; i < NF4; ++i) {
-            const int t = lane + i * 64;
-            const int o = BWD ? (t / (TM / 4)) * LDA + (t % (TM / 4)) * 4 : (t / (KC / 4)) * LDA + (t % (KC / 4)) * 4;
-            *reinterpret_cast<floatx4 *>(buf + o) = th_next[i];
-        }
-        float v[NQ];
-        float cmax = PC_NEG_INF;
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) { v[q] = v_next[q]; if (!BWD) cmax = fmaxf(cmax, v[q]); }
-        const float d = BWD ? Rrow - rblk_next : rblk_next - Rrow;      // exact integer <= 0
-        if (BWD) cmax = bmax_next + d;
-        else cmax = fmaxf(cmax, __shfl_xor(cmax, 32)) + d;
-        if (c + SPLIT < n_chunks) PC_ISSUE(c + SPLIT);
+    // arithmetic of one fetched chunk
+#define PC_COMPUTE(TH, V, RB, BM)                                                                                     \
+    do {                                                                                                              \
+        _Pragma("unroll") for (int i = 0; i < NF4; ++i) {                                                             \
+            const int t = lane + i * 64;                                                                              \
+            const int o = BWD ? (t / (TM / 4)) * LDA + (t % (TM / 4)) * 4 : (t / (KC / 4)) * LDA + (t % (KC / 4)) * 4; \
+            *reinterpret_cast<floatx4 *>(buf + o) = TH[i];                                                            \
+        }                                                                                                             \
+        const float d = BWD ? Rrow - RB : RB - Rrow;                    /* exact integer <= 0 */                      \
+        float cmax;                                                                                                   \
+        if (BWD) {                                                                                                    \
+            cmax = BM + d;                                                                                            \
+        } else {                                                                                                      \
+            cmax = PC_NEG_INF;                                                                                        \
+            _Pragma("unroll") for (int q = 0; q < NQ; ++q) cmax = fmaxf(cmax, V[q]);                                  \
+            cmax = fmaxf(cmax, __shfl_xor(cmax, 32)) + d;                                                             \
+        }                                                                                                             \
+        /* A operands of the whole chunk into registers first, so the MFMA stream never waits on LDS */               \
+        float areg[NQ][RT];                                                                                           \
+        _Pragma("unroll") for (int rt = 0; rt < RT; ++rt) {                                                           \
+            if (BWD) {                                                                                                \
+                _Pragma("unroll") for (int q = 0; q < NQ; ++q)                                                        \
+                    areg[q][rt] = buf[(8 * (q / 4) + 4 * half + (q % 4)) * LDA + rt * 32 + l32];                      \
+            } else {                                                                                                  \
+                _Pragma("unroll") for (int g = 0; g < NQ / 4; ++g) {                                                  \
+                    const floatx4 a4 = *reinterpret_cast<const floatx4 *>(buf + (rt * 32 + l32) * LDA + 8 * g + 4 * half); \
+                    areg[4 * g + 0][rt] = a4[0]; areg[4 * g + 1][rt] = a4[1];                                         \
+                    areg[4 * g + 2][rt] = a4[2]; areg[4 * g + 3][rt] = a4[3];                                         \
+                }                                                                                                     \
+            }                                                                                                         \
+        }                                                                                                             \
+        const float m_new = fmaxf(m, cmax);                                                                           \
+        const bool dead = !(m_new > PC_NEG_INF);                        /* every term of this column so far is 0 */   \
+        if (__any(m_new != m)) {                                                                                      \
+            const float scale = dead ? 1.0f : __expf(m - m_new);        /* m = -inf -> 0, acc is 0 anyway */          \
+            _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                         \
+                _Pragma("unroll") for (int e = 0; e < 16; ++e) acc[rt][e] *= scale;                                   \
+        }                                                                                                             \
+        m = m_new;                                                                                                    \
+        /* exp(v + d - m) = exp2(v * log2e + sh2); dead column: v = -inf -> 0 */                                      \
+        const float sh2 = dead ? 0.0f : (d - m_new) * PC_LOG2E;                                                       \
+        _Pragma("unroll") for (int q = 0; q < NQ; ++q) {                                                              \
+            const float p = __builtin_amdgcn_exp2f(fmaf(V[q], PC_LOG2E, sh2));                                        \
+            _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                         \
+                acc[rt] = __builtin_amdgcn_mfma_f32_32x32x2f32(areg[q][rt], p, acc[rt], 0, 0, 0);                     \
+        }                                                                                                             \
+    } while (0)
 
-        // A operands of the whole chunk into registers first, so the MFMA stream below never waits on LDS
-        float areg[NQ][RT];
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            if (BWD) {
-#pragma unroll
-                for (int q = 0; q < NQ; ++q) areg[q][rt] = buf[(8 * (q / 4) + 4 * half + (q % 4)) * LDA + rt * 32 + l32];
-            } else {
-#pragma unroll
-                for (int g = 0; g < NQ / 4; ++g) {
-                    const floatx4 a4 = *reinterpret_cast<const floatx4 *>(buf + (rt * 32 + l32) * LDA + 8 * g + 4 * half);
-                    areg[4 * g + 0][rt] = a4[0]; areg[4 * g + 1][rt] = a4[1]; areg[4 * g + 2][rt] = a4[2]; areg[4 * g + 3][rt] = a4[3];
-                }
-            }
-        }
-        const float m_new = fmaxf(m, cmax);
-        const bool dead = !(m_new > PC_NEG_INF);                        // every term of this column so far is 0
-        if (__any(m_new != m)) {
-            const float scale = dead ? 1.0f : __expf(m - m_new);        // m = -inf -> 0, acc is 0 anyway
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[rt][e] *= scale;
-        }
-        m = m_new;
-        const float sh2 = dead ? 0.0f : (d - m_new) * PC_LOG2E;        // exp(v + d - m) = exp2(v * log2e + sh2); dead: v = -inf -> 0
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(v[q], PC_LOG2E, sh2));
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt) acc[rt] = __builtin_amdgcn_mfma_f32_32x32x2f32(areg[q][rt], p, acc[rt], 0, 0, 0);
-        }
+    if (sp < n_chunks) PC_ISSUE(sp, thA, vA, rbA, bmA);
+    for (int c = sp; c < n_chunks; c += 2 * SPLIT) {
+        if (c + SPLIT < n_chunks) PC_ISSUE(c + SPLIT, thB, vB, rbB, bmB);
+        PC_COMPUTE(thA, vA, rbA, bmA);
+        if (c + SPLIT >= n_chunks) break;
+        if (c + 2 * SPLIT < n_chunks) PC_ISSUE(c + 2 * SPLIT, thA, vA, rbA, bmA);
+        PC_COMPUTE(thB, vB, rbB, bmB);
     }
 #undef PC_ISSUE
+#undef PC_COMPUTE
 
     if (SPLIT > 1) {                                                    // merge the partial sums of the SPLIT waves of a tile
         __syncthreads();
@@ -1019,7 +1033,6 @@ void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const Gro
         PC_SUM_CASE(64, 2, 1, BWD, __VA_ARGS__) PC_SUM_CASE(64, 2, 2, BWD, __VA_ARGS__) PC_SUM_CASE(64, 2, 4, BWD, __VA_ARGS__)    \
         PC_SUM_CASE(128, 1, 1, BWD, __VA_ARGS__) PC_SUM_CASE(128, 1, 2, BWD, __VA_ARGS__) PC_SUM_CASE(128, 1, 4, BWD, __VA_ARGS__) \
         PC_SUM_CASE(128, 2, 1, BWD, __VA_ARGS__) PC_SUM_CASE(128, 2, 2, BWD, __VA_ARGS__) PC_SUM_CASE(128, 2, 4, BWD, __VA_ARGS__) \
-        PC_SUM_CASE(128, 4, 1, BWD, __VA_ARGS__) PC_SUM_CASE(128, 4, 2, BWD, __VA_ARGS__) PC_SUM_CASE(128, 4, 4, BWD, __VA_ARGS__) \
     } while (0)
 
 // Tile shape for the forward / backward-to-children kernel: the largest row tile (least exp work and
@@ -1029,7 +1042,7 @@ static void pick_sum_shape(int32_t K, int32_t n_rows, int32_t width, int64_t Bs,
 {
     const int64_t col_tiles = (Bs + 31) / 32;
     const int64_t want = 2048;
-    rt = K / 32 > 4 ? 4 : K / 32;
+    rt = K / 32 > 2 ? 2 : K / 32;                                      // 64-row wave tiles at most (register budget)
     while (rt > 1 && (int64_t)n_rows * (K / (32 * rt)) * col_tiles * 4 < want) rt >>= 1;
     const int64_t tiles = (int64_t)n_rows * (K / (32 * rt)) * col_tiles;
     split = 1;
