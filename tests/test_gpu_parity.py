@@ -223,6 +223,32 @@ def test_forward_is_deterministic_and_state_errors():
         c.backward()
 
 
+def test_sum_block_without_parents_gets_zero_flow():
+    # an extra sum block over the product blocks of the HCLT root variable that nothing refers to: it is
+    # evaluated in the forward pass, carries flow 0, and must not disturb the flows of its children
+    w = W.reduced(2, B=40)
+    K, nb = w.K, w.meta["M"] // w.K
+    prods = [b for b in range(w.n_blocks) if w.type[b] == W.PRODUCT][:nb]          # P_0[0..nb-1]
+    rng = np.random.default_rng(4)
+    extra_theta = rng.dirichlet(np.ones(nb * K), size=K).astype(np.float32).reshape(K, nb, K).transpose(1, 0, 2)
+    w2 = w.with_batch(w.x)
+    w2.n_blocks = w.n_blocks + 1
+    w2.type = np.append(w.type, np.uint8(W.SUM))
+    w2.n_real = np.append(w.n_real, np.int32(K))
+    w2.in_var = np.append(w.in_var, np.int32(-1)); w2.in_table = np.append(w.in_table, np.int32(-1))
+    w2.child_ptr = np.append(w.child_ptr, w.child_ptr[-1] + nb)
+    w2.child = np.append(w.child, np.array(prods, dtype=np.int32))
+    w2.param_blk = np.append(w.param_blk, np.arange(w.n_param_blocks, w.n_param_blocks + nb, dtype=np.int32))
+    w2.n_param_blocks = w.n_param_blocks + nb
+    w2.theta = np.concatenate([w.theta, extra_theta])
+    print("case orphan sum block", flush=True)
+    got, ref = check_all(w2)
+    orphan = w.n_blocks
+    assert np.all(got["flow"][:, orphan * K:(orphan + 1) * K] == 0.0)
+    assert np.all(got["theta_flow"][-nb:] == 0.0)
+    assert np.all(np.isfinite(got["lp"][:, orphan * K:(orphan + 1) * K]))
+
+
 def test_out_of_range_category_has_probability_zero():
     w = W.reduced(1, B=8)
     x = w.x.copy(); x[2, 1] = w.n_cats + 5; x[5, 0] = -3
