@@ -19,6 +19,14 @@ if ROOT not in sys.path:
 PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak: 256 CU x 256 flop/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 
+# HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, scale factor 1.00) from the rocprofv3 --pmc runs summarised in
+# profiles/cfg4_hmm_T32_H4096_B256_hbm_traffic.txt; counters cannot be read from inside this process.
+MEASURED_TRAFFIC = {
+    ("cfg4_hmm_T32_H4096_V50257_B256", "sum_bwd_child"): (70771.4 + 4096.0) * 1024,
+    ("cfg4_hmm_T32_H4096_V50257_B256", "sum_fwd"): (53815.8 + 4128.0) * 1024,
+    ("cfg4_hmm_T32_H4096_V50257_B256", "sum_bwd_param"): (1289561.7 + 65552.0) * 1024,
+}
+
 
 def algorithmic_work(w):
     """Per-step algorithmic flops / bytes per kernel class (ideal-IO model of Sec. 3: every child value
@@ -56,6 +64,8 @@ def main():
     ap.add_argument("--K", type=int, default=None, help="node block size (default per config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-em", action="store_true", help="skip the secondary timing that adds pc_em_step")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device-to-device copy kernel (scale reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
@@ -70,6 +80,14 @@ def main():
     w = W.config(args.config, K=args.K)
     gen_s = time.time() - t0
     work, Es = algorithmic_work(w)
+
+    if args.calibrate_copy:                            # reads 256 MiB, writes 256 MiB: what FETCH_SIZE / WRITE_SIZE are scaled by
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     t0 = time.time()
     c = pcb.Circuit(w, "cuda:0")
@@ -118,7 +136,7 @@ def main():
     dom = max((k for k in kernels if "bound" in kernels[k]), key=lambda k: kernels[k]["ms_per_step"])
     d = kernels[dom]
     roofline = {"kernel": dom, "bound": d["bound"], "achieved": d["achieved"], "peak": d["peak"], "unit": d["unit"],
-                "frac": d["frac"], "traffic": None, "avg_launch_us": d["avg_launch_us"],
+                "frac": d["frac"], "traffic": MEASURED_TRAFFIC.get((w.name, dom)), "avg_launch_us": d["avg_launch_us"],
                 "work_per_launch": d["work_per_launch"]}
 
     em = None
