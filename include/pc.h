@@ -72,7 +72,8 @@ typedef struct {
 /* Compile once, reuse for every batch (Sec. 6.1).  Layers by longest-path depth (Sec. 3), groups by
  * the dynamic programme of App. A.1, forward index tensors sum_ids / prod_ids / param_ids (Sec. 4.3)
  * and backward index tensors ch_ids / par_ids / par_param_ids (App. A.2), for sum and product layers
- * alike.  Uploads the tables on `stream` and waits for the upload.  *out is set only on PC_OK. */
+ * alike.  Validation, depths and Alg. 2 run on the host; the graph transpose, the sorting of neighbour lists and
+ * the filling of every table run as HIP kernels on `stream`; the call waits for them.  *out is set only on PC_OK. */
 pc_status pc_compile(const pc_dag *dag, void *stream, pc_circuit **out);
 /* The host half of pc_compile alone (validation, layering, Alg. 2, tables); touches no GPU.  The handle
  * serves pc_get_sizes / pc_get_layer / pc_copy_group / pc_workspace_*; forward, backward and the EM

@@ -25,8 +25,9 @@ static pc_status hip_fail(hipError_t e, const char *what)
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// One arena for every table: sizes first, then pointers.
-static pc_status upload(pc_circuit *c, hipStream_t stream)
+// One arena for every table: sizes first, then pointers.  Host copies are uploaded where they exist; tables built
+// on the device only get their space.
+pc_status upload(pc_circuit *c, hipStream_t stream)
 {
     size_t bytes = 0;
     auto reserve = [&](size_t n_i32) { size_t off = bytes; bytes = align_up(bytes + n_i32 * 4, 256); return off; };
@@ -35,10 +36,18 @@ static pc_status upload(pc_circuit *c, hipStream_t stream)
     auto add = [&](int32_t **dst, const std::vector<int32_t> &v) {
         fixes.push_back({(void **)dst, reserve(v.size()), v.data(), v.size() * 4});
     };
+    auto add_sized = [&](int32_t **dst, const std::vector<int32_t> &v, size_t n) {   // n entries, copied only if present
+        fixes.push_back({(void **)dst, reserve(n), v.data(), v.size() == n ? n * 4 : 0});
+    };
     for (auto &layer : c->layers) {
         add(&layer.d_blk_ids, layer.blk_ids);
         for (auto *groups : {&layer.fwd, &layer.bwd})
-            for (auto &g : *groups) { add(&g.d_ids, g.ids); add(&g.d_nbr, g.nbr); add(&g.d_par, g.par); add(&g.d_aux, g.aux); }
+            for (auto &g : *groups) {
+                add_sized(&g.d_ids, g.ids, (size_t)g.n_rows);
+                add_sized(&g.d_nbr, g.nbr, (size_t)g.n_rows * g.width);
+                add_sized(&g.d_par, g.par, (size_t)g.n_rows * g.width);
+                add(&g.d_aux, g.aux);
+            }
     }
     add(&c->d_pb_group, c->pb_group); add(&c->d_pb_rows, c->pb_rows); add(&c->d_pb_cols, c->pb_cols);
     add(&c->d_group_nch, c->group_nch);
@@ -103,7 +112,7 @@ pc_status pc_compile_host(const pc_dag *dag, pc_circuit **out)
     if (!out) return fail(PC_ERR_ARG, "out is NULL");
     pc_circuit *c = new (std::nothrow) pc_circuit();
     if (!c) return fail(PC_ERR_ARG, "out of host memory");
-    pc_status st = compile_host(dag, c);
+    pc_status st = compile_host(dag, c, /*tables_on_host=*/true);
     if (st != PC_OK) { delete c; return st; }
     *out = c;
     return PC_OK;
@@ -111,10 +120,11 @@ pc_status pc_compile_host(const pc_dag *dag, pc_circuit **out)
 
 pc_status pc_compile(const pc_dag *dag, void *stream, pc_circuit **out)
 {
-    pc_circuit *c = nullptr;
-    pc_status st = pc_compile_host(dag, &c);
-    if (st != PC_OK) return st;
-    st = upload(c, (hipStream_t)stream);
+    if (!out) return fail(PC_ERR_ARG, "out is NULL");
+    pc_circuit *c = new (std::nothrow) pc_circuit();
+    if (!c) return fail(PC_ERR_ARG, "out of host memory");
+    pc_status st = compile_host(dag, c, /*tables_on_host=*/false);      // validation, layering, EM and flow maps
+    if (st == PC_OK) st = build_tables_device(dag, c, stream);          // groups (Alg. 2) + tables filled by HIP kernels
     if (st != PC_OK) { pc_destroy(c); return st; }
     const char *env = std::getenv("PC_FORCE_GENERIC");
     set_force_generic(env && env[0] == '1');
@@ -179,6 +189,7 @@ pc_status pc_copy_group(const pc_circuit *c, int32_t layer, int32_t dir, int32_t
         if (nbr_host && n_tab) PC_HIP(hipMemcpy(nbr_host, g->d_nbr, n_tab, hipMemcpyDeviceToHost));
         if (par_host && n_tab) PC_HIP(hipMemcpy(par_host, g->d_par, n_tab, hipMemcpyDeviceToHost));
     } else {
+        if (g->ids.size() * 4 != n_ids || g->nbr.size() * 4 != n_tab) return fail(PC_ERR_STATE, "tables live on the device");
         if (ids_host) std::memcpy(ids_host, g->ids.data(), n_ids);
         if (nbr_host) std::memcpy(nbr_host, g->nbr.data(), n_tab);
         if (par_host) std::memcpy(par_host, g->par.data(), n_tab);

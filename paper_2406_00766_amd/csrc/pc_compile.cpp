@@ -127,7 +127,7 @@ pc_status build_groups(std::vector<Row> &rows, int32_t max_groups, int32_t tol_p
 
 }  // namespace
 
-pc_status compile_host(const pc_dag *d, pc_circuit *c)
+pc_status compile_host(const pc_dag *d, pc_circuit *c, bool tables_on_host)
 {
     if (!d) return fail(PC_ERR_ARG, "dag is NULL");
     if (d->K < 1 || d->n_blocks < 1) return fail(PC_ERR_ARG, "K and n_blocks must be positive");
@@ -220,6 +220,8 @@ pc_status compile_host(const pc_dag *d, pc_circuit *c)
     c->K = K; c->n_blocks = n; c->root_block = d->root_block; c->n_param_blocks = d->n_param_blocks;
     c->n_vars = d->n_vars; c->n_cats = d->n_cats; c->n_tables = d->n_tables;
     c->layers.clear();
+    c->an_depth = depth;                                  // kept for the device table builder
+    c->an_last_parent_depth = last_parent_depth;
 
     // bucket blocks: layer key = 2*depth + (sum ? 1 : 0); inputs are layer 0
     std::vector<std::vector<int32_t>> bucket(2 * (size_t)max_depth + 2);
@@ -247,7 +249,7 @@ pc_status compile_host(const pc_dag *d, pc_circuit *c)
             std::sort(tabs.begin(), tabs.end());
             g.tied_in_group = std::adjacent_find(tabs.begin(), tabs.end()) != tabs.end();
             layer.fwd.push_back(std::move(g));
-        } else {
+        } else if (tables_on_host) {
             std::vector<Row> fwd_rows;
             std::map<int32_t, Row> by_child;                       // ordered: ascending child block id
             for (int32_t u : blocks) {

@@ -52,6 +52,9 @@ struct pc_circuit {
     size_t arena_bytes = 0;
     bool on_device = false;
 
+    // analysis results handed from compile_host to build_tables_device (cleared afterwards)
+    std::vector<int32_t> an_depth, an_last_parent_depth;
+
     // optional per-kernel-class timing (pc_profile_*)
     void *profiler = nullptr;                         // pc::Profiler*, owned
     int64_t prof_launches[16] = {0};
@@ -69,7 +72,11 @@ void set_error(const std::string &msg);
 pc_status fail(pc_status st, const std::string &msg);
 
 // Host part of compilation: validation, layering, grouping, table construction, EM maps.
-pc_status compile_host(const pc_dag *dag, pc_circuit *c);
+// tables_on_host = false leaves the sum / product layer tables to build_tables_device.
+pc_status compile_host(const pc_dag *dag, pc_circuit *c, bool tables_on_host);
+// Device part of compilation: transposes the block graph, sorts neighbour lists and fills every forward and
+// backward table with HIP kernels; allocates the handle's device arena and uploads the remaining metadata.
+pc_status build_tables_device(const pc_dag *dag, pc_circuit *c, void *stream);
 // Alg. 2 (App. A.1): ascending group capacities for the given neighbour counts.
 std::vector<int32_t> partition_groups(const std::vector<int32_t> &counts, int32_t max_groups, int32_t tol_permille);
 

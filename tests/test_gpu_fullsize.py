@@ -13,7 +13,7 @@ torch = pytest.importorskip("torch")
 from oracle import pc_oracle as orc
 from paper_2406_00766_amd import binding as pcb
 from paper_2406_00766_amd import workloads as W
-from tests.test_gpu_parity import assert_flow_close, assert_logprob_close
+from tests.test_gpu_parity import assert_device_tables_match_oracle, assert_flow_close, assert_logprob_close
 
 pytestmark = pytest.mark.gpu
 
@@ -26,6 +26,8 @@ def test_full_size_config(idx):
     w = W.config(idx)
     K, B, n = w.K, w.B, N_ORACLE[idx]
     c = pcb.Circuit(w)
+    print("  compiled tables (built by the device compiler) against the compile oracle, bit for bit", flush=True)
+    assert_device_tables_match_oracle(c.handle, w)
     c.set_batch(w.x)
     print("  gpu forward/backward at full batch", flush=True)
     ll = c.forward().double().cpu().numpy()
