@@ -272,12 +272,12 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
     const float *R = (const float *)(base + w.r_off);
     const int32_t *xT = (const int32_t *)(base + w.xt_off);
     const int32_t K = c->K;
-    const int64_t rows = ((int64_t)c->n_blocks + 1) * K;
 
     // MFMA block sizes: parameter flows of the whole circuit in one launch after the sweep (N and nfmax of
     // every sum layer stay valid until then); other block sizes: layer by layer
     const bool batched_params = param_flow_uses_mfma(K);
-    launch_fill(F, rows * w.Bs, 0.0f, s);
+    // no clearing of F: every block's flow is stored by the first layer that feeds it, blocks nobody feeds are
+    // initialised here
     launch_init_flows(l, F, N, nfmax, c->d_init_ids, (int32_t)c->init_ids.size(), (c->root_block + 1) * K, K, w.Bs, B, s);
     for (size_t li = c->layers.size(); li-- > 0;) {
         const LayerTab &L = c->layers[li];

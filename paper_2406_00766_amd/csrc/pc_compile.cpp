@@ -206,22 +206,28 @@ pc_status compile_host(const pc_dag *d, pc_circuit *c, bool tables_on_host)
     if (done != n) return fail(PC_ERR_CYCLE, "the block graph has a cycle");
 
     if (par_ptr[d->root_block + 1] != par_ptr[d->root_block]) return fail(PC_ERR_ARG, "the root block must not have parents");
-    // per block: the smallest depth among its parents (the last layer of the backward sweep that feeds it)
-    std::vector<int32_t> last_parent_depth(n, -1);
+    // per block: the smallest and the largest depth among its parents (the last and the first layer of the
+    // backward sweep that feed it; all parents of a block are of one kind, so a depth names one layer)
+    std::vector<int32_t> last_parent_depth(n, -1), first_parent_depth(n, -1);
     for (int32_t u = 0; u < n; ++u)
         for (int32_t k = par_ptr[u]; k < par_ptr[u + 1]; ++k) {
             const int32_t dp = depth[par_of[k]];
             if (last_parent_depth[u] < 0 || dp < last_parent_depth[u]) last_parent_depth[u] = dp;
+            if (dp > first_parent_depth[u]) first_parent_depth[u] = dp;
         }
+    // blocks no layer of the backward sweep writes: sum blocks as node offsets (flow and log_nf initialised),
+    // other blocks and the null block as ~offset (flow zeroed only)
     c->init_ids.clear();
+    c->init_ids.push_back(~0);
     for (int32_t u = 0; u < n; ++u)
-        if (d->type[u] == KIND_SUM && last_parent_depth[u] < 0) c->init_ids.push_back((u + 1) * K);
+        if (last_parent_depth[u] < 0) c->init_ids.push_back(d->type[u] == KIND_SUM ? (u + 1) * K : ~((u + 1) * K));
 
     c->K = K; c->n_blocks = n; c->root_block = d->root_block; c->n_param_blocks = d->n_param_blocks;
     c->n_vars = d->n_vars; c->n_cats = d->n_cats; c->n_tables = d->n_tables;
     c->layers.clear();
     c->an_depth = depth;                                  // kept for the device table builder
     c->an_last_parent_depth = last_parent_depth;
+    c->an_first_parent_depth = first_parent_depth;
 
     // bucket blocks: layer key = 2*depth + (sum ? 1 : 0); inputs are layer 0
     std::vector<std::vector<int32_t>> bucket(2 * (size_t)max_depth + 2);
@@ -271,12 +277,12 @@ pc_status compile_host(const pc_dag *d, pc_circuit *c, bool tables_on_host)
             if (st != PC_OK) return st;
             st = build_groups(bwd_rows, d->max_groups, d->tol_permille, layer.bwd);
             if (st != PC_OK) return st;
-            if (layer.kind == KIND_PRODUCT)
-                for (GroupTab &gt : layer.bwd)
-                    for (int32_t id : gt.ids) {
-                        const int32_t ch = id / K - 1;
-                        gt.aux.push_back(d->type[ch] == KIND_SUM && last_parent_depth[ch] == layer.depth ? 1 : 0);
-                    }
+            for (GroupTab &gt : layer.bwd)
+                for (int32_t id : gt.ids) {
+                    const int32_t ch = id / K - 1;
+                    gt.aux.push_back(bwd_row_flags(layer.kind, d->type[ch], layer.depth, last_parent_depth[ch],
+                                                   first_parent_depth[ch]));
+                }
         }
         c->layers.push_back(std::move(layer));
     }

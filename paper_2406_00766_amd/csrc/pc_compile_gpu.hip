@@ -261,12 +261,11 @@ pc_status build_tables_device(const pc_dag *d, pc_circuit *c, void *stream_v)
         for (int32_t r : rows) counts.push_back(rcnt[r]);
         assign_groups(counts, d->max_groups, d->tol_permille, L.bwd, grp, rank);
         for (size_t i = 0; i < rows.size(); ++i) { b_grp[rows[i]] = grp[i]; b_rank[rows[i]] = rank[i]; }
-        if (L.kind == KIND_PRODUCT) {
-            for (GroupTab &g : L.bwd) g.aux.assign(g.n_rows, 0);
-            for (size_t i = 0; i < rows.size(); ++i) {
-                const int32_t ch = rchild[rows[i]];
-                L.bwd[grp[i]].aux[rank[i]] = d->type[ch] == KIND_SUM && c->an_last_parent_depth[ch] == L.depth ? 1 : 0;
-            }
+        for (GroupTab &g : L.bwd) g.aux.assign(g.n_rows, 0);
+        for (size_t i = 0; i < rows.size(); ++i) {
+            const int32_t ch = rchild[rows[i]];
+            L.bwd[grp[i]].aux[rank[i]] = bwd_row_flags(L.kind, d->type[ch], L.depth, c->an_last_parent_depth[ch],
+                                                       c->an_first_parent_depth[ch]);
         }
     }
 
@@ -314,7 +313,7 @@ pc_status build_tables_device(const pc_dag *d, pc_circuit *c, void *stream_v)
                            d_rcnt.p, d_tp.p, d_src.p, d_param.p, d_type.p, K, d_bids.p, d_bnbr.p, d_bpar.p, d_bw.p);
     PC_HIP(hipGetLastError());
     PC_HIP(hipStreamSynchronize(stream));                               // temporaries are freed on return
-    c->an_depth.clear(); c->an_last_parent_depth.clear();
+    c->an_depth.clear(); c->an_last_parent_depth.clear(); c->an_first_parent_depth.clear();
     return PC_OK;
 }
 

@@ -10,11 +10,26 @@ namespace pc {
 
 enum : int { KIND_INPUT = 0, KIND_PRODUCT = 1, KIND_SUM = 2 };
 
+// Flags of one row (= one child block) of a layer's backward tables.
+//   BWD_FINAL  product layer, sum child: this is the last layer that adds to the child's flow, which is complete
+//              afterwards (log_nf of Alg. 3 / 4 is produced here)
+//   BWD_FIRST  this is the first layer of the backward sweep that adds to the child's flow: the kernel stores
+//              instead of accumulating, so the flow buffer needs no clearing (the '=' of Alg. 4's last line)
+enum : int32_t { BWD_FINAL = 1, BWD_FIRST = 2 };
+inline int32_t bwd_row_flags(int layer_kind, int child_kind, int32_t layer_depth, int32_t last_parent_depth,
+                             int32_t first_parent_depth)
+{
+    int32_t f = 0;
+    if (layer_kind == KIND_PRODUCT && child_kind == KIND_SUM && last_parent_depth == layer_depth) f |= BWD_FINAL;
+    if (first_parent_depth == layer_depth) f |= BWD_FIRST;
+    return f;
+}
+
 // One group of a layer: rows padded to a common width (Sec. 4.3).
 struct GroupTab {
     int32_t n_rows = 0, width = 0;
     std::vector<int32_t> ids, nbr, par;              // host copies
-    std::vector<int32_t> aux;                        // per row; product backward groups: flow final in this layer
+    std::vector<int32_t> aux;                        // per row of a backward group: BWD_* flags
     int32_t *d_ids = nullptr, *d_nbr = nullptr, *d_par = nullptr, *d_aux = nullptr;
     bool tied_in_group = false;                       // a parameter block occurs twice: flows need atomics
 };
@@ -44,7 +59,8 @@ struct pc_circuit {
     std::vector<int32_t> pf_pb, pf_ptr, pf_sum, pf_child;
     int32_t *d_pf_pb = nullptr, *d_pf_ptr = nullptr, *d_pf_sum = nullptr, *d_pf_child = nullptr;
 
-    // sum blocks whose flow no product layer finalises: the root block and sum blocks without parents
+    // blocks without parents, which no layer of the backward sweep writes.  Sum blocks (the root among them) as
+    // node offsets; other blocks and the null block as ~offset
     std::vector<int32_t> init_ids;
     int32_t *d_init_ids = nullptr;
 
@@ -53,7 +69,7 @@ struct pc_circuit {
     bool on_device = false;
 
     // analysis results handed from compile_host to build_tables_device (cleared afterwards)
-    std::vector<int32_t> an_depth, an_last_parent_depth;
+    std::vector<int32_t> an_depth, an_last_parent_depth, an_first_parent_depth;
 
     // optional per-kernel-class timing (pc_profile_*)
     void *profiler = nullptr;                         // pc::Profiler*, owned

@@ -11,7 +11,7 @@ struct GroupDev {            // device view of one table group
     int32_t n_rows, width;
     const int32_t *ids, *nbr, *par;
     bool tied;
-    const int32_t *aux;      // product-layer backward groups: 1 where the row's flow becomes final in this layer
+    const int32_t *aux;      // backward groups: per row, bit 0 = flow final after this layer, bit 1 = first layer to write it
 };
 
 struct ParamFlowDev {        // parameter blocks with the (sum block, child block) pairs that use them

@@ -268,11 +268,12 @@ __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *
 }
 
 // backward (Def. 2): rows = child blocks (sum / input blocks), neighbours = their product parents in this layer;
-// F_child += sum of the parents' flows.  Where this layer is the last one that feeds a SUM block (fin != 0)
-// its flow is final, so log_nf = log F - l (Alg. 3 / 4) and its column maximum per block are produced here.
+// F_child += sum of the parents' flows ('=' where this is the first layer that feeds the block, flag bit 1, so
+// the flow buffer is never cleared).  Where this layer is the last one that feeds a SUM block (flag bit 0) its
+// flow is final, so log_nf = log F - l (Alg. 3 / 4) and its column maximum per block are produced here.
 __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, float *__restrict__ F, float *__restrict__ N,
                                                   float *__restrict__ nfmax, const int32_t *__restrict__ ids,
-                                                  const int32_t *__restrict__ nbr, const int32_t *__restrict__ fin,
+                                                  const int32_t *__restrict__ nbr, const int32_t *__restrict__ flags,
                                                   int32_t width, int32_t K, int64_t Bs)
 {
     constexpr int RPT = 8;
@@ -283,13 +284,15 @@ __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, f
     const bool in = b < Bs;
     const int32_t *row_nbr = nbr + (int64_t)r * width;
     const int32_t id = ids[r];
-    const bool final_flow = fin[r] != 0;                               // uniform over the workgroup
+    const int32_t fl = flags[r];                                        // uniform over the workgroup
+    const bool final_flow = (fl & 1) != 0, first = (fl & 2) != 0;
     float4 f[RPT];
     if (in) {
 #pragma unroll
         for (int i = 0; i < RPT; ++i) {
             const int k = rg + 16 * i;
-            f[i] = k < K ? *reinterpret_cast<const float4 *>(F + (int64_t)(id + k) * Bs + b) : make_float4(0.f, 0.f, 0.f, 0.f);
+            f[i] = (k < K && !first) ? *reinterpret_cast<const float4 *>(F + (int64_t)(id + k) * Bs + b)
+                                     : make_float4(0.f, 0.f, 0.f, 0.f);
         }
         for (int j = 0; j < width; ++j) {
             const int32_t pa = row_nbr[j];                              // padding -> null block, flow 0
@@ -330,23 +333,34 @@ __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, f
     if (in && rg == 0) *reinterpret_cast<float4 *>(nfmax + (int64_t)(id / K) * Bs + b) = make_float4(mx[0], mx[1], mx[2], mx[3]);
 }
 
-// Sum blocks that no product layer finalises: the root block (flow 1 on node 0 of real samples with non-zero
-// probability, Def. 2) and sum blocks without parents (flow 0).  One workgroup per listed block and 256 columns.
+// Blocks without parents, which no layer of the backward sweep writes.  An entry >= 0 is a sum block: the root
+// (flow 1 on node 0 of real samples with non-zero probability, Def. 2) or a sum block nobody uses (flow 0); its
+// log_nf rows and block maximum are set as well.  An entry < 0 is ~offset of another block (the null block, a
+// product or input block nobody uses): its flow rows are zeroed.  One workgroup per entry and 256 columns.
 __global__ __launch_bounds__(256) void k_init_flows(const float *__restrict__ l, float *__restrict__ F, float *__restrict__ N,
                                                     float *__restrict__ nfmax, const int32_t *__restrict__ blk_ids,
                                                     int32_t root_id, int32_t K, int64_t Bs, int32_t B)
 {
-    const int32_t id = blk_ids[blockIdx.x];
+    const int32_t entry = blk_ids[blockIdx.x];
     const int64_t b = (int64_t)blockIdx.y * 256 + threadIdx.x;
     if (b >= Bs) return;
-    float top = PC_NEG_INF;
+    if (entry < 0) {
+        const int32_t id = ~entry;
+        for (int k = 0; k < K; ++k) F[(int64_t)(id + k) * Bs + b] = 0.0f;
+        return;
+    }
+    const int32_t id = entry;
+    float top = PC_NEG_INF, f0 = 0.0f;
     if (id == root_id) {
         const float lv = l[(int64_t)id * Bs + b];
         const bool live = b < B && lv > PC_NEG_INF;
-        F[(int64_t)id * Bs + b] = live ? 1.0f : 0.0f;
+        f0 = live ? 1.0f : 0.0f;
         top = live ? -lv : PC_NEG_INF;
     }
-    for (int k = 0; k < K; ++k) N[(int64_t)(id + k) * Bs + b] = k == 0 ? top : PC_NEG_INF;
+    for (int k = 0; k < K; ++k) {
+        F[(int64_t)(id + k) * Bs + b] = k == 0 ? f0 : 0.0f;
+        N[(int64_t)(id + k) * Bs + b] = k == 0 ? top : PC_NEG_INF;
+    }
     nfmax[(int64_t)(id / K) * Bs + b] = top;
 }
 
@@ -392,7 +406,8 @@ __global__ __launch_bounds__(256) void k_sum_bwd_child_generic(const float *__re
                                                                const float *__restrict__ R, const float *__restrict__ N,
                                                                float *__restrict__ F, const int32_t *__restrict__ ids,
                                                                const int32_t *__restrict__ nbr, const int32_t *__restrict__ par,
-                                                               int32_t n_rows, int32_t width, int32_t K, int64_t Bs)
+                                                               const int32_t *__restrict__ flags, int32_t n_rows,
+                                                               int32_t width, int32_t K, int64_t Bs)
 {
     const int64_t total = (int64_t)n_rows * K * Bs;
     for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
@@ -412,7 +427,8 @@ __global__ __launch_bounds__(256) void k_sum_bwd_child_generic(const float *__re
         }
         const int64_t at = (int64_t)(ids[r] + jj) * Bs + b;
         const float lc = l[at];
-        if (m > PC_NEG_INF && lc > PC_NEG_INF) F[at] += __expf(m + __logf(s) + lc);
+        const float add = (m > PC_NEG_INF && lc > PC_NEG_INF) ? __expf(m + __logf(s) + lc) : 0.0f;
+        F[at] = (flags[r] & 2) ? add : F[at] + add;                     // first layer that feeds the block stores
     }
 }
 
@@ -480,7 +496,8 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
                                                      float *__restrict__ R, const float *__restrict__ N,
                                                      const float *__restrict__ nfmax, float *__restrict__ F,
                                                      const int32_t *__restrict__ ids, const int32_t *__restrict__ nbr,
-                                                     const int32_t *__restrict__ par, int32_t width, int64_t Bs)
+                                                     const int32_t *__restrict__ par, const int32_t *__restrict__ flags,
+                                                     int32_t width, int64_t Bs)
 {
     constexpr int KC = 32;
     constexpr int TM = 32 * RT;
@@ -505,6 +522,8 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
     const int64_t col = (active ? col0 : 0) + l32;
     const int32_t *row_nbr = nbr + (int64_t)r * width, *row_par = par + (int64_t)r * width;
     const int32_t id = ids[r];
+    // backward: the first layer of the sweep that feeds this block stores its flow, later ones accumulate
+    const bool first = BWD ? (flags[r] & 2) != 0 : true;                // wave-uniform
     float *buf = lds + wave * WSZ;
 
     int n_real = 0;                                                     // padding sits at the end of a row
@@ -655,7 +674,9 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
             const int64_t at = (base + i) * Bs + col;
             if (BWD) {
                 const float lc = l[at];
-                if (a > 0.0f && lc > PC_NEG_INF) F[at] += __expf(__logf(a) + m + lc);
+                const float add = (a > 0.0f && lc > PC_NEG_INF) ? __expf(__logf(a) + m + lc) : 0.0f;
+                if (first) F[at] = add;
+                else if (add > 0.0f) F[at] += add;
             } else {
                 l[at] = a > 0.0f ? m + __logf(a) : PC_NEG_INF;
             }
@@ -1059,7 +1080,7 @@ void launch_sum_fwd(const float *theta, float *l, float *R, const GroupDev &g, i
         const int64_t cols_per_wg = 32 * (4 / split);
         dim3 grid((unsigned)(g.n_rows * (K / (32 * rt))), (unsigned)((Bs + cols_per_wg - 1) / cols_per_wg));
         PC_DISPATCH_SUM(false, grid, dim3(256), 0, s, theta, l, R, (const float *)nullptr, (const float *)nullptr,
-                        (float *)nullptr, g.ids, g.nbr, g.par, g.width, Bs);
+                        (float *)nullptr, g.ids, g.nbr, g.par, (const int32_t *)nullptr, g.width, Bs);
     } else {
         const int64_t items = (int64_t)g.n_rows * K * Bs;
         hipLaunchKernelGGL(k_sum_fwd_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, l, R, g.ids, g.nbr, g.par,
@@ -1078,11 +1099,11 @@ void launch_sum_bwd_child(const float *theta, const float *l, const float *R, co
         const int64_t cols_per_wg = 32 * (4 / split);
         dim3 grid((unsigned)(g.n_rows * (K / (32 * rt))), (unsigned)((Bs + cols_per_wg - 1) / cols_per_wg));
         PC_DISPATCH_SUM(true, grid, dim3(256), 0, s, theta, const_cast<float *>(l), const_cast<float *>(R), N, nfmax,
-                        F, g.ids, g.nbr, g.par, g.width, Bs);
+                        F, g.ids, g.nbr, g.par, g.aux, g.width, Bs);
     } else {
         const int64_t items = (int64_t)g.n_rows * K * Bs;
         hipLaunchKernelGGL(k_sum_bwd_child_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, l, R, N, F, g.ids, g.nbr,
-                           g.par, g.n_rows, g.width, K, Bs);
+                           g.par, g.aux, g.n_rows, g.width, K, Bs);
     }
 }
 

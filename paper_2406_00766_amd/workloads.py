@@ -7,7 +7,8 @@ one module both the CPU oracle's tests and the GPU path's tests / benchmark draw
 Structures follow the experimental section of the paper (Sec. 6, App. C): homogeneous HMMs
 written as circuits (footnote to Sec. 1), hidden Chow-Liu trees, and a Poon-Domingos grid
 structure with axis-aligned splits (App. C.4), optionally with whole child blocks pruned at
-random as in the block-sparse experiment (App. C.1).
+random as in the block-sparse experiment (App. C.1), and the single wide block-sparse sum layer of
+that experiment (also the shape of the layer analysed in Sec. 4.2).
 
 Block-level DAG convention (one "block" = K consecutive node slots):
   type[u]        0 input, 1 product, 2 sum
@@ -457,6 +458,103 @@ def pd(grid: int, cell: int, M: int, K: int, B: int, seed: int, *, keep=1.0, n_c
     meta = {"kind": "pd", "grid": grid, "cell": cell, "M": M, "keep": keep}
     return _make(name or f"pd_g{grid}_c{cell}_M{M}_K{K}_keep{keep}_B{B}", bld, root, n_param_blocks, D, n_cats,
                  D * nb, theta, tables, x, meta)
+
+
+# --------------------------------------------------------------------------------------------
+# One wide sum layer (App. C.1: independent fully-connected node sets; Sec. 4.2 analysis layer)
+# --------------------------------------------------------------------------------------------
+def sum_layer(n_sets: int, M: int, K: int, B: int, seed: int, *, keep=1.0, n_cats=256, draw=True, name=None) -> Workload:
+    """`n_sets` independent sets of M sum nodes fully connected to M product nodes, wrapped into a circuit.
+
+    set s (variable s):  E_s = M categorical input nodes, P_s[k] = E_s[k] (single child),
+                         S_s[i] = sum_j W_s[i, j] P_s[j]   -- the layer under study, n_sets * M * M edges
+    on top:              T[k] = prod_s S_s[k],  root = sum_k pi[k] T[k]
+    keep < 1:  each K x K edge block of a set survives with probability `keep`; every sum block keeps at
+               least one child block, so every sum node keeps at least one child (App. C.1).
+    Built with array operations only, so that K = 1 (one block per node) stays affordable.
+    """
+    assert M % K == 0
+    nb = M // K
+    rng = np.random.Generator(np.random.PCG64(seed))
+    nE = n_sets * nb
+    E0, P0, S0, T0 = 0, nE, 2 * nE, 3 * nE
+    root = T0 + nb
+    n_blocks = root + 1
+
+    masks = np.ones((n_sets, nb, nb), dtype=bool)
+    if keep < 1.0:
+        masks = rng.random((n_sets, nb, nb)) < keep
+        empty = ~masks.any(axis=2)
+        pick = rng.integers(0, nb, size=(n_sets, nb))
+        s_i, r_i = np.nonzero(empty)
+        masks[s_i, r_i, pick[s_i, r_i]] = True
+    n_kept = masks.sum(axis=2).astype(np.int64)                        # [n_sets, nb] child blocks per sum block
+    n_sum_edges = int(n_kept.sum())
+
+    typ = np.empty(n_blocks, dtype=np.uint8)
+    typ[E0:P0], typ[P0:S0], typ[S0:T0], typ[T0:root], typ[root] = INPUT, PRODUCT, SUM, PRODUCT, SUM
+    n_real = np.full(n_blocks, K, dtype=np.int32)
+    n_real[root] = 1
+    deg = np.zeros(n_blocks, dtype=np.int64)
+    deg[P0:S0] = 1
+    deg[S0:T0] = n_kept.ravel()
+    deg[T0:root] = n_sets
+    deg[root] = nb
+    ptr = np.zeros(n_blocks + 1, dtype=np.int64)
+    np.cumsum(deg, out=ptr[1:])
+    child = np.empty(int(ptr[-1]), dtype=np.int32)
+    param = np.full(int(ptr[-1]), -1, dtype=np.int32)
+    child[ptr[P0]:ptr[S0]] = np.arange(E0, P0, dtype=np.int32)
+    set_of, _, col = np.nonzero(masks)                                 # row-major: set, sum block, child block ascending
+    child[ptr[S0]:ptr[T0]] = (P0 + set_of * nb + col).astype(np.int32)
+    param[ptr[S0]:ptr[T0]] = np.arange(n_sum_edges, dtype=np.int32)
+    child[ptr[T0]:ptr[root]] = (S0 + np.arange(n_sets)[None, :] * nb + np.arange(nb)[:, None]).ravel().astype(np.int32)
+    child[ptr[root]:] = np.arange(T0, root, dtype=np.int32)
+    param[ptr[root]:] = n_sum_edges + np.arange(nb, dtype=np.int32)
+    n_param_blocks = n_sum_edges + nb
+
+    in_var = np.full(n_blocks, -1, dtype=np.int32)
+    in_table = np.full(n_blocks, -1, dtype=np.int32)
+    in_var[E0:P0] = np.repeat(np.arange(n_sets, dtype=np.int32), nb)
+    in_table[E0:P0] = np.arange(nE, dtype=np.int32)
+
+    theta = np.zeros((n_param_blocks + 1, K, K), dtype=np.float32)
+    tables = np.zeros((nE, n_cats, K), dtype=np.float32)
+    x = np.zeros((B, n_sets), dtype=np.int32)
+    if draw:
+        pos = 1
+        for s in range(n_sets):
+            Wd = rng.standard_exponential((M, M))
+            dense_mask = np.repeat(np.repeat(masks[s], K, axis=0), K, axis=1)
+            Wd *= dense_mask
+            Wd /= Wd.sum(axis=1, keepdims=True)
+            Wf = _f32_floor(Wd) * dense_mask
+            nk = int(n_kept[s].sum())
+            theta[pos:pos + nk] = _dense_to_blocks(Wf, K)[masks[s].ravel()]
+            pos += nk
+            Tv = _f32_floor(_dirichlet_rows(rng, 1.0, (M, n_cats)))
+            tables[s * nb:(s + 1) * nb] = Tv.reshape(nb, K, n_cats).transpose(0, 2, 1)
+        pi = _f32_floor(_dirichlet_rows(rng, 1.0, (1, M)))
+        theta[pos:pos + nb, 0, :] = pi.reshape(nb, K)
+        x = rng.integers(0, n_cats, size=(B, n_sets))
+    meta = {"kind": "sum_layer", "n_sets": n_sets, "M": M, "keep": keep, "n_layer_edges": n_sum_edges * K * K,
+            "S0": S0, "P0": P0, "T0": T0}
+    return Workload(name=name or f"layer_S{n_sets}_M{M}_K{K}_keep{keep}_B{B}", K=K, n_blocks=n_blocks, root_block=root,
+                    type=typ, n_real=n_real, child_ptr=ptr, child=child, param_blk=param, n_param_blocks=n_param_blocks,
+                    in_var=in_var, in_table=in_table, n_vars=n_sets, n_cats=n_cats, n_tables=nE, theta=theta,
+                    tables=tables, x=np.ascontiguousarray(x, dtype=np.int32), meta=meta)
+
+
+def sum_layer_dense(w: Workload, s: int) -> np.ndarray:
+    """float64 [M, M] weight matrix of set s of a `sum_layer` workload (zeros where edge blocks were dropped)."""
+    K, nb, M = w.K, w.meta["M"] // w.K, w.meta["M"]
+    out = np.zeros((M, M))
+    for i in range(nb):
+        u = w.meta["S0"] + s * nb + i
+        for e in range(int(w.child_ptr[u]), int(w.child_ptr[u + 1])):
+            j = int(w.child[e]) - w.meta["P0"] - s * nb
+            out[i * K:(i + 1) * K, j * K:(j + 1) * K] = w.theta[int(w.param_blk[e]) + 1]
+    return out
 
 
 # --------------------------------------------------------------------------------------------

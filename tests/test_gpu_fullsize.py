@@ -29,6 +29,7 @@ def test_full_size_config(idx):
     print("  compiled tables (built by the device compiler) against the compile oracle, bit for bit", flush=True)
     assert_device_tables_match_oracle(c.handle, w)
     c.set_batch(w.x)
+    c._ws.fill_(255)                       # NaN bit patterns: nothing may rely on a cleared workspace
     print("  gpu forward/backward at full batch", flush=True)
     ll = c.forward().double().cpu().numpy()
     c.backward()

@@ -29,6 +29,7 @@ def to_user_rows(buf, K, B):
 def gpu_run(w, mask=None, backward=True):
     c = pcb.Circuit(w)
     c.set_batch(w.x, mask)
+    c._ws.fill_(255)                       # NaN bit patterns: nothing may rely on a cleared workspace
     ll = c.forward().double().cpu().numpy()
     out = {"ll": ll}
     if backward:
@@ -118,6 +119,20 @@ def test_small_block_sizes_use_generic_kernels(make):
     w = make()
     print(f"case generic {w.name}", flush=True)
     check_all(w)
+
+
+@pytest.mark.parametrize("n_sets,M,K,keep,B", [
+    (5, 128, 32, 0.3, 50),      # MFMA kernels, several groups of different widths
+    (3, 256, 32, 1.0, 70),      # dense sets
+    (3, 256, 64, 0.5, 33),
+    (4, 64, 8, 0.4, 40),        # small blocks: generic kernels
+    (3, 32, 1, 0.5, 37),        # block size 1: one block per node
+])
+def test_block_sparse_sum_layer(n_sets, M, K, keep, B):
+    w = W.sum_layer(n_sets, M, K, B, 2406 + K, keep=keep, n_cats=16)
+    print(f"case layer {w.name}", flush=True)
+    got, _ = check_all(w)
+    assert_device_tables_match_oracle(got["circuit"].handle, w)
 
 
 def test_config1_full_size():
