@@ -107,6 +107,7 @@ pc_status build_groups(std::vector<Row> &rows, int32_t max_groups, int32_t tol_p
         std::sort(row.nbrs.begin(), row.nbrs.end());
         if (!fits_i32(row.id)) return fail(PC_ERR_TOO_LARGE, "node offset exceeds int32");
         gt.ids.push_back((int32_t)row.id);
+        gt.aux.push_back(cnt << AUX_COUNT_SHIFT);
         for (int32_t j = 0; j < gt.width; ++j) {
             int64_t a = 0, p = 0;
             if (j < cnt) { a = row.nbrs[j].first; p = row.nbrs[j].second; }
@@ -278,10 +279,10 @@ pc_status compile_host(const pc_dag *d, pc_circuit *c, bool tables_on_host)
             st = build_groups(bwd_rows, d->max_groups, d->tol_permille, layer.bwd);
             if (st != PC_OK) return st;
             for (GroupTab &gt : layer.bwd)
-                for (int32_t id : gt.ids) {
-                    const int32_t ch = id / K - 1;
-                    gt.aux.push_back(bwd_row_flags(layer.kind, d->type[ch], layer.depth, last_parent_depth[ch],
-                                                   first_parent_depth[ch]));
+                for (size_t i = 0; i < gt.ids.size(); ++i) {
+                    const int32_t ch = gt.ids[i] / K - 1;
+                    gt.aux[i] |= bwd_row_flags(layer.kind, d->type[ch], layer.depth, last_parent_depth[ch],
+                                               first_parent_depth[ch]);
                 }
         }
         c->layers.push_back(std::move(layer));

@@ -254,6 +254,8 @@ pc_status build_tables_device(const pc_dag *d, pc_circuit *c, void *stream_v)
         for (int32_t id : L.blk_ids) { const int32_t u = id / K - 1; counts.push_back(ptr32[u + 1] - ptr32[u]); }
         assign_groups(counts, d->max_groups, d->tol_permille, L.fwd, grp, rank);
         for (size_t i = 0; i < L.blk_ids.size(); ++i) { const int32_t u = L.blk_ids[i] / K - 1; f_grp[u] = grp[i]; f_rank[u] = rank[i]; }
+        for (GroupTab &g : L.fwd) g.aux.assign(g.n_rows, 0);
+        for (size_t i = 0; i < L.blk_ids.size(); ++i) L.fwd[grp[i]].aux[rank[i]] = counts[i] << AUX_COUNT_SHIFT;
         for (GroupTab &g : L.fwd) g.tied_in_group = L.kind == KIND_SUM;       // conservative: only the generic kernels look at it
         std::vector<int32_t> &rows = rows_of_layer[li];
         std::sort(rows.begin(), rows.end(), [&](int32_t a, int32_t b) { return rchild[a] < rchild[b]; });
@@ -264,7 +266,8 @@ pc_status build_tables_device(const pc_dag *d, pc_circuit *c, void *stream_v)
         for (GroupTab &g : L.bwd) g.aux.assign(g.n_rows, 0);
         for (size_t i = 0; i < rows.size(); ++i) {
             const int32_t ch = rchild[rows[i]];
-            L.bwd[grp[i]].aux[rank[i]] = bwd_row_flags(L.kind, d->type[ch], L.depth, c->an_last_parent_depth[ch],
+            L.bwd[grp[i]].aux[rank[i]] = (counts[i] << AUX_COUNT_SHIFT) |
+                                         bwd_row_flags(L.kind, d->type[ch], L.depth, c->an_last_parent_depth[ch],
                                                        c->an_first_parent_depth[ch]);
         }
     }

@@ -15,7 +15,9 @@ enum : int { KIND_INPUT = 0, KIND_PRODUCT = 1, KIND_SUM = 2 };
 //              afterwards (log_nf of Alg. 3 / 4 is produced here)
 //   BWD_FIRST  this is the first layer of the backward sweep that adds to the child's flow: the kernel stores
 //              instead of accumulating, so the flow buffer needs no clearing (the '=' of Alg. 4's last line)
-enum : int32_t { BWD_FINAL = 1, BWD_FIRST = 2 };
+// The per-row word of a group (GroupTab::aux) holds these flags in its low byte and the row's number of real
+// neighbours (the rest of the row is padding) from bit AUX_COUNT_SHIFT up.
+enum : int32_t { BWD_FINAL = 1, BWD_FIRST = 2, AUX_COUNT_SHIFT = 8 };
 inline int32_t bwd_row_flags(int layer_kind, int child_kind, int32_t layer_depth, int32_t last_parent_depth,
                              int32_t first_parent_depth)
 {
@@ -29,7 +31,7 @@ inline int32_t bwd_row_flags(int layer_kind, int child_kind, int32_t layer_depth
 struct GroupTab {
     int32_t n_rows = 0, width = 0;
     std::vector<int32_t> ids, nbr, par;              // host copies
-    std::vector<int32_t> aux;                        // per row of a backward group: BWD_* flags
+    std::vector<int32_t> aux;                        // per row: neighbour count << AUX_COUNT_SHIFT | BWD_* flags
     int32_t *d_ids = nullptr, *d_nbr = nullptr, *d_par = nullptr, *d_aux = nullptr;
     bool tied_in_group = false;                       // a parameter block occurs twice: flows need atomics
 };

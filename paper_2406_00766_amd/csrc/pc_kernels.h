@@ -11,7 +11,7 @@ struct GroupDev {            // device view of one table group
     int32_t n_rows, width;
     const int32_t *ids, *nbr, *par;
     bool tied;
-    const int32_t *aux;      // backward groups: per row, bit 0 = flow final after this layer, bit 1 = first layer to write it
+    const int32_t *aux;      // per row: real neighbours << 8 | bit 0 flow final after this layer | bit 1 first layer to write it
 };
 
 struct ParamFlowDev {        // parameter blocks with the (sum block, child block) pairs that use them

@@ -210,38 +210,55 @@ __device__ inline void block_col_max(float (&mx)[4], float (*red)[64], int wave,
     }
 }
 
+// Both kernels walk the row's real neighbours (count in the row's flag word) U at a time: the U neighbour ids are
+// fetched first, then all their loads are issued together, so a row costs one memory round trip per U neighbours
+// instead of one per neighbour (small layers are latency-bound).  RPT = rows per thread = ceil(K / 16).
+
 // forward (Sec. 3): s = sum of the children's residuals; the column maximum over the K rows is rounded to an
 // integer and moved into R
+template <int RPT, int U>
 __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *__restrict__ R,
                                                   const int32_t *__restrict__ ids, const int32_t *__restrict__ nbr,
-                                                  int32_t width, int32_t K, int64_t Bs)
+                                                  const int32_t *__restrict__ flags, int32_t width, int32_t K, int64_t Bs)
 {
-    constexpr int RPT = 8;                                             // rows per thread (K <= 128)
     __shared__ float red[4][64];
     const int r = blockIdx.x;
     const int rg = threadIdx.x >> 4, cl = threadIdx.x & 15, wave = threadIdx.x >> 6;
     const int64_t b = (int64_t)blockIdx.y * 64 + cl * 4;
     const bool in = b < Bs;                                            // Bs is a multiple of 32: b..b+3 all inside
     const int32_t *row_nbr = nbr + (int64_t)r * width;
+    const int32_t cnt = flags[r] >> 8;
+    const int32_t id = ids[r];
     float4 s[RPT];
     float mx[4] = {PC_NEG_INF, PC_NEG_INF, PC_NEG_INF, PC_NEG_INF};
     float4 rsum = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
     for (int i = 0; i < RPT; ++i) s[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (in) {
-        for (int j = 0; j < width; ++j) {
-            const int32_t ch = row_nbr[j];
+        for (int j0 = 0; j0 < cnt; j0 += U) {
+            int32_t ch[U];
 #pragma unroll
-            for (int i = 0; i < RPT; ++i) {
-                const int k = rg + 16 * i;
-                if (k < K) {
-                    const float4 t = *reinterpret_cast<const float4 *>(l + (int64_t)(ch + k) * Bs + b);
-                    s[i].x += t.x; s[i].y += t.y; s[i].z += t.z; s[i].w += t.w;
+            for (int u = 0; u < U; ++u) ch[u] = j0 + u < cnt ? row_nbr[j0 + u] : 0;
+            float4 t[U][RPT], tr[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const bool on = j0 + u < cnt;                          // uniform over the workgroup
+#pragma unroll
+                for (int i = 0; i < RPT; ++i) {
+                    const int k = rg + 16 * i;
+                    t[u][i] = (on && k < K) ? *reinterpret_cast<const float4 *>(l + (int64_t)(ch[u] + k) * Bs + b)
+                                            : make_float4(0.f, 0.f, 0.f, 0.f);
                 }
+                tr[u] = (on && rg == 0) ? *reinterpret_cast<const float4 *>(R + (int64_t)(ch[u] / K) * Bs + b)
+                                        : make_float4(0.f, 0.f, 0.f, 0.f);
             }
-            if (rg == 0) {
-                const float4 t = *reinterpret_cast<const float4 *>(R + (int64_t)(ch / K) * Bs + b);
-                rsum.x += t.x; rsum.y += t.y; rsum.z += t.z; rsum.w += t.w;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int i = 0; i < RPT; ++i) {
+                    s[i].x += t[u][i].x; s[i].y += t[u][i].y; s[i].z += t[u][i].z; s[i].w += t[u][i].w;
+                }
+                rsum.x += tr[u].x; rsum.y += tr[u].y; rsum.z += tr[u].z; rsum.w += tr[u].w;
             }
         }
 #pragma unroll
@@ -256,7 +273,6 @@ __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *
     float sh[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) sh[v] = mx[v] > PC_NEG_INF ? rintf(mx[v]) : 0.0f;
-    const int32_t id = ids[r];
     if (rg == 0)
         *reinterpret_cast<float4 *>(R + (int64_t)(id / K) * Bs + b) = make_float4(rsum.x + sh[0], rsum.y + sh[1], rsum.z + sh[2], rsum.w + sh[3]);
 #pragma unroll
@@ -271,12 +287,12 @@ __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *
 // F_child += sum of the parents' flows ('=' where this is the first layer that feeds the block, flag bit 1, so
 // the flow buffer is never cleared).  Where this layer is the last one that feeds a SUM block (flag bit 0) its
 // flow is final, so log_nf = log F - l (Alg. 3 / 4) and its column maximum per block are produced here.
+template <int RPT, int U>
 __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, float *__restrict__ F, float *__restrict__ N,
                                                   float *__restrict__ nfmax, const int32_t *__restrict__ ids,
                                                   const int32_t *__restrict__ nbr, const int32_t *__restrict__ flags,
                                                   int32_t width, int32_t K, int64_t Bs)
 {
-    constexpr int RPT = 8;
     __shared__ float red[4][64];
     const int r = blockIdx.x;
     const int rg = threadIdx.x >> 4, cl = threadIdx.x & 15, wave = threadIdx.x >> 6;
@@ -286,24 +302,39 @@ __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, f
     const int32_t id = ids[r];
     const int32_t fl = flags[r];                                        // uniform over the workgroup
     const bool final_flow = (fl & 1) != 0, first = (fl & 2) != 0;
-    float4 f[RPT];
+    const int32_t cnt = fl >> 8;
+    float4 f[RPT], lv[RPT];
     if (in) {
 #pragma unroll
         for (int i = 0; i < RPT; ++i) {
             const int k = rg + 16 * i;
             f[i] = (k < K && !first) ? *reinterpret_cast<const float4 *>(F + (int64_t)(id + k) * Bs + b)
                                      : make_float4(0.f, 0.f, 0.f, 0.f);
+            // the block's own log-probabilities, needed only for log_nf: fetched with everything else
+            lv[i] = (k < K && final_flow) ? *reinterpret_cast<const float4 *>(l + (int64_t)(id + k) * Bs + b)
+                                          : make_float4(0.f, 0.f, 0.f, 0.f);
         }
-        for (int j = 0; j < width; ++j) {
-            const int32_t pa = row_nbr[j];                              // padding -> null block, flow 0
+        for (int j0 = 0; j0 < cnt; j0 += U) {
+            int32_t pa[U];
 #pragma unroll
-            for (int i = 0; i < RPT; ++i) {
-                const int k = rg + 16 * i;
-                if (k < K) {
-                    const float4 t = *reinterpret_cast<const float4 *>(F + (int64_t)(pa + k) * Bs + b);
-                    f[i].x += t.x; f[i].y += t.y; f[i].z += t.z; f[i].w += t.w;
+            for (int u = 0; u < U; ++u) pa[u] = j0 + u < cnt ? row_nbr[j0 + u] : 0;
+            float4 t[U][RPT];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const bool on = j0 + u < cnt;                          // uniform over the workgroup
+#pragma unroll
+                for (int i = 0; i < RPT; ++i) {
+                    const int k = rg + 16 * i;
+                    t[u][i] = (on && k < K) ? *reinterpret_cast<const float4 *>(F + (int64_t)(pa[u] + k) * Bs + b)
+                                            : make_float4(0.f, 0.f, 0.f, 0.f);
                 }
             }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int i = 0; i < RPT; ++i) {
+                    f[i].x += t[u][i].x; f[i].y += t[u][i].y; f[i].z += t[u][i].z; f[i].w += t[u][i].w;
+                }
         }
 #pragma unroll
         for (int i = 0; i < RPT; ++i) {
@@ -318,12 +349,11 @@ __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, f
         for (int i = 0; i < RPT; ++i) {
             const int k = rg + 16 * i;
             if (k < K) {
-                const float4 lv = *reinterpret_cast<const float4 *>(l + (int64_t)(id + k) * Bs + b);
                 float4 nf;
-                nf.x = (f[i].x > 0.0f && lv.x > PC_NEG_INF) ? __logf(f[i].x) - lv.x : PC_NEG_INF;
-                nf.y = (f[i].y > 0.0f && lv.y > PC_NEG_INF) ? __logf(f[i].y) - lv.y : PC_NEG_INF;
-                nf.z = (f[i].z > 0.0f && lv.z > PC_NEG_INF) ? __logf(f[i].z) - lv.z : PC_NEG_INF;
-                nf.w = (f[i].w > 0.0f && lv.w > PC_NEG_INF) ? __logf(f[i].w) - lv.w : PC_NEG_INF;
+                nf.x = (f[i].x > 0.0f && lv[i].x > PC_NEG_INF) ? __logf(f[i].x) - lv[i].x : PC_NEG_INF;
+                nf.y = (f[i].y > 0.0f && lv[i].y > PC_NEG_INF) ? __logf(f[i].y) - lv[i].y : PC_NEG_INF;
+                nf.z = (f[i].z > 0.0f && lv[i].z > PC_NEG_INF) ? __logf(f[i].z) - lv[i].z : PC_NEG_INF;
+                nf.w = (f[i].w > 0.0f && lv[i].w > PC_NEG_INF) ? __logf(f[i].w) - lv[i].w : PC_NEG_INF;
                 *reinterpret_cast<float4 *>(N + (int64_t)(id + k) * Bs + b) = nf;
                 mx[0] = fmaxf(mx[0], nf.x); mx[1] = fmaxf(mx[1], nf.y); mx[2] = fmaxf(mx[2], nf.z); mx[3] = fmaxf(mx[3], nf.w);
             }
@@ -508,7 +538,7 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
     constexpr int NF4 = TM * KC / 4 / 64;                               // 16-byte loads per lane per chunk
     constexpr int LDA = BWD ? TM : KC + 4;                              // LDS row stride (floats); KC+4: b128 reads conflict-free
     constexpr int TILE = (BWD ? KC : TM) * LDA;
-    constexpr int XCH = RT * 16 * 64 + 64;                              // one partial accumulator + its maxima
+    constexpr int XCH = RT * 16 * 64 + 128;                             // one partial accumulator, its maxima and references
     constexpr int WSZ = TILE > XCH ? TILE : XCH;
     static_assert(K % TM == 0 && (SPLIT == 1 || SPLIT == 2 || SPLIT == 4), "tile shape");
     __shared__ float lds[4 * WSZ];
@@ -522,23 +552,16 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
     const int64_t col = (active ? col0 : 0) + l32;
     const int32_t *row_nbr = nbr + (int64_t)r * width, *row_par = par + (int64_t)r * width;
     const int32_t id = ids[r];
+    const int32_t fl = flags[r];                                        // wave-uniform
     // backward: the first layer of the sweep that feeds this block stores its flow, later ones accumulate
-    const bool first = BWD ? (flags[r] & 2) != 0 : true;                // wave-uniform
+    const bool first = (fl & 2) != 0;
     float *buf = lds + wave * WSZ;
+    const int n_chunks = (fl >> 8) * CPB;                               // real neighbours; padding sits at the end of a row
 
-    int n_real = 0;                                                     // padding sits at the end of a row
-    while (n_real < width && row_par[n_real] != 0) ++n_real;
-    const int n_chunks = n_real * CPB;
-
-    // block reference of this row: forward max of the children's (and stored), backward the row's own
-    float Rrow;
-    if (BWD) {
-        Rrow = R[(int64_t)(id / K) * Bs + col];
-    } else {
-        Rrow = PC_NEG_INF;
-        for (int j = 0; j < n_real; ++j) Rrow = fmaxf(Rrow, R[(int64_t)(row_nbr[j] / K) * Bs + col]);
-        if (active && sub == 0 && sp == 0 && half == 0) R[(int64_t)(id / K) * Bs + col] = Rrow;
-    }
+    // block reference of this row.  Backward: the row's own.  Forward: the maximum of the children's, found
+    // on the fly -- Rrow is the maximum over the chunks seen so far and the running maximum m is relative to it
+    float Rrow = PC_NEG_INF;
+    if (BWD) Rrow = R[(int64_t)(id / K) * Bs + col];
 
     floatx16 acc[RT];
 #pragma unroll
@@ -546,6 +569,16 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[rt][e] = 0.0f;
     float m = PC_NEG_INF;
+    // backward: the rows' own log-probabilities are needed only at the end; fetched now, their latency is hidden
+    // behind the whole reduction (short reductions are latency-bound)
+    floatx16 lown[BWD ? RT : 1];
+    if (BWD) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                lown[rt][e] = l[((int64_t)(id + sub * TM) + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4)) * Bs + col];
+    }
 
     // Two register sets (A, B) hold the fetched theta sub-block, neighbour values and block scalars of two
     // consecutive chunks of this wave: while one set is consumed the other is being loaded.
@@ -586,6 +619,11 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
             const int t = lane + i * 64;                                                                              \
             const int o = BWD ? (t / (TM / 4)) * LDA + (t % (TM / 4)) * 4 : (t / (KC / 4)) * LDA + (t % (KC / 4)) * 4; \
             *reinterpret_cast<floatx4 *>(buf + o) = TH[i];                                                            \
+        }                                                                                                             \
+        if (!BWD) {                                                     /* a larger reference: m moves by an exact integer */ \
+            const float Rn = fmaxf(Rrow, RB);                                                                         \
+            m += Rrow - Rn;                                             /* -inf stays -inf (RB is finite) */          \
+            Rrow = Rn;                                                                                                \
         }                                                                                                             \
         const float d = BWD ? Rrow - RB : RB - Rrow;                    /* exact integer <= 0 */                      \
         float cmax;                                                                                                   \
@@ -646,13 +684,21 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
 #pragma unroll
                 for (int e = 0; e < 16; ++e) buf[(rt * 16 + e) * 64 + lane] = acc[rt][e];
             buf[RT * 16 * 64 + lane] = m;
+            if (!BWD) buf[RT * 16 * 64 + 64 + lane] = Rrow;
         }
         __syncthreads();
         if (sp != 0) return;
 #pragma unroll
         for (int s = 1; s < SPLIT; ++s) {
             const float *ob = lds + (wave + s) * WSZ;
-            const float mo = ob[RT * 16 * 64 + lane];
+            float mo = ob[RT * 16 * 64 + lane];
+            if (!BWD) {                                                 // bring both partial sums to the larger reference
+                const float Ro = ob[RT * 16 * 64 + 64 + lane];          // -inf: that wave had no chunk (its sum is 0)
+                const float Rn = fmaxf(Rrow, Ro);
+                m += Rrow - Rn;
+                mo = Ro > PC_NEG_INF ? mo + (Ro - Rn) : PC_NEG_INF;
+                Rrow = Rn;
+            }
             const float m_new = fmaxf(m, mo);
             const bool dead = !(m_new > PC_NEG_INF);
             const float s0 = dead ? 1.0f : __expf(m - m_new), s1 = dead ? 0.0f : __expf(mo - m_new);
@@ -664,6 +710,7 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
         }
     }
     if (!active) return;
+    if (!BWD && sub == 0 && half == 0) R[(int64_t)(id / K) * Bs + col] = Rrow;
     const int64_t base = (int64_t)(id + sub * TM);
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
@@ -673,7 +720,7 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
             const float a = acc[rt][e];
             const int64_t at = (base + i) * Bs + col;
             if (BWD) {
-                const float lc = l[at];
+                const float lc = lown[rt][e];
                 const float add = (a > 0.0f && lc > PC_NEG_INF) ? __expf(__logf(a) + m + lc) : 0.0f;
                 if (first) F[at] = add;
                 else if (add > 0.0f) F[at] += add;
@@ -1027,12 +1074,21 @@ void launch_input_bwd(const float *F, const int32_t *xT, const GroupDev &g, int3
     }
 }
 
+// rows per thread and neighbours in flight by block size: about 16 outstanding 16-byte loads per thread
+#define PC_DISPATCH_PROD(KERNEL, ...)                                                                      \
+    do {                                                                                                   \
+        if (K <= 16) hipLaunchKernelGGL((KERNEL<1, 8>), __VA_ARGS__);                                      \
+        else if (K <= 32) hipLaunchKernelGGL((KERNEL<2, 8>), __VA_ARGS__);                                 \
+        else if (K <= 64) hipLaunchKernelGGL((KERNEL<4, 4>), __VA_ARGS__);                                 \
+        else hipLaunchKernelGGL((KERNEL<8, 2>), __VA_ARGS__);                                              \
+    } while (0)
+
 void launch_prod_fwd(float *l, float *R, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
 {
     if (g.n_rows == 0) return;
     Timed timed(KC_PROD_FWD, s);
     dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 63) / 64));
-    hipLaunchKernelGGL(k_prod_fwd, grid, dim3(256), 0, s, l, R, g.ids, g.nbr, g.width, K, Bs);
+    PC_DISPATCH_PROD(k_prod_fwd, grid, dim3(256), 0, s, l, R, g.ids, g.nbr, g.aux, g.width, K, Bs);
 }
 
 void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
@@ -1040,9 +1096,8 @@ void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const Gro
     if (g.n_rows == 0) return;
     Timed timed(KC_PROD_BWD, s);
     dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 63) / 64));
-    hipLaunchKernelGGL(k_prod_bwd, grid, dim3(256), 0, s, l, F, N, nfmax, g.ids, g.nbr, g.aux, g.width, K, Bs);
+    PC_DISPATCH_PROD(k_prod_bwd, grid, dim3(256), 0, s, l, F, N, nfmax, g.ids, g.nbr, g.aux, g.width, K, Bs);
 }
-
 
 // forward / backward-to-children: (K, rows per wave tile / 32, waves sharing one tile)
 #define PC_SUM_CASE(KK, RR, SS, BWD, ...)                                                                  \
@@ -1080,7 +1135,7 @@ void launch_sum_fwd(const float *theta, float *l, float *R, const GroupDev &g, i
         const int64_t cols_per_wg = 32 * (4 / split);
         dim3 grid((unsigned)(g.n_rows * (K / (32 * rt))), (unsigned)((Bs + cols_per_wg - 1) / cols_per_wg));
         PC_DISPATCH_SUM(false, grid, dim3(256), 0, s, theta, l, R, (const float *)nullptr, (const float *)nullptr,
-                        (float *)nullptr, g.ids, g.nbr, g.par, (const int32_t *)nullptr, g.width, Bs);
+                        (float *)nullptr, g.ids, g.nbr, g.par, g.aux, g.width, Bs);
     } else {
         const int64_t items = (int64_t)g.n_rows * K * Bs;
         hipLaunchKernelGGL(k_sum_fwd_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, l, R, g.ids, g.nbr, g.par,
