@@ -275,7 +275,7 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
 
     // MFMA block sizes: parameter flows of the whole circuit in one launch after the sweep (N and nfmax of
     // every sum layer stay valid until then); other block sizes: layer by layer
-    const bool batched_params = param_flow_uses_mfma(K);
+    const bool batched_params = param_flow_by_block(K);
     // no clearing of F: every block's flow is stored by the first layer that feeds it, blocks nobody feeds are
     // initialised here
     launch_init_flows(l, F, N, nfmax, c->d_init_ids, (int32_t)c->init_ids.size(), (c->root_block + 1) * K, K, w.Bs, B, s);

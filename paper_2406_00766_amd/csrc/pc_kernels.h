@@ -61,7 +61,7 @@ void launch_sum_bwd_child(const float *theta, const float *l, const float *R, co
                           const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s);
 void launch_sum_bwd_param_generic(const float *theta, const float *l, const float *R, const float *N, float *G,
                                   const GroupDev &g, int32_t K, int64_t Bs, int32_t B, hipStream_t s);
-bool param_flow_uses_mfma(int32_t K);
+bool param_flow_by_block(int32_t K);
 void launch_param_flow(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *G,
                        const ParamFlowDev &pf, int32_t K, int64_t Bs, hipStream_t s);
 void launch_em(float *theta, float *tables, float *theta_flow, float *table_flow, const EmDev &em, int32_t K,

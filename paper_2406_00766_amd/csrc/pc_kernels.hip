@@ -495,6 +495,201 @@ __global__ __launch_bounds__(256) void k_sum_bwd_param_generic(const float *__re
 }
 
 // ------------------------------------------------------------------------------------------
+// small-block sum-layer kernels (K in {1, 2, 4, 8, 16}): block-based parallelisation (Sec. 4.1) on the vector
+// ALU.  A thread owns one sample column of one node block: it reads each of the K neighbour values once,
+// exponentiates it once and uses it for all K outputs of the block -- the K-fold cut in reloads and in
+// exponentials that Sec. 4.1 describes.  The K x K weights have workgroup-uniform addresses and ride in scalar
+// registers.  Linear-space accumulators with a running maximum, as in the MFMA kernels.
+// ------------------------------------------------------------------------------------------
+#define PC_SPLIT 43.0f
+#define PC_SPLIT_CAP 44.5f
+template <int K>
+__global__ __launch_bounds__(256) void k_sum_fwd_small(const float *__restrict__ theta, float *__restrict__ l,
+                                                       float *__restrict__ R, const int32_t *__restrict__ ids,
+                                                       const int32_t *__restrict__ nbr, const int32_t *__restrict__ par,
+                                                       const int32_t *__restrict__ flags, int32_t width, int64_t Bs)
+{
+    const int r = blockIdx.x;
+    const int64_t b = (int64_t)blockIdx.y * 256 + threadIdx.x;
+    if (b >= Bs) return;
+    const int32_t *row_nbr = nbr + (int64_t)r * width, *row_par = par + (int64_t)r * width;
+    const int32_t cnt = flags[r] >> 8, id = ids[r];
+    float acc[K];
+#pragma unroll
+    for (int i = 0; i < K; ++i) acc[i] = 0.0f;
+    float m = PC_NEG_INF, Rrow = PC_NEG_INF;                            // Rrow: largest child reference seen so far
+    for (int j = 0; j < cnt; ++j) {
+        const int32_t ns = row_nbr[j];
+        const float *th = theta + row_par[j];
+        float v[K];
+#pragma unroll
+        for (int jj = 0; jj < K; ++jj) v[jj] = l[(int64_t)(ns + jj) * Bs + b];
+        const float RB = R[(int64_t)(ns / K) * Bs + b];
+        const float Rn = fmaxf(Rrow, RB);
+        m += Rrow - Rn;                                                 // exact integer shift; -inf stays -inf
+        Rrow = Rn;
+        const float d = RB - Rrow;
+        float bm = v[0];
+#pragma unroll
+        for (int jj = 1; jj < K; ++jj) bm = fmaxf(bm, v[jj]);
+        bm += d;
+        if (bm > m) {
+            const float sc = __expf(m - bm);                            // m = -inf: 0, and the accumulators are 0
+#pragma unroll
+            for (int i = 0; i < K; ++i) acc[i] *= sc;
+            m = bm;
+        }
+        const float sh = m > PC_NEG_INF ? d - m : 0.0f;                 // dead column: v = -inf -> p = 0
+        float pv[K];
+#pragma unroll
+        for (int jj = 0; jj < K; ++jj) pv[jj] = __expf(v[jj] + sh);
+#pragma unroll
+        for (int i = 0; i < K; ++i) {
+#pragma unroll
+            for (int jj = 0; jj < K; ++jj) acc[i] = fmaf(th[i * K + jj], pv[jj], acc[i]);
+            if (K == 16 && i % 4 == 3) __builtin_amdgcn_sched_barrier(0);   // keeps the 256 weights from all being live in scalar registers
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < K; ++i) l[(int64_t)(id + i) * Bs + b] = acc[i] > 0.0f ? m + __logf(acc[i]) : PC_NEG_INF;
+    R[(int64_t)(id / K) * Bs + b] = Rrow;
+}
+
+template <int K>
+__global__ __launch_bounds__(256) void k_sum_bwd_small(const float *__restrict__ theta, const float *__restrict__ l,
+                                                       const float *__restrict__ R, const float *__restrict__ N,
+                                                       const float *__restrict__ nfmax, float *__restrict__ F,
+                                                       const int32_t *__restrict__ ids, const int32_t *__restrict__ nbr,
+                                                       const int32_t *__restrict__ par, const int32_t *__restrict__ flags,
+                                                       int32_t width, int64_t Bs)
+{
+    const int r = blockIdx.x;
+    const int64_t b = (int64_t)blockIdx.y * 256 + threadIdx.x;
+    if (b >= Bs) return;
+    const int32_t *row_nbr = nbr + (int64_t)r * width, *row_par = par + (int64_t)r * width;
+    const int32_t fl = flags[r], id = ids[r];
+    const int32_t cnt = fl >> 8;
+    const bool first = (fl & 2) != 0;
+    const float Rc = R[(int64_t)(id / K) * Bs + b];
+    float lown[K];
+#pragma unroll
+    for (int jj = 0; jj < K; ++jj) lown[jj] = l[(int64_t)(id + jj) * Bs + b];
+    float acc[K];
+#pragma unroll
+    for (int jj = 0; jj < K; ++jj) acc[jj] = 0.0f;
+    float m = PC_NEG_INF;
+    for (int j = 0; j < cnt; ++j) {
+        const int32_t ms = row_nbr[j];
+        const float *th = theta + row_par[j];
+        float nv[K];
+#pragma unroll
+        for (int i = 0; i < K; ++i) nv[i] = N[(int64_t)(ms + i) * Bs + b];
+        const float d = Rc - R[(int64_t)(ms / K) * Bs + b];
+        const float bm = nfmax[(int64_t)(ms / K) * Bs + b] + d;
+        if (bm > m) {
+            const float sc = __expf(m - bm);
+#pragma unroll
+            for (int jj = 0; jj < K; ++jj) acc[jj] *= sc;
+            m = bm;
+        }
+        const float sh = m > PC_NEG_INF ? d - m : 0.0f;
+        float pv[K];
+#pragma unroll
+        for (int i = 0; i < K; ++i) pv[i] = __expf(nv[i] + sh);
+#pragma unroll
+        for (int i = 0; i < K; ++i)
+#pragma unroll
+            for (int jj = 0; jj < K; ++jj) acc[jj] = fmaf(th[i * K + jj], pv[i], acc[jj]);
+    }
+#pragma unroll
+    for (int jj = 0; jj < K; ++jj) {
+        const int64_t at = (int64_t)(id + jj) * Bs + b;
+        const float add = (acc[jj] > 0.0f && lown[jj] > PC_NEG_INF) ? __expf(__logf(acc[jj]) + m + lown[jj]) : 0.0f;
+        if (first) F[at] = add;                                         // first layer that feeds the block stores
+        else if (add > 0.0f) F[at] += add;
+    }
+}
+
+// Backward to the parameters for small blocks, by parameter block like k_param_flow_mfma: one wave per parameter
+// block, lanes = samples.  Per pass a lane holds IG x K partial sums of the two-factor products (the same
+// balanced split as the MFMA kernel); at the end the 64 lanes are reduced with an exchange-and-halve butterfly
+// (each step a lane hands half of its values to its partner and adds the partner's other half), which costs
+// about 4 operations per value instead of 12.
+template <int K, int IG>
+__global__ __launch_bounds__(256) void k_param_flow_small(const float *__restrict__ theta, const float *__restrict__ l,
+                                                          const float *__restrict__ R, const float *__restrict__ N,
+                                                          const float *__restrict__ nfmax, float *__restrict__ G,
+                                                          const int32_t *__restrict__ pf_pb, const int32_t *__restrict__ pf_ptr,
+                                                          const int32_t *__restrict__ pf_sum, const int32_t *__restrict__ pf_child,
+                                                          int32_t n_pb, int64_t Bs)
+{
+    constexpr int A = IG * K;                                           // values per lane and pass
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int64_t pidx = (int64_t)blockIdx.x * 4 + wave;
+    if (pidx >= n_pb) return;                                           // wave-uniform; no workgroup barrier below
+    const int32_t pb = pf_pb[pidx];
+    const int i0 = pf_ptr[pidx], i1 = pf_ptr[pidx + 1];
+    for (int ig = 0; ig < K; ig += IG) {
+        float acc[A];
+#pragma unroll
+        for (int a = 0; a < A; ++a) acc[a] = 0.0f;
+        for (int inst = i0; inst < i1; ++inst) {
+            const int32_t ms = pf_sum[inst], ns = pf_child[inst];
+            for (int64_t b = lane; b < Bs; b += 64) {
+                const float mx = nfmax[(int64_t)(ms / K) * Bs + b];
+                const float dR = R[(int64_t)(ns / K) * Bs + b] - R[(int64_t)(ms / K) * Bs + b];
+                const bool live = mx > PC_NEG_INF;                      // dead sample: both factors 0
+                const float qa = live ? PC_SPLIT - mx : PC_NEG_INF;
+                const float qb = live ? mx + dR - PC_SPLIT : PC_NEG_INF;
+                float fa[IG], fb[K];
+#pragma unroll
+                for (int i = 0; i < IG; ++i) fa[i] = __expf(N[(int64_t)(ms + ig + i) * Bs + b] + qa);
+#pragma unroll
+                for (int jj = 0; jj < K; ++jj) fb[jj] = __expf(fminf(l[(int64_t)(ns + jj) * Bs + b] + qb, PC_SPLIT_CAP));
+#pragma unroll
+                for (int i = 0; i < IG; ++i)
+#pragma unroll
+                    for (int jj = 0; jj < K; ++jj) acc[i * K + jj] = fmaf(fa[i], fb[jj], acc[i * K + jj]);
+            }
+        }
+        // reduce over the 64 lanes
+        int cur = A, idx = 0;                                           // idx: first of the values this lane still holds
+#pragma unroll
+        for (int dist = 32; dist >= 1; dist >>= 1) {
+            if (cur > 1) {
+                const int h = cur / 2;
+                const bool up = (lane & dist) != 0;
+#pragma unroll
+                for (int e = 0; e < A / 2; ++e) {
+                    if (e < h) {
+                        const float lo = acc[e], hi = acc[e + h];
+                        const float give = up ? lo : hi, keep = up ? hi : lo;
+                        acc[e] = keep + __shfl_xor(give, dist);
+                    }
+                }
+                idx += up ? h : 0;
+                cur = h;
+            } else {
+                acc[0] += __shfl_xor(acc[0], dist);
+            }
+        }
+        // cur values per lane; lanes that differ only in the bits of the plain-sum steps hold copies
+        constexpr int HALVINGS = A >= 64 ? 6 : (A == 32 ? 5 : A == 16 ? 4 : A == 8 ? 3 : A == 4 ? 2 : A == 2 ? 1 : 0);
+        constexpr int COPIES = 64 >> HALVINGS;
+        if ((lane & (COPIES - 1)) == 0) {
+#pragma unroll
+            for (int e = 0; e < (A >= 64 ? A / 64 : 1); ++e) {
+                const int a = idx + e;                                  // = i * K + jj inside this pass
+                const int64_t at = (int64_t)pb + (int64_t)ig * K + a;
+                const float th = theta[at];
+                if (th > 0.0f) G[at] += th * acc[e];
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // MFMA sum-layer kernels (K % 32 == 0).  Workgroup = 4 waves; a wave owns 32 sample columns.
 // ------------------------------------------------------------------------------------------
 
@@ -749,8 +944,6 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
 // to reach the MFMA operand layouts (batch index on k: step q pairs lanes 0-31 with sample 8*(q/4) + q%4
 // and lanes 32-63 with sample 8*(q/4) + 4 + q%4); loads of the next chunk are issued before the
 // arithmetic of the current one.
-#define PC_SPLIT 43.0f
-#define PC_SPLIT_CAP 44.5f
 template <int K, int RT, int CT>
 __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restrict__ theta, const float *__restrict__ l,
                                                             const float *__restrict__ R, const float *__restrict__ N,
@@ -1008,6 +1201,15 @@ static inline int grid_for(int64_t items, int per_block = 256, int cap = 1 << 16
 static bool g_force_generic = false;
 void set_force_generic(bool on) { g_force_generic = on; }
 static inline bool use_mfma(int32_t K) { return !g_force_generic && (K == 32 || K == 64 || K == 128); }
+static inline bool use_small(int32_t K) { return !g_force_generic && (K == 1 || K == 2 || K == 4 || K == 8 || K == 16); }
+#define PC_DISPATCH_SMALL(KERNEL, ...)                                                                     \
+    do {                                                                                                   \
+        if (K == 1) hipLaunchKernelGGL((KERNEL<1>), __VA_ARGS__);                                          \
+        else if (K == 2) hipLaunchKernelGGL((KERNEL<2>), __VA_ARGS__);                                     \
+        else if (K == 4) hipLaunchKernelGGL((KERNEL<4>), __VA_ARGS__);                                     \
+        else if (K == 8) hipLaunchKernelGGL((KERNEL<8>), __VA_ARGS__);                                     \
+        else hipLaunchKernelGGL((KERNEL<16>), __VA_ARGS__);                                                \
+    } while (0)
 
 void launch_fill(float *p, int64_t n, float v, hipStream_t s)
 {
@@ -1136,6 +1338,9 @@ void launch_sum_fwd(const float *theta, float *l, float *R, const GroupDev &g, i
         dim3 grid((unsigned)(g.n_rows * (K / (32 * rt))), (unsigned)((Bs + cols_per_wg - 1) / cols_per_wg));
         PC_DISPATCH_SUM(false, grid, dim3(256), 0, s, theta, l, R, (const float *)nullptr, (const float *)nullptr,
                         (float *)nullptr, g.ids, g.nbr, g.par, g.aux, g.width, Bs);
+    } else if (use_small(K)) {
+        dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 255) / 256));
+        PC_DISPATCH_SMALL(k_sum_fwd_small, grid, dim3(256), 0, s, theta, l, R, g.ids, g.nbr, g.par, g.aux, g.width, Bs);
     } else {
         const int64_t items = (int64_t)g.n_rows * K * Bs;
         hipLaunchKernelGGL(k_sum_fwd_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, l, R, g.ids, g.nbr, g.par,
@@ -1155,6 +1360,10 @@ void launch_sum_bwd_child(const float *theta, const float *l, const float *R, co
         dim3 grid((unsigned)(g.n_rows * (K / (32 * rt))), (unsigned)((Bs + cols_per_wg - 1) / cols_per_wg));
         PC_DISPATCH_SUM(true, grid, dim3(256), 0, s, theta, const_cast<float *>(l), const_cast<float *>(R), N, nfmax,
                         F, g.ids, g.nbr, g.par, g.aux, g.width, Bs);
+    } else if (use_small(K)) {
+        dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 255) / 256));
+        PC_DISPATCH_SMALL(k_sum_bwd_small, grid, dim3(256), 0, s, theta, l, R, N, nfmax, F, g.ids, g.nbr, g.par, g.aux,
+                          g.width, Bs);
     } else {
         const int64_t items = (int64_t)g.n_rows * K * Bs;
         hipLaunchKernelGGL(k_sum_bwd_child_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, l, R, N, F, g.ids, g.nbr,
@@ -1172,14 +1381,25 @@ void launch_sum_bwd_param_generic(const float *theta, const float *l, const floa
                        g.par, g.n_rows, g.width, K, Bs, B, g.tied ? 1 : 0);
 }
 
-bool param_flow_uses_mfma(int32_t K) { return use_mfma(K); }
+bool param_flow_by_block(int32_t K) { return use_mfma(K) || use_small(K); }
 
 void launch_param_flow(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *G,
                        const ParamFlowDev &pf, int32_t K, int64_t Bs, hipStream_t s)
 {
     if (pf.n_pb == 0) return;
     Timed timed(KC_SUM_BWD_PARAM, s);
-    if (K == 32) {
+    if (use_small(K)) {
+        const dim3 grid((unsigned)((pf.n_pb + 3) / 4));
+#define PC_PF_SMALL(KK, IG)                                                                                         \
+    hipLaunchKernelGGL((k_param_flow_small<KK, IG>), grid, dim3(256), 0, s, theta, l, R, N, nfmax, G, pf.pb, pf.ptr, \
+                       pf.sum, pf.child, pf.n_pb, Bs)
+        if (K == 1) PC_PF_SMALL(1, 1);
+        else if (K == 2) PC_PF_SMALL(2, 2);
+        else if (K == 4) PC_PF_SMALL(4, 4);
+        else if (K == 8) PC_PF_SMALL(8, 8);
+        else PC_PF_SMALL(16, 8);
+#undef PC_PF_SMALL
+    } else if (K == 32) {
         hipLaunchKernelGGL((k_param_flow_mfma<32, 1, 1>), dim3((unsigned)((pf.n_pb + 3) / 4)), dim3(256), 0, s, theta, l, R, N,
                            nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, Bs);
     } else if (K == 64) {

@@ -114,8 +114,11 @@ def test_reduced_configs_match_oracle(idx, K):
     lambda: W.hclt(7, 10, 5, 40, 9, n_cats=6),             # K = 5
     lambda: W.pd(3, 1, 8, 4, 19, 10, n_cats=3, keep=0.5),  # K = 4, block-sparse
     lambda: W.pd(2, 2, 24, 8, 65, 11, n_cats=4),           # K = 8
+    lambda: W.hmm(6, 32, 20, 16, 70, 12),                  # K = 16, tied parameter blocks
+    lambda: W.hmm(5, 8, 9, 2, 300, 13),                    # K = 2, tied, several column tiles
+    lambda: W.hclt(9, 16, 4, 90, 14, n_cats=7),            # K = 4
 ])
-def test_small_block_sizes_use_generic_kernels(make):
+def test_small_block_sizes(make):
     w = make()
     print(f"case generic {w.name}", flush=True)
     check_all(w)
@@ -125,8 +128,12 @@ def test_small_block_sizes_use_generic_kernels(make):
     (5, 128, 32, 0.3, 50),      # MFMA kernels, several groups of different widths
     (3, 256, 32, 1.0, 70),      # dense sets
     (3, 256, 64, 0.5, 33),
-    (4, 64, 8, 0.4, 40),        # small blocks: generic kernels
+    (4, 64, 8, 0.4, 40),        # small blocks: vector-ALU block kernels
+    (3, 64, 16, 0.6, 130),
+    (3, 32, 4, 0.5, 65),
+    (3, 32, 2, 0.5, 64),
     (3, 32, 1, 0.5, 37),        # block size 1: one block per node
+    (2, 24, 3, 0.7, 20),        # other block sizes: generic kernels
 ])
 def test_block_sparse_sum_layer(n_sets, M, K, keep, B):
     w = W.sum_layer(n_sets, M, K, B, 2406 + K, keep=keep, n_cats=16)
