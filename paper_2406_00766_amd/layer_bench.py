@@ -3,7 +3,7 @@ Sec. 6.1, and the block-size analysis of Sec. 4.2).
 
     python -m paper_2406_00766_amd.layer_bench --sweep keep          # 200 sets of 1024 x 1024, K = 32, blocks dropped
     python -m paper_2406_00766_amd.layer_bench --sweep K             # 28 sets of 1024 x 1024 (29 K nodes, 29 M edges), K = 1..128
-    python -m paper_2406_00766_amd.layer_bench --sets 28 --K 8 --keep 1 --steps 3      # one point (e.g. under rocprofv3 --pmc)
+    python paper_2406_00766_amd/layer_bench.py --sets 28 --K 8 --keep 1 --steps 3      # one point (e.g. under rocprofv3 --pmc)
 
 Every point compiles the layer (wrapped into a small circuit by workloads.sum_layer), runs pc_forward +
 pc_backward and prints ONE JSON line with the per-launch durations of the sum-layer kernels (HIP events on the
@@ -12,16 +12,21 @@ row with M / K child blocks, a few microseconds.
 """
 import argparse
 import json
+import os
 import sys
 import time
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:                     # also runnable as a script from any directory (e.g. under rocprofv3)
+    sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3
 
 
 def run_point(n_sets, M, K, keep, B, steps, warmup, seed):
     import torch
-    from . import binding as pcb
-    from . import workloads as W
+    from paper_2406_00766_amd import binding as pcb
+    from paper_2406_00766_amd import workloads as W
 
     w = W.sum_layer(n_sets, M, K, B, seed, keep=keep)
     t0 = time.time()
