@@ -775,9 +775,13 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
                 lown[rt][e] = l[((int64_t)(id + sub * TM) + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4)) * Bs + col];
     }
 
-    // Two register sets (A, B) hold the fetched theta sub-block, neighbour values and block scalars of two
-    // consecutive chunks of this wave: while one set is consumed the other is being loaded.
-    floatx4 thA[NF4], thB[NF4];
+    // Software pipeline over the wave's chunks.  One register set `th` carries a theta sub-block from global
+    // memory to the LDS tile; two sets (A, B) hold the MFMA A operands read back from the tile and the neighbour
+    // values / block scalars of two consecutive chunks.  In the middle of the arithmetic of chunk c the tile is
+    // overwritten with the theta of chunk c+1 and read back into the other operand set, so neither the LDS round
+    // trip nor a global load is ever waited for at a chunk boundary.
+    floatx4 th[NF4];
+    float arA[NQ][RT], arB[NQ][RT];
     float vA[NQ], vB[NQ];
     float rbA = 0.0f, rbB = 0.0f, bmA = PC_NEG_INF, bmB = PC_NEG_INF;
     const float *vsrc = BWD ? N : l;
@@ -786,17 +790,22 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
     // loads of chunk C (macros, so the arrays stay in registers).  Row bases are wave-uniform (scalar
     // registers); only the 32-bit lane offset is per lane.  Nothing is computed on the loaded values here:
     // any arithmetic would wait for the load.
-#define PC_ISSUE(C, TH, V, RB, BM)                                                                                    \
+#define PC_ISSUE_TH(C)                                                                                                \
     do {                                                                                                              \
         const int j_ = (C) / CPB, kc_ = (C) % CPB;                                                                    \
-        const int32_t ns_ = row_nbr[j_], ps_ = row_par[j_];                                                           \
+        const int32_t ps_ = row_par[j_];                                                                              \
         const float *tb_ = BWD ? theta + (int64_t)ps_ + (int64_t)(kc_ * KC) * K + sub * TM                            \
                                : theta + (int64_t)ps_ + (int64_t)(sub * TM) * K + kc_ * KC;                           \
         _Pragma("unroll") for (int i = 0; i < NF4; ++i) {                                                             \
             const int t = lane + i * 64;                                                                              \
             const uint32_t o_ = BWD ? (t / (TM / 4)) * K + (t % (TM / 4)) * 4 : (t / (KC / 4)) * K + (t % (KC / 4)) * 4; \
-            TH[i] = *reinterpret_cast<const floatx4 *>(tb_ + o_);                                                     \
+            th[i] = *reinterpret_cast<const floatx4 *>(tb_ + o_);                                                     \
         }                                                                                                             \
+    } while (0)
+#define PC_ISSUE_V(C, V, RB, BM)                                                                                      \
+    do {                                                                                                              \
+        const int j_ = (C) / CPB, kc_ = (C) % CPB;                                                                    \
+        const int32_t ns_ = row_nbr[j_];                                                                              \
         const float *src_ = vsrc + (int64_t)(ns_ + kc_ * KC) * Bs;                                                    \
         _Pragma("unroll") for (int q = 0; q < NQ; ++q) {                                                              \
             const float *srow_ = src_ + (int64_t)(8 * (q / 4) + (q % 4)) * Bs;                                        \
@@ -806,15 +815,34 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
         RB = rrow_[(uint32_t)col];                                                                                    \
         if (BWD) { const float *mrow_ = nfmax + (int64_t)(ns_ / K) * Bs; BM = mrow_[(uint32_t)col]; }                 \
     } while (0)
-
-    // arithmetic of one fetched chunk
-#define PC_COMPUTE(TH, V, RB, BM)                                                                                     \
+    // theta registers -> LDS tile
+#define PC_COMMIT()                                                                                                   \
     do {                                                                                                              \
         _Pragma("unroll") for (int i = 0; i < NF4; ++i) {                                                             \
             const int t = lane + i * 64;                                                                              \
             const int o = BWD ? (t / (TM / 4)) * LDA + (t % (TM / 4)) * 4 : (t / (KC / 4)) * LDA + (t % (KC / 4)) * 4; \
-            *reinterpret_cast<floatx4 *>(buf + o) = TH[i];                                                            \
+            *reinterpret_cast<floatx4 *>(buf + o) = th[i];                                                            \
         }                                                                                                             \
+    } while (0)
+    // LDS tile -> MFMA A operands of the whole chunk
+#define PC_READ_A(AR)                                                                                                 \
+    do {                                                                                                              \
+        _Pragma("unroll") for (int rt = 0; rt < RT; ++rt) {                                                           \
+            if (BWD) {                                                                                                \
+                _Pragma("unroll") for (int q = 0; q < NQ; ++q)                                                        \
+                    AR[q][rt] = buf[(8 * (q / 4) + 4 * half + (q % 4)) * LDA + rt * 32 + l32];                        \
+            } else {                                                                                                  \
+                _Pragma("unroll") for (int g = 0; g < NQ / 4; ++g) {                                                  \
+                    const floatx4 a4 = *reinterpret_cast<const floatx4 *>(buf + (rt * 32 + l32) * LDA + 8 * g + 4 * half); \
+                    AR[4 * g + 0][rt] = a4[0]; AR[4 * g + 1][rt] = a4[1];                                             \
+                    AR[4 * g + 2][rt] = a4[2]; AR[4 * g + 3][rt] = a4[3];                                             \
+                }                                                                                                     \
+            }                                                                                                         \
+        }                                                                                                             \
+    } while (0)
+    // per-chunk scalars: reference, maximum, rescale of the accumulator; leaves sh2 for the exponentials
+#define PC_PRE(V, RB, BM)                                                                                             \
+    do {                                                                                                              \
         if (!BWD) {                                                     /* a larger reference: m moves by an exact integer */ \
             const float Rn = fmaxf(Rrow, RB);                                                                         \
             m += Rrow - Rn;                                             /* -inf stays -inf (RB is finite) */          \
@@ -829,20 +857,6 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
             _Pragma("unroll") for (int q = 0; q < NQ; ++q) cmax = fmaxf(cmax, V[q]);                                  \
             cmax = fmaxf(cmax, __shfl_xor(cmax, 32)) + d;                                                             \
         }                                                                                                             \
-        /* A operands of the whole chunk into registers first, so the MFMA stream never waits on LDS */               \
-        float areg[NQ][RT];                                                                                           \
-        _Pragma("unroll") for (int rt = 0; rt < RT; ++rt) {                                                           \
-            if (BWD) {                                                                                                \
-                _Pragma("unroll") for (int q = 0; q < NQ; ++q)                                                        \
-                    areg[q][rt] = buf[(8 * (q / 4) + 4 * half + (q % 4)) * LDA + rt * 32 + l32];                      \
-            } else {                                                                                                  \
-                _Pragma("unroll") for (int g = 0; g < NQ / 4; ++g) {                                                  \
-                    const floatx4 a4 = *reinterpret_cast<const floatx4 *>(buf + (rt * 32 + l32) * LDA + 8 * g + 4 * half); \
-                    areg[4 * g + 0][rt] = a4[0]; areg[4 * g + 1][rt] = a4[1];                                         \
-                    areg[4 * g + 2][rt] = a4[2]; areg[4 * g + 3][rt] = a4[3];                                         \
-                }                                                                                                     \
-            }                                                                                                         \
-        }                                                                                                             \
         const float m_new = fmaxf(m, cmax);                                                                           \
         const bool dead = !(m_new > PC_NEG_INF);                        /* every term of this column so far is 0 */   \
         if (__any(m_new != m)) {                                                                                      \
@@ -852,24 +866,61 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
         }                                                                                                             \
         m = m_new;                                                                                                    \
         /* exp(v + d - m) = exp2(v * log2e + sh2); dead column: v = -inf -> 0 */                                      \
-        const float sh2 = dead ? 0.0f : (d - m_new) * PC_LOG2E;                                                       \
-        _Pragma("unroll") for (int q = 0; q < NQ; ++q) {                                                              \
+        sh2 = dead ? 0.0f : (d - m_new) * PC_LOG2E;                                                                   \
+    } while (0)
+    // MFMA steps [Q0, Q0 + NQ/2) of a chunk
+#define PC_MATH(AR, V, Q0)                                                                                            \
+    do {                                                                                                              \
+        _Pragma("unroll") for (int q = (Q0); q < (Q0) + NQ / 2; ++q) {                                                \
             const float p = __builtin_amdgcn_exp2f(fmaf(V[q], PC_LOG2E, sh2));                                        \
             _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                         \
-                acc[rt] = __builtin_amdgcn_mfma_f32_32x32x2f32(areg[q][rt], p, acc[rt], 0, 0, 0);                     \
+                acc[rt] = __builtin_amdgcn_mfma_f32_32x32x2f32(AR[q][rt], p, acc[rt], 0, 0, 0);                       \
         }                                                                                                             \
     } while (0)
 
-    if (sp < n_chunks) PC_ISSUE(sp, thA, vA, rbA, bmA);
-    for (int c = sp; c < n_chunks; c += 2 * SPLIT) {
-        if (c + SPLIT < n_chunks) PC_ISSUE(c + SPLIT, thB, vB, rbB, bmB);
-        PC_COMPUTE(thA, vA, rbA, bmA);
-        if (c + SPLIT >= n_chunks) break;
-        if (c + 2 * SPLIT < n_chunks) PC_ISSUE(c + 2 * SPLIT, thA, vA, rbA, bmA);
-        PC_COMPUTE(thB, vB, rbB, bmB);
+    float sh2 = 0.0f;
+    if (sp < n_chunks) {
+        PC_ISSUE_TH(sp);
+        PC_ISSUE_V(sp, vA, rbA, bmA);
+        PC_COMMIT();
+        if (sp + SPLIT < n_chunks) { PC_ISSUE_TH(sp + SPLIT); PC_ISSUE_V(sp + SPLIT, vB, rbB, bmB); }
+        PC_READ_A(arA);
     }
-#undef PC_ISSUE
-#undef PC_COMPUTE
+    // pairs of chunks (c on set A, c + SPLIT on set B); a last single chunk follows the loop, so the loop has one
+    // exit and the accumulators stay in place
+    int c = sp;
+    for (; c + SPLIT < n_chunks; c += 2 * SPLIT) {
+        const bool more1 = c + 2 * SPLIT < n_chunks, more2 = c + 3 * SPLIT < n_chunks;
+        // chunk c on set A; chunk c + SPLIT is staged into set B meanwhile
+        PC_PRE(vA, rbA, bmA);
+        PC_MATH(arA, vA, 0);
+        PC_COMMIT();
+        if (more1) PC_ISSUE_TH(c + 2 * SPLIT);
+        PC_READ_A(arB);
+        PC_MATH(arA, vA, NQ / 2);
+        if (more1) PC_ISSUE_V(c + 2 * SPLIT, vA, rbA, bmA);
+        // chunk c + SPLIT on set B; chunk c + 2 SPLIT is staged into set A meanwhile
+        PC_PRE(vB, rbB, bmB);
+        PC_MATH(arB, vB, 0);
+        if (more1) {
+            PC_COMMIT();
+            if (more2) PC_ISSUE_TH(c + 3 * SPLIT);
+            PC_READ_A(arA);
+        }
+        PC_MATH(arB, vB, NQ / 2);
+        if (more2) PC_ISSUE_V(c + 3 * SPLIT, vB, rbB, bmB);
+    }
+    if (c < n_chunks) {                                                 // a last chunk, staged in set A
+        PC_PRE(vA, rbA, bmA);
+        PC_MATH(arA, vA, 0);
+        PC_MATH(arA, vA, NQ / 2);
+    }
+#undef PC_ISSUE_TH
+#undef PC_ISSUE_V
+#undef PC_COMMIT
+#undef PC_READ_A
+#undef PC_PRE
+#undef PC_MATH
 
     if (SPLIT > 1) {                                                    // merge the partial sums of the SPLIT waves of a tile
         __syncthreads();
