@@ -716,6 +716,9 @@ __global__ __launch_bounds__(256) void k_param_flow_small(const float *__restric
 // per block).  Partial sums of the SPLIT waves are merged through LDS at the end.  No lane-dependent
 // branch surrounds an MFMA.
 #define PC_LOG2E 1.4426950408889634f
+// buffer descriptor of the main-loop loads: raw (stride 0), 2 GiB window from the chunk's base, 32-bit data format
+#define PC_BUF_RANGE 0x7fffffff
+#define PC_BUF_FLAGS 0x00020000
 template <int K, int RT, int SPLIT, bool BWD>
 __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ theta, float *__restrict__ l,
                                                      float *__restrict__ R, const float *__restrict__ N,
@@ -785,7 +788,19 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
     float vA[NQ], vB[NQ];
     float rbA = 0.0f, rbB = 0.0f, bmA = PC_NEG_INF, bmB = PC_NEG_INF;
     const float *vsrc = BWD ? N : l;
-    const uint32_t lane_off = (uint32_t)((int64_t)(4 * half) * Bs + col);   // per-lane part of a neighbour-value address
+    // per-lane parts of the load addresses (32-bit offsets from wave-uniform bases, so the loads take a scalar
+    // base and need no vector address arithmetic): neighbour-value rows 0-3 of a group of 8, theta sub-block
+    // The loads of the main loop are buffer loads: a wave-uniform descriptor per chunk (base = first row of the
+    // chunk), a loop-invariant per-lane byte offset and a loop-invariant scalar row offset, so they need no
+    // vector address arithmetic (the vector ALU issues instead of the matrix cores, not beside them).
+    int voff[4];                                                        // rows 0-3 of a group of 8 rows
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) voff[rr] = (int)(((int64_t)(4 * half + rr) * Bs + col) * 4);
+    int soff[NQ / 4];                                                   // groups of 8 rows
+#pragma unroll
+    for (int g = 0; g < NQ / 4; ++g) soff[g] = __builtin_amdgcn_readfirstlane((int)((int64_t)(8 * g) * Bs * 4));
+    const int toff = BWD ? ((lane / (TM / 4)) * K + (lane % (TM / 4)) * 4) * 4
+                         : ((lane / (KC / 4)) * K + (lane % (KC / 4)) * 4) * 4;
 
     // loads of chunk C (macros, so the arrays stay in registers).  Row bases are wave-uniform (scalar
     // registers); only the 32-bit lane offset is per lane.  Nothing is computed on the loaded values here:
@@ -796,10 +811,10 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
         const int32_t ps_ = row_par[j_];                                                                              \
         const float *tb_ = BWD ? theta + (int64_t)ps_ + (int64_t)(kc_ * KC) * K + sub * TM                            \
                                : theta + (int64_t)ps_ + (int64_t)(sub * TM) * K + kc_ * KC;                           \
-        _Pragma("unroll") for (int i = 0; i < NF4; ++i) {                                                             \
-            const int t = lane + i * 64;                                                                              \
-            const uint32_t o_ = BWD ? (t / (TM / 4)) * K + (t % (TM / 4)) * 4 : (t / (KC / 4)) * K + (t % (KC / 4)) * 4; \
-            th[i] = *reinterpret_cast<const floatx4 *>(tb_ + o_);                                                     \
+        const __amdgpu_buffer_rsrc_t rt_ = __builtin_amdgcn_make_buffer_rsrc((void *)tb_, 0, PC_BUF_RANGE, PC_BUF_FLAGS); \
+        _Pragma("unroll") for (int i = 0; i < NF4; ++i) {               /* 64 lanes cover 64 / (TM/4 or KC/4) rows */   \
+            const int so_ = (BWD ? i * (64 / (TM / 4)) * K : i * (64 / (KC / 4)) * K) * 4;                            \
+            th[i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rt_, toff, so_, 0));           \
         }                                                                                                             \
     } while (0)
 #define PC_ISSUE_V(C, V, RB, BM)                                                                                      \
@@ -807,10 +822,9 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
         const int j_ = (C) / CPB, kc_ = (C) % CPB;                                                                    \
         const int32_t ns_ = row_nbr[j_];                                                                              \
         const float *src_ = vsrc + (int64_t)(ns_ + kc_ * KC) * Bs;                                                    \
-        _Pragma("unroll") for (int q = 0; q < NQ; ++q) {                                                              \
-            const float *srow_ = src_ + (int64_t)(8 * (q / 4) + (q % 4)) * Bs;                                        \
-            V[q] = srow_[lane_off];                                                                                   \
-        }                                                                                                             \
+        const __amdgpu_buffer_rsrc_t rv_ = __builtin_amdgcn_make_buffer_rsrc((void *)src_, 0, PC_BUF_RANGE, PC_BUF_FLAGS); \
+        _Pragma("unroll") for (int q = 0; q < NQ; ++q)                                                                \
+            V[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv_, voff[q % 4], soff[q / 4], 0)); \
         const float *rrow_ = R + (int64_t)(ns_ / K) * Bs;                                                             \
         RB = rrow_[(uint32_t)col];                                                                                    \
         if (BWD) { const float *mrow_ = nfmax + (int64_t)(ns_ / K) * Bs; BM = mrow_[(uint32_t)col]; }                 \
