@@ -1126,6 +1126,144 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restr
             }
 }
 
+// The same computation for K = 128 with the staging shared by the workgroup: the four waves own the four 64 x 64
+// quarters of one 128 x 128 parameter block, and every fetched row is used by two of them.  Per chunk of 32
+// samples the 256 threads fetch and exponentiate the 128 rows of N and the 128 rows of l ONCE (4 + 4 sixteen-byte
+// loads per thread instead of 16 + 16) into a workgroup tile in LDS; each wave then reads the 64 + 64 rows of its
+// quarter.  The tile is double-buffered, so one barrier per chunk suffices, and the loads run two chunks ahead of
+// the arithmetic: a chunk's matrix work (1.7 us) is shorter than a trip to HBM, which some of a chunk's loads
+// always take.
+__global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg128(const float *__restrict__ theta, const float *__restrict__ l,
+                                                                  const float *__restrict__ R, const float *__restrict__ N,
+                                                                  const float *__restrict__ nfmax, float *__restrict__ G,
+                                                                  const int32_t *__restrict__ pf_pb, const int32_t *__restrict__ pf_ptr,
+                                                                  const int32_t *__restrict__ pf_sum, const int32_t *__restrict__ pf_child,
+                                                                  int64_t Bs)
+{
+    constexpr int K = 128, LD = 36;                                     // LDS row stride: 16-byte rows, b128 reads conflict-free
+    constexpr int TILE = 2 * K * LD;                                    // 128 rows of factors from N, 128 rows from l
+    __shared__ float lds[2 * TILE];
+
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
+    const int r0 = (wave >> 1) * 64, c0 = (wave & 1) * 64;              // this wave's quarter of the block
+    const int pidx = blockIdx.x;
+    const int32_t pb = pf_pb[pidx];
+    const int i0 = pf_ptr[pidx], i1 = pf_ptr[pidx + 1];
+    const int srow = threadIdx.x >> 3, sc4 = (threadIdx.x & 7) * 4;     // staging: 8 threads x 16 bytes per row, 32 rows per pass
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[rt][ct][e] = 0.0f;
+
+    const int chunks_per_inst = (int)(Bs / 32);
+    const int n_chunks = (i1 - i0) * chunks_per_inst;
+    // two register sets of fetched tiles (loads two chunks ahead)
+    floatx4 nfA[4], lcA[4], mxA, rsA, rcA;
+    floatx4 nfB[4], lcB[4], mxB, rsB, rcB;
+    const int voff = (int)(((int64_t)srow * Bs + sc4) * 4), voff1 = sc4 * 4;
+    int soff[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) soff[i] = __builtin_amdgcn_readfirstlane((int)((int64_t)(32 * i) * Bs * 4));
+
+#define PC_ISSUE(C, NF, LC, MX, RS, RC)                                                                               \
+    do {                                                                                                              \
+        const int inst_ = i0 + (C) / chunks_per_inst;                                                                 \
+        const int64_t b0_ = (int64_t)((C) % chunks_per_inst) * 32;                                                    \
+        const int32_t ms_ = pf_sum[inst_], ns_ = pf_child[inst_];                                                     \
+        const __amdgpu_buffer_rsrc_t rn_ = __builtin_amdgcn_make_buffer_rsrc((void *)(N + (int64_t)ms_ * Bs + b0_), 0, PC_BUF_RANGE, PC_BUF_FLAGS); \
+        const __amdgpu_buffer_rsrc_t rl_ = __builtin_amdgcn_make_buffer_rsrc((void *)(l + (int64_t)ns_ * Bs + b0_), 0, PC_BUF_RANGE, PC_BUF_FLAGS); \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                                 \
+            NF[i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rn_, voff, soff[i], 0));        \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                                 \
+            LC[i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rl_, voff, soff[i], 0));        \
+        const __amdgpu_buffer_rsrc_t rm_ = __builtin_amdgcn_make_buffer_rsrc((void *)(nfmax + (int64_t)(ms_ / K) * Bs + b0_), 0, PC_BUF_RANGE, PC_BUF_FLAGS); \
+        const __amdgpu_buffer_rsrc_t rs_ = __builtin_amdgcn_make_buffer_rsrc((void *)(R + (int64_t)(ms_ / K) * Bs + b0_), 0, PC_BUF_RANGE, PC_BUF_FLAGS); \
+        const __amdgpu_buffer_rsrc_t rc_ = __builtin_amdgcn_make_buffer_rsrc((void *)(R + (int64_t)(ns_ / K) * Bs + b0_), 0, PC_BUF_RANGE, PC_BUF_FLAGS); \
+        MX = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rm_, voff1, 0, 0));                    \
+        RS = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rs_, voff1, 0, 0));                    \
+        RC = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rc_, voff1, 0, 0));                    \
+    } while (0)
+
+    // exponentials of a fetched chunk into tile T of the workgroup (this thread's rows srow, srow + 32, ...)
+#define PC_STAGE(T, NF, LC, MX, RS, RC)                                                                               \
+    do {                                                                                                              \
+        float *Qt_ = lds + (T) * TILE, *Pt_ = Qt_ + K * LD;                                                           \
+        floatx4 qa, qb;                                                 /* per-sample shifts in log2 units */         \
+        _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                               \
+            const bool live = MX[e] > PC_NEG_INF;                                                                     \
+            qa[e] = live ? (PC_SPLIT - MX[e]) * PC_LOG2E : PC_NEG_INF;  /* dead sample: both factors 0 */             \
+            qb[e] = live ? (MX[e] + (RC[e] - RS[e]) - PC_SPLIT) * PC_LOG2E : PC_NEG_INF;                              \
+        }                                                                                                             \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                               \
+            floatx4 q, p;                                                                                             \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                           \
+                q[e] = __builtin_amdgcn_exp2f(fmaf(NF[i][e], PC_LOG2E, qa[e]));                                       \
+                p[e] = __builtin_amdgcn_exp2f(fminf(fmaf(LC[i][e], PC_LOG2E, qb[e]), PC_SPLIT_CAP * PC_LOG2E));      \
+            }                                                                                                         \
+            *reinterpret_cast<floatx4 *>(Qt_ + (32 * i + srow) * LD + sc4) = q;                                       \
+            *reinterpret_cast<floatx4 *>(Pt_ + (32 * i + srow) * LD + sc4) = p;                                       \
+        }                                                                                                             \
+    } while (0)
+
+    // this wave's operands of the whole chunk from tile T, then the products
+#define PC_MATH(T)                                                                                                    \
+    do {                                                                                                              \
+        const float *Qt_ = lds + (T) * TILE + r0 * LD, *Pt_ = lds + (T) * TILE + (K + c0) * LD;                       \
+        float areg[16][2], breg[16][2];                                                                               \
+        _Pragma("unroll") for (int rt = 0; rt < 2; ++rt)                                                              \
+            _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                                           \
+                const floatx4 a4 = *reinterpret_cast<const floatx4 *>(Qt_ + (rt * 32 + l32) * LD + 8 * g + 4 * half); \
+                areg[4 * g + 0][rt] = a4[0]; areg[4 * g + 1][rt] = a4[1]; areg[4 * g + 2][rt] = a4[2]; areg[4 * g + 3][rt] = a4[3]; \
+                const floatx4 b4 = *reinterpret_cast<const floatx4 *>(Pt_ + (rt * 32 + l32) * LD + 8 * g + 4 * half); \
+                breg[4 * g + 0][rt] = b4[0]; breg[4 * g + 1][rt] = b4[1]; breg[4 * g + 2][rt] = b4[2]; breg[4 * g + 3][rt] = b4[3]; \
+            }                                                                                                         \
+        _Pragma("unroll") for (int q = 0; q < 16; ++q)                                                                \
+            _Pragma("unroll") for (int rt = 0; rt < 2; ++rt)                                                          \
+                _Pragma("unroll") for (int ct = 0; ct < 2; ++ct)                                                      \
+                    acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(areg[q][rt], breg[q][ct], acc[rt][ct], 0, 0, 0); \
+    } while (0)
+
+    // n_chunks is the same for all four waves, so every wave reaches every barrier
+    if (n_chunks > 0) PC_ISSUE(0, nfA, lcA, mxA, rsA, rcA);
+    if (n_chunks > 1) PC_ISSUE(1, nfB, lcB, mxB, rsB, rcB);
+    int c = 0;
+    for (; c + 1 < n_chunks; c += 2) {                                  // pairs of chunks; a last single chunk follows
+        PC_STAGE(0, nfA, lcA, mxA, rsA, rcA);
+        if (c + 2 < n_chunks) PC_ISSUE(c + 2, nfA, lcA, mxA, rsA, rcA);
+        __syncthreads();
+        PC_MATH(0);
+        PC_STAGE(1, nfB, lcB, mxB, rsB, rcB);
+        if (c + 3 < n_chunks) PC_ISSUE(c + 3, nfB, lcB, mxB, rsB, rcB);
+        __syncthreads();
+        PC_MATH(1);
+    }
+    if (c < n_chunks) {
+        PC_STAGE(0, nfA, lcA, mxA, rsA, rcA);
+        __syncthreads();
+        PC_MATH(0);
+    }
+#undef PC_ISSUE
+#undef PC_STAGE
+#undef PC_MATH
+
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int i = r0 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                const int64_t at = (int64_t)pb + (int64_t)i * K + c0 + ct * 32 + l32;
+                const float th = theta[at];
+                if (th > 0.0f) G[at] += th * acc[rt][ct][e];          // theta = 0: no flow (and never 0 * inf)
+            }
+}
+
 // ------------------------------------------------------------------------------------------
 // EM update
 // ------------------------------------------------------------------------------------------
@@ -1471,8 +1609,8 @@ void launch_param_flow(const float *theta, const float *l, const float *R, const
         hipLaunchKernelGGL((k_param_flow_mfma<64, 2, 2>), dim3((unsigned)((pf.n_pb + 3) / 4)), dim3(256), 0, s, theta, l, R, N,
                            nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, Bs);
     } else {
-        hipLaunchKernelGGL((k_param_flow_mfma<128, 2, 2>), dim3((unsigned)pf.n_pb), dim3(256), 0, s, theta, l, R, N, nfmax, G,
-                           pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, Bs);
+        hipLaunchKernelGGL(k_param_flow_mfma_wg128, dim3((unsigned)pf.n_pb), dim3(256), 0, s, theta, l, R, N, nfmax, G, pf.pb,
+                           pf.ptr, pf.sum, pf.child, Bs);
     }
 }
 
