@@ -60,7 +60,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=4, help="1..5, the configurations of BASELINE.json")
+    ap.add_argument("--config", default="4", help="1..5, the configurations of BASELINE.json; 'rat' = the RAT-SPN stand-in")
+    ap.add_argument("--batch", type=int, default=None, help="batch size (default per configuration)")
     ap.add_argument("--K", type=int, default=None, help="node block size (default per config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-em", action="store_true", help="skip the secondary timing that adds pc_em_step")
@@ -77,7 +78,7 @@ def main():
     from paper_2406_00766_amd import workloads as W
 
     t0 = time.time()
-    w = W.config(args.config, K=args.K)
+    w = W.rat_config(K=args.K, B=args.batch) if args.config == "rat" else W.config(int(args.config), K=args.K, B=args.batch)
     gen_s = time.time() - t0
     work, Es = algorithmic_work(w)
 

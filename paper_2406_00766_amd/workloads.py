@@ -7,8 +7,8 @@ one module both the CPU oracle's tests and the GPU path's tests / benchmark draw
 Structures follow the experimental section of the paper (Sec. 6, App. C): homogeneous HMMs
 written as circuits (footnote to Sec. 1), hidden Chow-Liu trees, and a Poon-Domingos grid
 structure with axis-aligned splits (App. C.4), optionally with whole child blocks pruned at
-random as in the block-sparse experiment (App. C.1), and the single wide block-sparse sum layer of
-that experiment (also the shape of the layer analysed in Sec. 4.2).
+random as in the block-sparse experiment (App. C.1), a random tensorised structure (RAT-SPN), and the
+single wide block-sparse sum layer of that experiment (also the shape of the layer analysed in Sec. 4.2).
 
 Block-level DAG convention (one "block" = K consecutive node slots):
   type[u]        0 input, 1 product, 2 sum
@@ -461,6 +461,89 @@ def pd(grid: int, cell: int, M: int, K: int, B: int, seed: int, *, keep=1.0, n_c
 
 
 # --------------------------------------------------------------------------------------------
+# Random tensorised structure (RAT-SPN, the fourth structure of Sec. 6.1)
+# --------------------------------------------------------------------------------------------
+def rat_spn(D: int, depth: int, R: int, S: int, K: int, B: int, seed: int, *, n_cats=256, data="gauss", draw=True,
+            name=None) -> Workload:
+    """R replicas of a random region tree over D variables, joined under one root.
+
+    replica r:  a random permutation of the variables is split into two halves, recursively, `depth` times
+    leaf region (variable set V):  S factorised distributions, distribution k = prod_{v in V} E_{r,v}[k]
+                (one table per replica and variable)
+    region with halves (left, right), each offering S / K node blocks: one product block per PAIR of blocks,
+                P_{a,b}[k] = left_a[k] * right_b[k]   (the cross product taken block-wise; a leaf half
+                contributes the input blocks of its variables directly, so products never feed products);
+                the region's S sum nodes range over all (S / K)^2 * K product nodes
+    root:       one sum node over the product nodes of the R top regions
+    The paper gives sizes only (nodes / edges); depth, R and S are free parameters chosen to match them.
+    """
+    assert S % K == 0 and depth >= 1 and D >= 2 ** depth
+    nb = S // K
+    rng = np.random.Generator(np.random.PCG64(seed))
+    bld = _Builder(K)
+    n_tables = R * D * nb
+    E = [[[bld.add(INPUT, var=v, table=(r * D + v) * nb + j) for j in range(nb)] for v in range(D)] for r in range(R)]
+    sums: list[tuple[int, list[int]]] = []                 # (sum block, its product blocks), creation order
+    top_products: list[int] = []
+
+    def region(r: int, vs: np.ndarray, level: int):
+        """-> per node block of the region, the list of blocks a product above has to multiply"""
+        if level == depth:
+            return [[E[r][int(v)][j] for v in vs] for j in range(nb)]
+        half = len(vs) // 2
+        left, right = region(r, vs[:half], level + 1), region(r, vs[half:], level + 1)
+        prods = []
+        for a in range(nb):
+            for b in range(nb):
+                p = bld.add(PRODUCT)
+                for ch in left[a] + right[b]:
+                    bld.link(p, ch)
+                prods.append(p)
+        if level == 0:
+            top_products.extend(prods)
+            return None
+        blocks = [bld.add(SUM) for _ in range(nb)]
+        for sblk in blocks:
+            sums.append((sblk, prods))
+        return [[sblk] for sblk in blocks]
+
+    for r in range(R):
+        region(r, rng.permutation(D), 0)
+    root = bld.add(SUM, n_real=1)
+    sums.append((root, top_products))
+    n_param_blocks = 0
+    for sblk, prods in sums:
+        for p in prods:
+            bld.link(sblk, p, n_param_blocks)
+            n_param_blocks += 1
+
+    meta = {"kind": "rat_spn", "D": D, "depth": depth, "R": R, "S": S}
+    nm = name or f"rat_D{D}_d{depth}_R{R}_S{S}_K{K}_B{B}"
+    theta = np.zeros((n_param_blocks + 1, K, K), dtype=np.float32)
+    if not draw:
+        return _make(nm, bld, root, n_param_blocks, D, n_cats, n_tables, theta,
+                     np.zeros((n_tables, n_cats, K), dtype=np.float32), np.zeros((B, D), dtype=np.int32), meta)
+    pos = 1
+    for sblk, prods in sums:
+        rows = 1 if sblk == root else K
+        nk = len(prods)
+        Wt = _f32_floor(_dirichlet_rows(rng, 1.0, (rows, nk * K)))
+        theta[pos:pos + nk, :rows, :] = Wt.reshape(rows, nk, K).transpose(1, 0, 2)
+        pos += nk
+    tables = np.empty((n_tables, n_cats, K), dtype=np.float32)
+    for t in range(R * D):
+        Tv = _f32_floor(_dirichlet_rows(rng, 1.0, (S, n_cats)))
+        tables[t * nb:(t + 1) * nb] = Tv.reshape(nb, K, n_cats).transpose(0, 2, 1)
+    hi = n_cats - 1
+    if data == "gauss":
+        mu = rng.uniform(0.0, float(hi), size=D)
+        x = np.clip(np.rint(rng.normal(mu[None, :], 40.0 * n_cats / 256.0, size=(B, D))), 0, hi)
+    else:
+        x = rng.integers(0, n_cats, size=(B, D))
+    return _make(nm, bld, root, n_param_blocks, D, n_cats, n_tables, theta, tables, x, meta)
+
+
+# --------------------------------------------------------------------------------------------
 # One wide sum layer (App. C.1: independent fully-connected node sets; Sec. 4.2 analysis layer)
 # --------------------------------------------------------------------------------------------
 def sum_layer(n_sets: int, M: int, K: int, B: int, seed: int, *, keep=1.0, n_cats=256, draw=True, name=None) -> Workload:
@@ -583,6 +666,13 @@ def config(idx: int, *, K: int | None = None, B: int | None = None, draw: bool =
     raise ValueError(idx)
 
 
+def rat_config(*, K: int | None = None, B: int | None = None, draw: bool = True) -> Workload:
+    """RAT-SPN stand-in at the size of the paper's batch-size table (App. D: 465 K nodes, 33.4 M edges): 784 variables,
+    depth 4, 4 replicas, 256 sums per region -> 29.4 M sum edges; the node count is larger (940 K) because every
+    replica owns its input distributions.  Seed = SEED_BASE + 6."""
+    return rat_spn(784, 4, 4, 256, K or 32, B or 512, SEED_BASE + 6, draw=draw, name=f"rat_D784_d4_R4_S256_B{B or 512}")
+
+
 def reduced(idx: int, *, K: int | None = None, B: int | None = None) -> Workload:
     """Same structure family and value distributions as `config(idx)`, at a size a plain CPU
     implementation finishes in seconds; still spans several blocks and a ragged batch tail."""
@@ -597,4 +687,6 @@ def reduced(idx: int, *, K: int | None = None, B: int | None = None) -> Workload
         return hmm(5, 256, 1000, K or 64, B or 96, seed, alpha_trans=0.1, alpha_emis=0.1, tokens="zipf")
     if idx == 5:
         return pd(3, 2, 64, K or 32, B or 45, seed, keep=0.25, n_cats=16)
+    if idx == 6:
+        return rat_spn(24, 2, 2, 64, K or 32, B or 50, seed, n_cats=16)
     raise ValueError(idx)

@@ -97,7 +97,7 @@ def assert_device_tables_match_oracle(handle, w):
 
 
 # ------------------------------------------------------------------------------------------------
-REDUCED = [(i, None) for i in range(1, 6)] + [(1, 16), (2, 64), (3, 32), (3, 128), (4, 32), (4, 128)]
+REDUCED = [(i, None) for i in range(1, 7)] + [(1, 16), (2, 64), (3, 32), (3, 128), (4, 32), (4, 128), (6, 64), (6, 16)]
 
 
 @pytest.mark.parametrize("idx,K", REDUCED)
