@@ -17,14 +17,23 @@ from tests.test_gpu_parity import assert_device_tables_match_oracle, assert_flow
 
 pytestmark = pytest.mark.gpu
 
-N_ORACLE = {2: 16, 3: 4, 4: 4, 5: 4}
+# (label, workload factory, samples the oracle checks one by one)
+CASES = [
+    ("config 2", lambda: W.config(2), 16),
+    ("config 3", lambda: W.config(3), 4),
+    ("config 4", lambda: W.config(4), 4),
+    ("config 5", lambda: W.config(5), 4),
+    ("rat-spn", lambda: W.rat_config(), 8),
+    ("block-sparse layer, 200 sets, 30 % kept", lambda: W.sum_layer(200, 1024, 32, 512, W.SEED_BASE + 7, keep=0.3), 4),
+    ("layer of 28 sets at block size 8", lambda: W.sum_layer(28, 1024, 8, 512, W.SEED_BASE + 7), 4),
+]
 
 
-@pytest.mark.parametrize("idx", [2, 3, 4, 5])
-def test_full_size_config(idx):
-    print(f"case full-size config {idx}: generating", flush=True)
-    w = W.config(idx)
-    K, B, n = w.K, w.B, N_ORACLE[idx]
+@pytest.mark.parametrize("label,make,n", CASES, ids=[c[0] for c in CASES])
+def test_full_size_config(label, make, n):
+    print(f"case full-size {label}: generating", flush=True)
+    w = make()
+    K, B = w.K, w.B
     c = pcb.Circuit(w)
     print("  compiled tables (built by the device compiler) against the compile oracle, bit for bit", flush=True)
     assert_device_tables_match_oracle(c.handle, w)
