@@ -123,6 +123,7 @@ pc_status pc_copy_group(const pc_circuit *c, int32_t layer, int32_t dir, int32_t
  * integers; keeping the bulk of a large log-probability there leaves l accurate to ~1e-6).
  * stride = B rounded up to a multiple of 32; columns >= B behave as fully marginalised samples with
  * root flow 0. */
+#define PC_MAX_BATCH 2097152   /* samples per call: kernels address a batch row with 32-bit byte offsets (else PC_ERR_TOO_LARGE) */
 typedef struct {
     int64_t stride;            /* floats between consecutive rows                               */
     size_t l_offset, f_offset, n_offset, r_offset;   /* byte offsets into the workspace         */

@@ -201,6 +201,7 @@ pc_status pc_workspace_layout(const pc_circuit *c, int32_t B, pc_ws_layout *out)
 {
     if (!c || !out) return fail(PC_ERR_ARG, "NULL argument");
     if (B < 1) return fail(PC_ERR_ARG, "B must be positive");
+    if (B > PC_MAX_BATCH) return fail(PC_ERR_TOO_LARGE, "more than PC_MAX_BATCH samples in one call");
     const Ws w = ws_layout(c, B);
     out->stride = w.Bs; out->l_offset = w.l_off; out->f_offset = w.f_off; out->n_offset = w.n_off;
     out->r_offset = w.r_off;
@@ -224,6 +225,7 @@ pc_status pc_forward(pc_circuit *c, const float *theta, const float *tables, con
     if (!c || !theta || !tables || !x || !workspace || !ll) return fail(PC_ERR_ARG, "NULL argument");
     if (!c->on_device) return fail(PC_ERR_STATE, "circuit was compiled without a device");
     if (B < 1) return fail(PC_ERR_ARG, "B must be positive");
+    if (B > PC_MAX_BATCH) return fail(PC_ERR_TOO_LARGE, "more than PC_MAX_BATCH samples in one call");
     const Ws w = ws_layout(c, B);
     if (workspace_bytes < w.total) return fail(PC_ERR_WORKSPACE, "workspace smaller than pc_workspace_bytes");
     hipStream_t s = (hipStream_t)stream;

@@ -129,3 +129,16 @@ def test_host_only_handle_refuses_device_work():
         assert e.value.status_name == "PC_ERR_STATE"
     finally:
         pcb.pc_destroy(h)
+
+
+def test_batch_size_limits():
+    w = W.hmm(3, 2, 3, 2, 1, 52)
+    h = pcb.pc_compile(w, host_only=True)
+    try:
+        assert pcb.pc_workspace_bytes(h, 2097152) > 0              # PC_MAX_BATCH itself is fine
+        for bad, status in ((0, "PC_ERR_ARG"), (-3, "PC_ERR_ARG"), (2097153, "PC_ERR_TOO_LARGE")):
+            with pytest.raises(pcb.PcError) as e:
+                pcb.pc_workspace_bytes(h, bad)
+            assert e.value.status_name == status
+    finally:
+        pcb.pc_destroy(h)
