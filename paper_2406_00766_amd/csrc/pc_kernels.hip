@@ -712,7 +712,7 @@ __global__ __launch_bounds__(256) void k_param_flow_small(const float *__restric
 // the matrix cores (MFMA step q of a chunk pairs lanes 0-31 with node 8*(q/4) + q%4 and lanes 32-63 with
 // node 8*(q/4) + 4 + q%4, so that one 16-byte LDS read yields the A operands of four steps); the
 // accumulator stays in linear space and is rescaled when the maximum grows (the same sum as the
-// per-block log-space update of Alg. 1 line 16 / Alg. 4 line 16, with one log per output instead of one
+// per-block log-space update of the accumulator in Alg. 1 / Alg. 4, with one log per output instead of one
 // per block).  Partial sums of the SPLIT waves are merged through LDS at the end.  No lane-dependent
 // branch surrounds an MFMA.
 #define PC_LOG2E 1.4426950408889634f
@@ -995,7 +995,7 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
 // (up to 64 x 64) of one K x K parameter block and reduces over the batch of every (sum block, child
 // block) pair that uses the block -- all tied instances, e.g. the T-1 transition layers of an HMM
 // (App. A.3) -- in registers, so each flow element is read-modified-written once per call, without
-// atomics and without the per-layer accumulation of Alg. 3 line 21.
+// atomics and without the per-layer accumulation that closes Alg. 3.
 //
 // Each term exp(log_nf_s + l_c) is split into two fp32 factors around a per-sample shift (any shift is
 // valid: it only moves scale between the factors).  With a = max_s log_nf_s of the sum block, the
