@@ -191,12 +191,22 @@ __global__ __launch_bounds__(256) void k_input_bwd_direct(const float *__restric
 // rg, rg+16, ... of 4 adjacent columns (16-byte accesses along the batch), so a K-row block is K/16 rows
 // deep per thread and all its loads are independent.  Column maxima over the K rows go through one
 // shuffle stage (4 row groups per wave) and one LDS stage (4 waves).
+// max(x of lane i, x of lane i ^ 32) in every lane: one swap of the wave's halves in the vector ALU instead of a
+// trip through the LDS crossbar
+__device__ inline float pc_max_across_halves(float x)
+{
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    const unsigned bits = __builtin_bit_cast(unsigned, x);
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
+    return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+}
+
 __device__ inline void block_col_max(float (&mx)[4], float (*red)[64], int wave, int cl)
 {
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         mx[v] = fmaxf(mx[v], __shfl_xor(mx[v], 16));
-        mx[v] = fmaxf(mx[v], __shfl_xor(mx[v], 32));
+        mx[v] = pc_max_across_halves(mx[v]);
     }
     if ((threadIdx.x & 63) < 16) {
 #pragma unroll
@@ -869,7 +879,7 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
         } else {                                                                                                      \
             cmax = PC_NEG_INF;                                                                                        \
             _Pragma("unroll") for (int q = 0; q < NQ; ++q) cmax = fmaxf(cmax, V[q]);                                  \
-            cmax = fmaxf(cmax, __shfl_xor(cmax, 32)) + d;                                                             \
+            cmax = pc_max_across_halves(cmax) + d;                                                                    \
         }                                                                                                             \
         const float m_new = fmaxf(m, cmax);                                                                           \
         const bool dead = !(m_new > PC_NEG_INF);                        /* every term of this column so far is 0 */   \
