@@ -1136,49 +1136,53 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restr
             }
 }
 
-// The same computation for K = 128 with the staging shared by the workgroup: the four waves own the four 64 x 64
-// quarters of one 128 x 128 parameter block, and every fetched row is used by two of them.  Per chunk of 32
-// samples the 256 threads fetch and exponentiate the 128 rows of N and the 128 rows of l ONCE (4 + 4 sixteen-byte
-// loads per thread instead of 16 + 16) into a workgroup tile in LDS; each wave then reads the 64 + 64 rows of its
-// quarter.  The tile is double-buffered, so one barrier per chunk suffices, and the loads run two chunks ahead of
+// The same computation for K = 64 and 128 with the staging shared by the workgroup: the four waves own the four
+// quarters of one K x K parameter block, and every fetched row is used by two of them.  Per chunk of 32 samples the
+// 256 threads fetch and exponentiate the K rows of N and the K rows of l ONCE (K / 32 + K / 32 sixteen-byte loads per
+// thread; the per-wave kernel needs four times as many at K = 128) into a workgroup tile in LDS; each wave then reads
+// the K / 2 + K / 2 rows of its quarter.  The tile is double-buffered, so one barrier per chunk suffices, and the loads run two chunks ahead of
 // the arithmetic: a chunk's matrix work (1.7 us) is shorter than a trip to HBM, which some of a chunk's loads
 // always take.
-__global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg128(const float *__restrict__ theta, const float *__restrict__ l,
-                                                                  const float *__restrict__ R, const float *__restrict__ N,
-                                                                  const float *__restrict__ nfmax, float *__restrict__ G,
-                                                                  const int32_t *__restrict__ pf_pb, const int32_t *__restrict__ pf_ptr,
-                                                                  const int32_t *__restrict__ pf_sum, const int32_t *__restrict__ pf_child,
-                                                                  int64_t Bs)
+template <int K>
+__global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__restrict__ theta, const float *__restrict__ l,
+                                                               const float *__restrict__ R, const float *__restrict__ N,
+                                                               const float *__restrict__ nfmax, float *__restrict__ G,
+                                                               const int32_t *__restrict__ pf_pb, const int32_t *__restrict__ pf_ptr,
+                                                               const int32_t *__restrict__ pf_sum, const int32_t *__restrict__ pf_child,
+                                                               int64_t Bs)
 {
-    constexpr int K = 128, LD = 36;                                     // LDS row stride: 16-byte rows, b128 reads conflict-free
-    constexpr int TILE = 2 * K * LD;                                    // 128 rows of factors from N, 128 rows from l
+    constexpr int LD = 36;                                              // LDS row stride: 16-byte rows, b128 reads conflict-free
+    constexpr int TILE = 2 * K * LD;                                    // K rows of factors from N, K rows from l
+    constexpr int Q = K / 2, QT = Q / 32;                               // a wave's quarter: Q x Q, QT x QT MFMA tiles
+    constexpr int NL = K / 32;                                          // 16-byte loads per thread, chunk and array
+    static_assert(K == 64 || K == 128, "workgroup-shared parameter-flow kernel");
     __shared__ float lds[2 * TILE];
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
-    const int r0 = (wave >> 1) * 64, c0 = (wave & 1) * 64;              // this wave's quarter of the block
+    const int r0 = (wave >> 1) * Q, c0 = (wave & 1) * Q;                // this wave's quarter of the block
     const int pidx = blockIdx.x;
     const int32_t pb = pf_pb[pidx];
     const int i0 = pf_ptr[pidx], i1 = pf_ptr[pidx + 1];
     const int srow = threadIdx.x >> 3, sc4 = (threadIdx.x & 7) * 4;     // staging: 8 threads x 16 bytes per row, 32 rows per pass
 
-    floatx16 acc[2][2];
+    floatx16 acc[QT][QT];
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
+    for (int rt = 0; rt < QT; ++rt)
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
+        for (int ct = 0; ct < QT; ++ct)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[rt][ct][e] = 0.0f;
 
     const int chunks_per_inst = (int)(Bs / 32);
     const int n_chunks = (i1 - i0) * chunks_per_inst;
     // two register sets of fetched tiles (loads two chunks ahead)
-    floatx4 nfA[4], lcA[4], mxA, rsA, rcA;
-    floatx4 nfB[4], lcB[4], mxB, rsB, rcB;
+    floatx4 nfA[NL], lcA[NL], mxA, rsA, rcA;
+    floatx4 nfB[NL], lcB[NL], mxB, rsB, rcB;
     const int voff = (int)(((int64_t)srow * Bs + sc4) * 4), voff1 = sc4 * 4;
-    int soff[4];
+    int soff[NL];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) soff[i] = __builtin_amdgcn_readfirstlane((int)((int64_t)(32 * i) * Bs * 4));
+    for (int i = 0; i < NL; ++i) soff[i] = __builtin_amdgcn_readfirstlane((int)((int64_t)(32 * i) * Bs * 4));
 
 #define PC_ISSUE(C, NF, LC, MX, RS, RC)                                                                               \
     do {                                                                                                              \
@@ -1187,9 +1191,9 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg128(const float *_
         const int32_t ms_ = pf_sum[inst_], ns_ = pf_child[inst_];                                                     \
         const __amdgpu_buffer_rsrc_t rn_ = __builtin_amdgcn_make_buffer_rsrc((void *)(N + (int64_t)ms_ * Bs + b0_), 0, PC_BUF_RANGE, PC_BUF_FLAGS); \
         const __amdgpu_buffer_rsrc_t rl_ = __builtin_amdgcn_make_buffer_rsrc((void *)(l + (int64_t)ns_ * Bs + b0_), 0, PC_BUF_RANGE, PC_BUF_FLAGS); \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                                 \
+        _Pragma("unroll") for (int i = 0; i < NL; ++i)                                                                \
             NF[i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rn_, voff, soff[i], 0));        \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                                 \
+        _Pragma("unroll") for (int i = 0; i < NL; ++i)                                                                \
             LC[i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rl_, voff, soff[i], 0));        \
         const __amdgpu_buffer_rsrc_t rm_ = __builtin_amdgcn_make_buffer_rsrc((void *)(nfmax + (int64_t)(ms_ / K) * Bs + b0_), 0, PC_BUF_RANGE, PC_BUF_FLAGS); \
         const __amdgpu_buffer_rsrc_t rs_ = __builtin_amdgcn_make_buffer_rsrc((void *)(R + (int64_t)(ms_ / K) * Bs + b0_), 0, PC_BUF_RANGE, PC_BUF_FLAGS); \
@@ -1209,7 +1213,7 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg128(const float *_
             qa[e] = live ? (PC_SPLIT - MX[e]) * PC_LOG2E : PC_NEG_INF;  /* dead sample: both factors 0 */             \
             qb[e] = live ? (MX[e] + (RC[e] - RS[e]) - PC_SPLIT) * PC_LOG2E : PC_NEG_INF;                              \
         }                                                                                                             \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                               \
+        _Pragma("unroll") for (int i = 0; i < NL; ++i) {                                                              \
             floatx4 q, p;                                                                                             \
             _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                           \
                 q[e] = __builtin_amdgcn_exp2f(fmaf(NF[i][e], PC_LOG2E, qa[e]));                                       \
@@ -1224,8 +1228,8 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg128(const float *_
 #define PC_MATH(T)                                                                                                    \
     do {                                                                                                              \
         const float *Qt_ = lds + (T) * TILE + r0 * LD, *Pt_ = lds + (T) * TILE + (K + c0) * LD;                       \
-        float areg[16][2], breg[16][2];                                                                               \
-        _Pragma("unroll") for (int rt = 0; rt < 2; ++rt)                                                              \
+        float areg[16][QT], breg[16][QT];                                                                             \
+        _Pragma("unroll") for (int rt = 0; rt < QT; ++rt)                                                             \
             _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                                           \
                 const floatx4 a4 = *reinterpret_cast<const floatx4 *>(Qt_ + (rt * 32 + l32) * LD + 8 * g + 4 * half); \
                 areg[4 * g + 0][rt] = a4[0]; areg[4 * g + 1][rt] = a4[1]; areg[4 * g + 2][rt] = a4[2]; areg[4 * g + 3][rt] = a4[3]; \
@@ -1233,8 +1237,8 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg128(const float *_
                 breg[4 * g + 0][rt] = b4[0]; breg[4 * g + 1][rt] = b4[1]; breg[4 * g + 2][rt] = b4[2]; breg[4 * g + 3][rt] = b4[3]; \
             }                                                                                                         \
         _Pragma("unroll") for (int q = 0; q < 16; ++q)                                                                \
-            _Pragma("unroll") for (int rt = 0; rt < 2; ++rt)                                                          \
-                _Pragma("unroll") for (int ct = 0; ct < 2; ++ct)                                                      \
+            _Pragma("unroll") for (int rt = 0; rt < QT; ++rt)                                                         \
+                _Pragma("unroll") for (int ct = 0; ct < QT; ++ct)                                                     \
                     acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(areg[q][rt], breg[q][ct], acc[rt][ct], 0, 0, 0); \
     } while (0)
 
@@ -1262,9 +1266,9 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg128(const float *_
 #undef PC_MATH
 
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
+    for (int rt = 0; rt < QT; ++rt)
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
+        for (int ct = 0; ct < QT; ++ct)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int i = r0 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
@@ -1616,11 +1620,11 @@ void launch_param_flow(const float *theta, const float *l, const float *R, const
         hipLaunchKernelGGL((k_param_flow_mfma<32, 1, 1>), dim3((unsigned)((pf.n_pb + 3) / 4)), dim3(256), 0, s, theta, l, R, N,
                            nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, Bs);
     } else if (K == 64) {
-        hipLaunchKernelGGL((k_param_flow_mfma<64, 2, 2>), dim3((unsigned)((pf.n_pb + 3) / 4)), dim3(256), 0, s, theta, l, R, N,
-                           nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, Bs);
+        hipLaunchKernelGGL((k_param_flow_mfma_wg<64>), dim3((unsigned)pf.n_pb), dim3(256), 0, s, theta, l, R, N, nfmax, G,
+                           pf.pb, pf.ptr, pf.sum, pf.child, Bs);
     } else {
-        hipLaunchKernelGGL(k_param_flow_mfma_wg128, dim3((unsigned)pf.n_pb), dim3(256), 0, s, theta, l, R, N, nfmax, G, pf.pb,
-                           pf.ptr, pf.sum, pf.child, Bs);
+        hipLaunchKernelGGL((k_param_flow_mfma_wg<128>), dim3((unsigned)pf.n_pb), dim3(256), 0, s, theta, l, R, N, nfmax, G,
+                           pf.pb, pf.ptr, pf.sum, pf.child, Bs);
     }
 }
 
