@@ -641,6 +641,80 @@ def sum_layer_dense(w: Workload, s: int) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------------------------
+# Random alternating DAGs (test inputs: skip connections, tying, placeholders, unused blocks)
+# --------------------------------------------------------------------------------------------
+def random_circuit(n_vars: int, n_levels: int, width: int, K: int, B: int, seed: int, *, n_cats=5, tie_prob=0.3,
+                   name=None) -> Workload:
+    """A random block DAG that alternates product and sum levels above one input level.
+
+    Children are drawn from ALL lower levels of the right kind (products take sum and input blocks, sums take
+    product blocks), so blocks collect parents from several layers; some sum blocks reuse the whole parameter-block
+    list of an earlier sum block with as many children (tying); some sum blocks have fewer than K real nodes; blocks
+    that nothing refers to stay in the DAG.  Not smooth or decomposable in general -- the forward and backward
+    passes are plain arithmetic on any such DAG, and every value stays a probability <= 1.
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    bld = _Builder(K)
+    inputs = [bld.add(INPUT, var=int(rng.integers(0, n_vars)), table=i) for i in range(width)]
+    sums_or_inputs = list(inputs)
+    products: list[int] = []
+    sum_children: dict[int, list[int]] = {}
+    for level in range(n_levels):
+        new_p = []
+        for _ in range(int(rng.integers(1, width + 1))):
+            p = bld.add(PRODUCT)
+            k = int(rng.integers(1, min(3, len(sums_or_inputs)) + 1))
+            for ch in rng.choice(len(sums_or_inputs), size=k, replace=False):
+                bld.link(p, sums_or_inputs[int(ch)])
+            new_p.append(p)
+        products.extend(new_p)
+        new_s = []
+        for _ in range(int(rng.integers(1, width + 1))):
+            n_real = K if rng.random() < 0.7 else int(rng.integers(1, K + 1))
+            sblk = bld.add(SUM, n_real=n_real)
+            k = int(rng.integers(1, min(4, len(products)) + 1))
+            sum_children[sblk] = [products[int(c)] for c in rng.choice(len(products), size=k, replace=False)]
+            new_s.append(sblk)
+        sums_or_inputs.extend(new_s)
+    root = bld.add(SUM, n_real=1)
+    k = int(rng.integers(1, min(4, len(products)) + 1))
+    sum_children[root] = [products[int(c)] for c in rng.choice(len(products), size=k, replace=False)]
+
+    n_param_blocks = 0
+    owner_of_list: dict[int, list[int]] = {}                # sum block -> its parameter block ids
+    by_count: dict[int, list[int]] = {}
+    for sblk, chs in sum_children.items():
+        donors = [d for d in by_count.get(len(chs), []) if bld.n_real[d] == bld.n_real[sblk]]
+        if sblk != root and donors and rng.random() < tie_prob:
+            ids = owner_of_list[donors[int(rng.integers(0, len(donors)))]]
+        else:
+            ids = list(range(n_param_blocks, n_param_blocks + len(chs)))
+            n_param_blocks += len(chs)
+            by_count.setdefault(len(chs), []).append(sblk)
+        owner_of_list[sblk] = ids
+        for ch, pid in zip(chs, ids):
+            bld.link(sblk, ch, pid)
+
+    theta = np.zeros((n_param_blocks + 1, K, K), dtype=np.float32)
+    done = set()
+    for sblk, chs in sum_children.items():
+        ids = owner_of_list[sblk]
+        if ids[0] in done:
+            continue
+        done.update(ids)
+        rows = bld.n_real[sblk]
+        Wt = _f32_floor(_dirichlet_rows(rng, 0.5, (rows, len(chs) * K)))
+        for j, pid in enumerate(ids):
+            theta[pid + 1, :rows, :] = Wt[:, j * K:(j + 1) * K]
+    tables = np.empty((width, n_cats, K), dtype=np.float32)
+    for t in range(width):
+        tables[t] = _f32_floor(_dirichlet_rows(rng, 1.0, (K, n_cats))).T
+    x = rng.integers(0, n_cats, size=(B, n_vars))
+    return _make(name or f"random_v{n_vars}_L{n_levels}_w{width}_K{K}_B{B}_s{seed}", bld, root, n_param_blocks, n_vars, n_cats,
+                 width, theta, tables, x, {"kind": "random"})
+
+
+# --------------------------------------------------------------------------------------------
 # The five benchmark configurations and their reduced twins
 # --------------------------------------------------------------------------------------------
 DEFAULT_K = {1: 32, 2: 64, 3: 64, 4: 128, 5: 32}

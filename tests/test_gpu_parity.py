@@ -142,6 +142,17 @@ def test_block_sparse_sum_layer(n_sets, M, K, keep, B):
     assert_device_tables_match_oracle(got["circuit"].handle, w)
 
 
+@pytest.mark.parametrize("seed,K,B", [(s, K, B) for s in range(4) for K, B in ((32, 70), (4, 33))] +
+                         [(7, 64, 40), (8, 128, 33), (9, 3, 20), (10, 16, 65), (11, 1, 64)])
+def test_random_dags_with_skip_connections_tying_and_unused_blocks(seed, K, B):
+    w = W.random_circuit(5, 5, 5, K, B, 200 + seed)
+    print(f"case random {w.name}", flush=True)
+    rng = np.random.default_rng(seed)
+    mask = (rng.random(w.x.shape) < 0.2).astype(np.uint8) if seed % 2 else None
+    got, _ = check_all(w, mask)
+    assert_device_tables_match_oracle(got["circuit"].handle, w)
+
+
 def test_config1_full_size():
     w = W.config(1)
     print("case cfg1 full", flush=True)

@@ -47,7 +47,10 @@ def assert_tables_equal(handle, w):
 CASES = [lambda: W.reduced(i) for i in range(1, 6)] + \
         [lambda: W.config(1), lambda: W.config(1, K=16), lambda: W.config(2, draw=False),
          lambda: W.config(2, K=32, draw=False), lambda: W.config(4, draw=False), lambda: W.config(4, K=32, draw=False),
-         lambda: W.hmm(4, 6, 5, 3, 2, 7), lambda: W.pd(3, 1, 4, 1, 2, 8, n_cats=3, keep=0.5)]
+         lambda: W.hmm(4, 6, 5, 3, 2, 7), lambda: W.pd(3, 1, 4, 1, 2, 8, n_cats=3, keep=0.5),
+         lambda: W.rat_spn(16, 2, 2, 8, 4, 2, 14, n_cats=3, draw=False),
+         lambda: W.sum_layer(5, 64, 8, 3, 15, keep=0.3, draw=False)] + \
+        [(lambda s=s, K=K: W.random_circuit(4, 5, 5, K, 3, 100 + s)) for s in range(6) for K in (1, 4, 32)]
 
 
 @pytest.mark.parametrize("make", CASES)
