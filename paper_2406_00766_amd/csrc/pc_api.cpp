@@ -275,8 +275,8 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
     const int32_t *xT = (const int32_t *)(base + w.xt_off);
     const int32_t K = c->K;
 
-    // MFMA block sizes: parameter flows of the whole circuit in one launch after the sweep (N and nfmax of
-    // every sum layer stay valid until then); other block sizes: layer by layer
+    // block sizes with a by-parameter-block kernel (1-16, 32, 64, 128): parameter flows of the whole circuit in one
+    // launch after the sweep (N and nfmax of every sum layer stay valid until then); other block sizes: layer by layer
     const bool batched_params = param_flow_by_block(K);
     // no clearing of F: every block's flow is stored by the first layer that feeds it, blocks nobody feeds are
     // initialised here
