@@ -103,6 +103,48 @@ __global__ __launch_bounds__(256) void k_input_fwd(const float *__restrict__ tab
     }
 }
 
+// The same through an LDS tile, for K a multiple of 4: one workgroup per (block, 64 samples).  K / 4 lanes fetch one
+// sample's table row with 16-byte loads (every global read is a whole contiguous row), the logs go into a
+// [K x 64] tile, and the tile leaves as 16-byte stores along the batch -- no access is narrower than a row.
+__global__ __launch_bounds__(256) void k_input_fwd_tile(const float *__restrict__ tables, const int32_t *__restrict__ xT,
+                                                        const int32_t *__restrict__ ids, const int32_t *__restrict__ var,
+                                                        const int32_t *__restrict__ tab, int32_t K, int32_t n_cats,
+                                                        int64_t Bs, float *__restrict__ l)
+{
+    extern __shared__ float smem[];
+    float *tile = smem;                                                 // [K][65]
+    int *cats = reinterpret_cast<int *>(tile + K * 65);
+    const int u = blockIdx.x;
+    const int64_t b0 = (int64_t)blockIdx.y * 64;
+    if (threadIdx.x < 64) cats[threadIdx.x] = (b0 + threadIdx.x < Bs) ? xT[(int64_t)var[u] * Bs + b0 + threadIdx.x] : -1;
+    __syncthreads();
+    const int lps = K / 4;                                              // lanes per sample
+    const float *tbase = tables + (int64_t)tab[u] * n_cats * K;
+    for (int idx = threadIdx.x; idx < 64 * lps; idx += 256) {
+        const int sidx = idx / lps, kl = idx - sidx * lps;
+        const int xv = cats[sidx];
+        float4 t;
+        if (xv >= 0) {
+            const float4 r = *reinterpret_cast<const float4 *>(tbase + (int64_t)xv * K + kl * 4);
+            t = make_float4(__logf(r.x), __logf(r.y), __logf(r.z), __logf(r.w));
+        } else {
+            const float v = xv == -1 ? 0.0f : PC_NEG_INF;               // marginalised / tail : out-of-range category
+            t = make_float4(v, v, v, v);
+        }
+        float *dst = tile + (kl * 4) * 65 + sidx;
+        dst[0] = t.x; dst[65] = t.y; dst[130] = t.z; dst[195] = t.w;
+    }
+    __syncthreads();
+    const int32_t id = ids[u];
+    for (int idx = threadIdx.x; idx < K * 16; idx += 256) {
+        const int row = idx >> 4, c4 = (idx & 15) * 4;
+        if (b0 + c4 < Bs) {
+            const float *src = tile + row * 65 + c4;
+            *reinterpret_cast<float4 *>(l + (int64_t)(id + row) * Bs + b0 + c4) = make_float4(src[0], src[1], src[2], src[3]);
+        }
+    }
+}
+
 // table_flow[t][x_b,v][k] += F[n,b] for observed variables.
 // Both variants first bring a [K rows x 64 samples] tile of the flow buffer into LDS with coalesced 16-byte
 // loads along the batch, then turn it: a group of lanes owns consecutive nodes k of ONE sample, so every add
@@ -1464,8 +1506,14 @@ void launch_input_fwd(const float *tables, const int32_t *xT, const GroupDev &g,
 {
     Timed timed(KC_INPUT_FWD, s);
     if (g.n_rows == 0) return;
-    dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 255) / 256));
-    hipLaunchKernelGGL(k_input_fwd, grid, dim3(256), 0, s, tables, xT, g.ids, g.nbr, g.par, K, n_cats, Bs, l);
+    if ((K & 3) == 0 && K <= 64) {                                    // larger blocks: the tile costs occupancy, rows are long enough
+        dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 63) / 64));
+        const size_t lds = (size_t)K * 65 * 4 + 64 * 4;
+        hipLaunchKernelGGL(k_input_fwd_tile, grid, dim3(256), lds, s, tables, xT, g.ids, g.nbr, g.par, K, n_cats, Bs, l);
+    } else {
+        dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 255) / 256));
+        hipLaunchKernelGGL(k_input_fwd, grid, dim3(256), 0, s, tables, xT, g.ids, g.nbr, g.par, K, n_cats, Bs, l);
+    }
 }
 
 void launch_input_bwd(const float *F, const int32_t *xT, const GroupDev &g, int32_t K, int32_t n_cats, int64_t Bs,
