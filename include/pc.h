@@ -4,7 +4,8 @@
  *
  * Conventions used by every entry point
  *   - "device" pointers are hipMalloc-style GPU addresses owned by the caller; "host" pointers are
- *     ordinary CPU memory.  The handle (pc_circuit) owns only its compiled int32 tables and a few
+ *     ordinary CPU memory.  theta, tables, their flow arrays and the workspace must be 16-byte aligned
+ *     (PC_ERR_ARG otherwise).  The handle (pc_circuit) owns only its compiled int32 tables and a few
  *     KB of reduction scratch.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Forward, backward
  *     and the EM step only enqueue work; they never synchronise the device.  A kernel fault

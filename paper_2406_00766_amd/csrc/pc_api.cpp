@@ -83,6 +83,8 @@ struct Ws {
     int64_t Bs;
     size_t l_off, f_off, n_off, r_off, mx_off, xt_off, total;
 };
+static inline bool misaligned(const void *p) { return ((uintptr_t)p & 15) != 0; }   // kernels use 16-byte accesses
+
 static Ws ws_layout(const pc_circuit *c, int32_t B)
 {
     Ws w;
@@ -226,6 +228,8 @@ pc_status pc_forward(pc_circuit *c, const float *theta, const float *tables, con
     if (!c->on_device) return fail(PC_ERR_STATE, "circuit was compiled without a device");
     if (B < 1) return fail(PC_ERR_ARG, "B must be positive");
     if (B > PC_MAX_BATCH) return fail(PC_ERR_TOO_LARGE, "more than PC_MAX_BATCH samples in one call");
+    if (misaligned(theta) || misaligned(tables) || misaligned(workspace))
+        return fail(PC_ERR_ARG, "theta, tables and workspace must be 16-byte aligned");
     const Ws w = ws_layout(c, B);
     if (workspace_bytes < w.total) return fail(PC_ERR_WORKSPACE, "workspace smaller than pc_workspace_bytes");
     hipStream_t s = (hipStream_t)stream;
@@ -264,6 +268,8 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
     if (c->fw_B != B || c->fw_workspace != workspace || c->fw_theta != theta || c->fw_tables != tables ||
         c->fw_x != x || c->fw_mask != mask)
         return fail(PC_ERR_STATE, "pc_backward needs the pc_forward that just ran on the same arguments");
+    if (misaligned(theta_flow) || misaligned(table_flow))
+        return fail(PC_ERR_ARG, "theta_flow and table_flow must be 16-byte aligned");
     const Ws w = ws_layout(c, B);
     if (workspace_bytes < w.total) return fail(PC_ERR_WORKSPACE, "workspace smaller than pc_workspace_bytes");
     hipStream_t s = (hipStream_t)stream;

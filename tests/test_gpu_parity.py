@@ -250,6 +250,12 @@ def test_forward_is_deterministic_and_state_errors():
     with pytest.raises(pcb.PcError) as e:
         pcb.pc_forward(c.handle, c.theta, c.tables, c.x, None, 0, c._ws, c._ws.numel(), c.ll)
     assert e.value.status_name == "PC_ERR_ARG"
+    with pytest.raises(pcb.PcError) as e:                  # the kernels use 16-byte accesses
+        pcb.pc_forward(c.handle, c.theta[1:], c.tables, c.x, None, c.B, c._ws, c._ws.numel(), c.ll)
+    assert e.value.status_name == "PC_ERR_ARG"
+    with pytest.raises(pcb.PcError) as e:
+        pcb.pc_forward(c.handle, c.theta, c.tables, c.x, None, 2097153, c._ws, c._ws.numel(), c.ll)
+    assert e.value.status_name == "PC_ERR_TOO_LARGE"
     # EM invalidates the forward state
     c.forward(); c.backward(); c.em_step()
     with pytest.raises(pcb.PcError):
