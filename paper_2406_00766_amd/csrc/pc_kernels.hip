@@ -233,22 +233,12 @@ __global__ __launch_bounds__(256) void k_input_bwd_direct(const float *__restric
 // rg, rg+16, ... of 4 adjacent columns (16-byte accesses along the batch), so a K-row block is K/16 rows
 // deep per thread and all its loads are independent.  Column maxima over the K rows go through one
 // shuffle stage (4 row groups per wave) and one LDS stage (4 waves).
-// max(x of lane i, x of lane i ^ 32) in every lane: one swap of the wave's halves in the vector ALU instead of a
-// trip through the LDS crossbar
-__device__ inline float pc_max_across_halves(float x)
-{
-    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
-    const unsigned bits = __builtin_bit_cast(unsigned, x);
-    const u32x2 r = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
-    return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
-}
-
 __device__ inline void block_col_max(float (&mx)[4], float (*red)[64], int wave, int cl)
 {
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         mx[v] = fmaxf(mx[v], __shfl_xor(mx[v], 16));
-        mx[v] = pc_max_across_halves(mx[v]);
+        mx[v] = fmaxf(mx[v], __shfl_xor(mx[v], 32));
     }
     if ((threadIdx.x & 63) < 16) {
 #pragma unroll
@@ -553,8 +543,16 @@ __global__ __launch_bounds__(256) void k_sum_bwd_param_generic(const float *__re
 // exponentials that Sec. 4.1 describes.  The K x K weights have workgroup-uniform addresses and ride in scalar
 // registers.  Linear-space accumulators with a running maximum, as in the MFMA kernels.
 // ------------------------------------------------------------------------------------------
-#define PC_SPLIT 43.0f
-#define PC_SPLIT_CAP 44.5f
+// Two-factor split of a parameter-flow term exp(log_nf_s + l_c) around a = max_s log_nf_s of the sum block:
+//   first factor  exp(log_nf_s - a + PC_SPLIT_A)  <= e^31
+//   second factor exp(l_c + a - PC_SPLIT_B)       <= e^32.5   (theta p_c / p_s <= 1 and theta >= FLT_MIN bound l_c + a by 87.3)
+// The products carry the fixed scale e^-(PC_SPLIT_B - PC_SPLIT_A) = e^-24, taken out again when the flow is written:
+// a sum over up to 2^21 samples times a thousand tied instances of terms as large as 1 / FLT_MIN then still fits
+// fp32, and a product is lost to underflow only when the term is below e^-30.
+#define PC_SPLIT_A 31.0f
+#define PC_SPLIT_B 55.0f
+#define PC_SPLIT_CAP 32.5f
+#define PC_SPLIT_OUT 2.6489122e10f   /* e^24 */
 template <int K>
 __global__ __launch_bounds__(256) void k_sum_fwd_small(const float *__restrict__ theta, float *__restrict__ l,
                                                        float *__restrict__ R, const int32_t *__restrict__ ids,
@@ -692,8 +690,8 @@ __global__ __launch_bounds__(256) void k_param_flow_small(const float *__restric
                 const float mx = nfmax[(int64_t)(ms / K) * Bs + b];
                 const float dR = R[(int64_t)(ns / K) * Bs + b] - R[(int64_t)(ms / K) * Bs + b];
                 const bool live = mx > PC_NEG_INF;                      // dead sample: both factors 0
-                const float qa = live ? PC_SPLIT - mx : PC_NEG_INF;
-                const float qb = live ? mx + dR - PC_SPLIT : PC_NEG_INF;
+                const float qa = live ? PC_SPLIT_A - mx : PC_NEG_INF;
+                const float qb = live ? mx + dR - PC_SPLIT_B : PC_NEG_INF;
                 float fa[IG], fb[K];
 #pragma unroll
                 for (int i = 0; i < IG; ++i) fa[i] = __expf(N[(int64_t)(ms + ig + i) * Bs + b] + qa);
@@ -735,7 +733,7 @@ __global__ __launch_bounds__(256) void k_param_flow_small(const float *__restric
                 const int a = idx + e;                                  // = i * K + jj inside this pass
                 const int64_t at = (int64_t)pb + (int64_t)ig * K + a;
                 const float th = theta[at];
-                if (th > 0.0f) G[at] += th * acc[e];
+                if (th > 0.0f) G[at] += th * acc[e] * PC_SPLIT_OUT;
             }
         }
     }
@@ -921,7 +919,7 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
         } else {                                                                                                      \
             cmax = PC_NEG_INF;                                                                                        \
             _Pragma("unroll") for (int q = 0; q < NQ; ++q) cmax = fmaxf(cmax, V[q]);                                  \
-            cmax = pc_max_across_halves(cmax) + d;                                                                    \
+            cmax = fmaxf(cmax, __shfl_xor(cmax, 32)) + d;                                                             \
         }                                                                                                             \
         const float m_new = fmaxf(m, cmax);                                                                           \
         const bool dead = !(m_new > PC_NEG_INF);                        /* every term of this column so far is 0 */   \
@@ -1050,11 +1048,9 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
 // atomics and without the per-layer accumulation that closes Alg. 3.
 //
 // Each term exp(log_nf_s + l_c) is split into two fp32 factors around a per-sample shift (any shift is
-// valid: it only moves scale between the factors).  With a = max_s log_nf_s of the sum block, the
-// factors are exp(log_nf_s - a + 43) <= e^43 and exp(l_c + a - 43) <= e^44.3 (theta p_c / p_s <= 1 and
-// theta >= FLT_MIN bound l_c + a by 87.3), so neither overflows and a product is lost to underflow only
-// when it is below e^-40.  Alg. 3 shifts by a alone, which can drop products of order one when a weight
-// is as small as FLT_MIN.
+// valid: it only moves scale between the factors) -- the balanced split defined with PC_SPLIT_A / PC_SPLIT_B
+// above.  Alg. 3 shifts by the block maximum a alone, which can drop products of order one when a weight is as
+// small as FLT_MIN.
 //
 // Per chunk of 32 samples a wave fetches its TMW rows of N and TNW rows of l with 16-byte loads along
 // the batch, applies the exponentials, and stages both tiles in wave-private LDS (row stride 36 floats)
@@ -1119,8 +1115,8 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restr
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const bool live = mx_next[e] > PC_NEG_INF;
-            qa[e] = live ? (PC_SPLIT - mx_next[e]) * PC_LOG2E : PC_NEG_INF;              // dead sample: both factors 0
-            qb[e] = live ? (mx_next[e] + (rc_next[e] - rs_next[e]) - PC_SPLIT) * PC_LOG2E : PC_NEG_INF;
+            qa[e] = live ? (PC_SPLIT_A - mx_next[e]) * PC_LOG2E : PC_NEG_INF;              // dead sample: both factors 0
+            qb[e] = live ? (mx_next[e] + (rc_next[e] - rs_next[e]) - PC_SPLIT_B) * PC_LOG2E : PC_NEG_INF;
         }
 #pragma unroll
         for (int i = 0; i < NA4; ++i) {
@@ -1174,7 +1170,7 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restr
                 const int i = r0 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
                 const int64_t at = (int64_t)pb + (int64_t)i * K + c0 + ct * 32 + l32;
                 const float th = theta[at];
-                if (th > 0.0f) G[at] += th * acc[rt][ct][e];          // theta = 0: no flow (and never 0 * inf)
+                if (th > 0.0f) G[at] += th * acc[rt][ct][e] * PC_SPLIT_OUT;   // theta = 0: no flow (and never 0 * inf)
             }
 }
 
@@ -1252,8 +1248,8 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
         floatx4 qa, qb;                                                 /* per-sample shifts in log2 units */         \
         _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                               \
             const bool live = MX[e] > PC_NEG_INF;                                                                     \
-            qa[e] = live ? (PC_SPLIT - MX[e]) * PC_LOG2E : PC_NEG_INF;  /* dead sample: both factors 0 */             \
-            qb[e] = live ? (MX[e] + (RC[e] - RS[e]) - PC_SPLIT) * PC_LOG2E : PC_NEG_INF;                              \
+            qa[e] = live ? (PC_SPLIT_A - MX[e]) * PC_LOG2E : PC_NEG_INF; /* dead sample: both factors 0 */            \
+            qb[e] = live ? (MX[e] + (RC[e] - RS[e]) - PC_SPLIT_B) * PC_LOG2E : PC_NEG_INF;                            \
         }                                                                                                             \
         _Pragma("unroll") for (int i = 0; i < NL; ++i) {                                                              \
             floatx4 q, p;                                                                                             \
@@ -1316,7 +1312,7 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
                 const int i = r0 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
                 const int64_t at = (int64_t)pb + (int64_t)i * K + c0 + ct * 32 + l32;
                 const float th = theta[at];
-                if (th > 0.0f) G[at] += th * acc[rt][ct][e];          // theta = 0: no flow (and never 0 * inf)
+                if (th > 0.0f) G[at] += th * acc[rt][ct][e] * PC_SPLIT_OUT;   // theta = 0: no flow (and never 0 * inf)
             }
 }
 

@@ -153,6 +153,46 @@ def test_random_dags_with_skip_connections_tying_and_unused_blocks(seed, K, B):
     assert_device_tables_match_oracle(got["circuit"].handle, w)
 
 
+@pytest.mark.parametrize("make", [
+    # sharply peaked parameters (a quarter of the weights at FLT_MIN), 64 tied layers: node log_nf values spread over
+    # 100+ nats inside a block, so a wrong block maximum or an unbalanced factor split shows up as inf / lost flows
+    lambda: W.hmm(64, 64, 200, 32, 50, 31, alpha_trans=0.01, alpha_emis=0.01, tokens="zipf"),
+    lambda: W.hmm(12, 64, 300, 16, 70, 38, alpha_trans=0.02, alpha_emis=0.02, tokens="zipf"),
+    lambda: W.hmm(6, 256, 5000, 128, 40, 32, alpha_trans=0.02, alpha_emis=0.02, tokens="zipf"),
+    lambda: W.hmm(10, 128, 500, 64, 45, 39, alpha_trans=0.01, alpha_emis=0.01, tokens="zipf"),
+])
+def test_sharply_peaked_parameters(make):
+    w = make()
+    print(f"case peaked {w.name}", flush=True)
+    check_all(w)
+
+
+def test_block_references_and_block_maxima_are_what_they_claim():
+    """R of a product block = sum of its children's R + the ROUNDED column maximum of the block's residuals, so after
+    the forward pass every product block's residuals peak within [-0.5, 0.5]; nfmax = column maximum of log_nf."""
+    w = W.hmm(8, 64, 100, 32, 40, 40, alpha_trans=0.05, alpha_emis=0.05, tokens="zipf")
+    c = pcb.Circuit(w); c.set_batch(w.x); c._ws.fill_(255)
+    c.forward(); c.backward(); torch.cuda.synchronize()
+    K, B = w.K, w.B
+    l, F, R = c.node_buffers()
+    for u in np.nonzero(w.type == W.PRODUCT)[0]:
+        top = l[(u + 1) * K:(u + 2) * K, :B].max(dim=0).values.cpu().numpy()
+        assert np.all(np.abs(top) <= 0.5 + 1e-4), f"product block {u}: residual maximum {np.abs(top).max()}"
+    lay = pcb.pc_workspace_layout(c.handle, B)
+    n = c.sizes.n_rows * lay.stride
+    N = c._ws[lay.n_offset:lay.n_offset + 4 * n].view(torch.float32).view(c.sizes.n_rows, lay.stride)
+    ref = orc.backward(w, w.theta, w.tables, w.x, None)
+    lp, flow = ref[1], ref[2]
+    with np.errstate(divide="ignore"):
+        for u in np.nonzero(w.type == W.SUM)[0]:
+            if u == w.root_block:
+                continue
+            got = N[(u + 1) * K:(u + 2) * K, :B].max(dim=0).values.cpu().numpy() - R[u + 1, :B].cpu().numpy()
+            want = (np.log(flow[:, u * K:(u + 1) * K]) - lp[:, u * K:(u + 1) * K]).max(axis=1)
+            assert np.allclose(got, want, rtol=1e-4, atol=1e-3), f"sum block {u}"
+    c.close()
+
+
 def test_config1_full_size():
     w = W.config(1)
     print("case cfg1 full", flush=True)
