@@ -178,6 +178,11 @@ def test_block_references_and_block_maxima_are_what_they_claim():
     for u in np.nonzero(w.type == W.PRODUCT)[0]:
         top = l[(u + 1) * K:(u + 2) * K, :B].max(dim=0).values.cpu().numpy()
         assert np.all(np.abs(top) <= 0.5 + 1e-4), f"product block {u}: residual maximum {np.abs(top).max()}"
+    Rh = R[:, :B].cpu().numpy()
+    assert np.array_equal(Rh, np.rint(Rh))                 # references are integers: their differences are exact
+    for u in np.nonzero(w.type == W.SUM)[0]:                # a sum block's reference = the largest of its children's
+        ch = w.child[w.child_ptr[u]:w.child_ptr[u + 1]]
+        assert np.array_equal(Rh[u + 1], Rh[ch + 1].max(axis=0)), f"sum block {u}"
     lay = pcb.pc_workspace_layout(c.handle, B)
     n = c.sizes.n_rows * lay.stride
     N = c._ws[lay.n_offset:lay.n_offset + 4 * n].view(torch.float32).view(c.sizes.n_rows, lay.stride)
