@@ -29,6 +29,21 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 #define PC_NEG_INF (-__builtin_inff())
+// Sum-layer terms are theta * exp(value - running maximum + PC_UP).  The maximum is taken over the values alone (as in
+// Alg. 1 / Alg. 4), so without the upward shift a term with a large weight whose value lies 87 nats below that of a
+// child with a weight near FLT_MIN would be flushed to zero although it dominates the sum.  With it every term or
+// factor that underflows is at least e^-20 smaller than the largest term kept, and nothing can overflow.  The shift
+// is kept small because the result is  maximum - PC_UP + log(sum): the larger the two cancelling parts, the larger
+// the absolute rounding error of a log-probability near zero.
+#define PC_UP 20.0f
+// Rescaling an accumulator when the running maximum grows by -delta: the factor exp(delta) itself may leave the
+// fp32 range where accumulator * factor does not (the accumulator can be as large as e^28 times the term count),
+// so the factor is applied as two multiplications by exp(delta / 2); below delta = -174 the result is nil anyway.
+__device__ inline float pc_half_scale(float delta) { return __expf(0.5f * fmaxf(delta, -174.0f)); }
+// The running maximum is only a reference: it is raised (and the accumulator rescaled) when a chunk exceeds it by
+// more than PC_LAZY nats, not at every new maximum -- with 64 columns per wave some column has a new maximum in
+// almost every chunk, and the rescale costs a multiplication per accumulator register.  Terms reach e^(PC_UP + PC_LAZY).
+#define PC_LAZY 8.0f
 
 // ------------------------------------------------------------------------------------------
 // small utility kernels
@@ -583,13 +598,13 @@ __global__ __launch_bounds__(256) void k_sum_fwd_small(const float *__restrict__
 #pragma unroll
         for (int jj = 1; jj < K; ++jj) bm = fmaxf(bm, v[jj]);
         bm += d;
-        if (bm > m) {
-            const float sc = __expf(m - bm);                            // m = -inf: 0, and the accumulators are 0
+        if (bm > m + PC_LAZY) {
+            const float sc = pc_half_scale(m - bm);                     // m = -inf: the accumulators are 0
 #pragma unroll
-            for (int i = 0; i < K; ++i) acc[i] *= sc;
+            for (int i = 0; i < K; ++i) acc[i] = acc[i] * sc * sc;
             m = bm;
         }
-        const float sh = m > PC_NEG_INF ? d - m : 0.0f;                 // dead column: v = -inf -> p = 0
+        const float sh = m > PC_NEG_INF ? d - m + PC_UP : 0.0f;         // dead column: v = -inf -> p = 0
         float pv[K];
 #pragma unroll
         for (int jj = 0; jj < K; ++jj) pv[jj] = __expf(v[jj] + sh);
@@ -601,7 +616,7 @@ __global__ __launch_bounds__(256) void k_sum_fwd_small(const float *__restrict__
         }
     }
 #pragma unroll
-    for (int i = 0; i < K; ++i) l[(int64_t)(id + i) * Bs + b] = acc[i] > 0.0f ? m + __logf(acc[i]) : PC_NEG_INF;
+    for (int i = 0; i < K; ++i) l[(int64_t)(id + i) * Bs + b] = acc[i] > 0.0f ? m - PC_UP + __logf(acc[i]) : PC_NEG_INF;
     R[(int64_t)(id / K) * Bs + b] = Rrow;
 }
 
@@ -636,13 +651,13 @@ __global__ __launch_bounds__(256) void k_sum_bwd_small(const float *__restrict__
         for (int i = 0; i < K; ++i) nv[i] = N[(int64_t)(ms + i) * Bs + b];
         const float d = Rc - R[(int64_t)(ms / K) * Bs + b];
         const float bm = nfmax[(int64_t)(ms / K) * Bs + b] + d;
-        if (bm > m) {
-            const float sc = __expf(m - bm);
+        if (bm > m + PC_LAZY) {
+            const float sc = pc_half_scale(m - bm);
 #pragma unroll
-            for (int jj = 0; jj < K; ++jj) acc[jj] *= sc;
+            for (int jj = 0; jj < K; ++jj) acc[jj] = acc[jj] * sc * sc;
             m = bm;
         }
-        const float sh = m > PC_NEG_INF ? d - m : 0.0f;
+        const float sh = m > PC_NEG_INF ? d - m + PC_UP : 0.0f;
         float pv[K];
 #pragma unroll
         for (int i = 0; i < K; ++i) pv[i] = __expf(nv[i] + sh);
@@ -654,7 +669,7 @@ __global__ __launch_bounds__(256) void k_sum_bwd_small(const float *__restrict__
 #pragma unroll
     for (int jj = 0; jj < K; ++jj) {
         const int64_t at = (int64_t)(id + jj) * Bs + b;
-        const float add = (acc[jj] > 0.0f && lown[jj] > PC_NEG_INF) ? __expf(__logf(acc[jj]) + m + lown[jj]) : 0.0f;
+        const float add = (acc[jj] > 0.0f && lown[jj] > PC_NEG_INF) ? __expf(__logf(acc[jj]) + (m - PC_UP) + lown[jj]) : 0.0f;
         if (first) F[at] = add;                                         // first layer that feeds the block stores
         else if (add > 0.0f) F[at] += add;
     }
@@ -921,16 +936,16 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
             _Pragma("unroll") for (int q = 0; q < NQ; ++q) cmax = fmaxf(cmax, V[q]);                                  \
             cmax = fmaxf(cmax, __shfl_xor(cmax, 32)) + d;                                                             \
         }                                                                                                             \
-        const float m_new = fmaxf(m, cmax);                                                                           \
+        const float m_new = cmax > m + PC_LAZY ? cmax : m;              /* -inf + 8 = -inf: the first finite chunk sets it */  \
         const bool dead = !(m_new > PC_NEG_INF);                        /* every term of this column so far is 0 */   \
         if (__any(m_new != m)) {                                                                                      \
-            const float scale = dead ? 1.0f : __expf(m - m_new);        /* m = -inf -> 0, acc is 0 anyway */          \
+            const float scale = dead ? 1.0f : pc_half_scale(m - m_new); /* m = -inf: acc is 0 anyway */               \
             _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                         \
-                _Pragma("unroll") for (int e = 0; e < 16; ++e) acc[rt][e] *= scale;                                   \
+                _Pragma("unroll") for (int e = 0; e < 16; ++e) acc[rt][e] = acc[rt][e] * scale * scale;               \
         }                                                                                                             \
         m = m_new;                                                                                                    \
         /* exp(v + d - m) = exp2(v * log2e + sh2); dead column: v = -inf -> 0 */                                      \
-        sh2 = dead ? 0.0f : (d - m_new) * PC_LOG2E;                                                                   \
+        sh2 = dead ? 0.0f : (d - m_new + PC_UP) * PC_LOG2E;                                                           \
     } while (0)
     // MFMA steps [Q0, Q0 + NQ/2) of a chunk
 #define PC_MATH(AR, V, Q0)                                                                                            \
@@ -1011,11 +1026,11 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
             }
             const float m_new = fmaxf(m, mo);
             const bool dead = !(m_new > PC_NEG_INF);
-            const float s0 = dead ? 1.0f : __expf(m - m_new), s1 = dead ? 0.0f : __expf(mo - m_new);
+            const float s0 = dead ? 1.0f : pc_half_scale(m - m_new), s1 = dead ? 0.0f : pc_half_scale(mo - m_new);
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[rt][e] = acc[rt][e] * s0 + ob[(rt * 16 + e) * 64 + lane] * s1;
+                for (int e = 0; e < 16; ++e) acc[rt][e] = acc[rt][e] * s0 * s0 + ob[(rt * 16 + e) * 64 + lane] * s1 * s1;
             m = m_new;
         }
     }
@@ -1031,11 +1046,11 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
             const int64_t at = (base + i) * Bs + col;
             if (BWD) {
                 const float lc = lown[rt][e];
-                const float add = (a > 0.0f && lc > PC_NEG_INF) ? __expf(__logf(a) + m + lc) : 0.0f;
+                const float add = (a > 0.0f && lc > PC_NEG_INF) ? __expf(__logf(a) + (m - PC_UP) + lc) : 0.0f;
                 if (first) F[at] = add;
                 else if (add > 0.0f) F[at] += add;
             } else {
-                l[at] = a > 0.0f ? m + __logf(a) : PC_NEG_INF;
+                l[at] = a > 0.0f ? m - PC_UP + __logf(a) : PC_NEG_INF;
             }
         }
 }

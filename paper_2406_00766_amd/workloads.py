@@ -644,7 +644,7 @@ def sum_layer_dense(w: Workload, s: int) -> np.ndarray:
 # Random alternating DAGs (test inputs: skip connections, tying, placeholders, unused blocks)
 # --------------------------------------------------------------------------------------------
 def random_circuit(n_vars: int, n_levels: int, width: int, K: int, B: int, seed: int, *, n_cats=5, tie_prob=0.3,
-                   name=None) -> Workload:
+                   alpha=0.5, name=None) -> Workload:
     """A random block DAG that alternates product and sum levels above one input level.
 
     Children are drawn from ALL lower levels of the right kind (products take sum and input blocks, sums take
@@ -703,12 +703,12 @@ def random_circuit(n_vars: int, n_levels: int, width: int, K: int, B: int, seed:
             continue
         done.update(ids)
         rows = bld.n_real[sblk]
-        Wt = _f32_floor(_dirichlet_rows(rng, 0.5, (rows, len(chs) * K)))
+        Wt = _f32_floor(_dirichlet_rows(rng, alpha, (rows, len(chs) * K)))
         for j, pid in enumerate(ids):
             theta[pid + 1, :rows, :] = Wt[:, j * K:(j + 1) * K]
     tables = np.empty((width, n_cats, K), dtype=np.float32)
     for t in range(width):
-        tables[t] = _f32_floor(_dirichlet_rows(rng, 1.0, (K, n_cats))).T
+        tables[t] = _f32_floor(_dirichlet_rows(rng, min(1.0, 2 * alpha), (K, n_cats))).T
     x = rng.integers(0, n_cats, size=(B, n_vars))
     return _make(name or f"random_v{n_vars}_L{n_levels}_w{width}_K{K}_B{B}_s{seed}", bld, root, n_param_blocks, n_vars, n_cats,
                  width, theta, tables, x, {"kind": "random"})

@@ -167,6 +167,17 @@ def test_sharply_peaked_parameters(make):
     check_all(w)
 
 
+@pytest.mark.parametrize("seed,K", [(3001, 1), (3002, 4), (3014, 4), (3038, 8), (3017, 4), (3018, 1), (3005, 32), (3006, 64),
+                                    (3010, 128), (3012, 16)])
+def test_random_dags_with_weights_at_the_fp32_floor(seed, K):
+    """A quarter of the weights sit at FLT_MIN: a child with such a weight and a large value sets the running maximum
+    while a child 87 nats below it with weight 1 contributes as much -- the sum must keep both."""
+    s = seed - 3000
+    w = W.random_circuit(4 + s % 4, 4 + s % 6, 3 + s % 4, K, 40 if K > 1 else 64, seed, tie_prob=0.5, alpha=0.02)
+    print(f"case floor {w.name}", flush=True)
+    check_all(w)
+
+
 def test_block_references_and_block_maxima_are_what_they_claim():
     """R of a product block = sum of its children's R + the ROUNDED column maximum of the block's residuals, so after
     the forward pass every product block's residuals peak within [-0.5, 0.5]; nfmax = column maximum of log_nf."""
