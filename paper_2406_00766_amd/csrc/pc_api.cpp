@@ -79,6 +79,26 @@ static const char *const kClassNames[KC_COUNT] = {"misc", "input_fwd", "prod_fwd
 
 static GroupDev dev(const GroupTab &g) { return GroupDev{g.n_rows, g.width, g.d_ids, g.d_nbr, g.d_par, g.tied_in_group, g.d_aux}; }
 
+// Group sets of every layer, built once after the tables are on the device.
+struct LaunchPlan {
+    struct Layer { std::vector<GroupSet> fwd, bwd; };
+    std::vector<Layer> layers;
+};
+static LaunchPlan *make_plan(const pc_circuit *c)
+{
+    LaunchPlan *p = new (std::nothrow) LaunchPlan();
+    if (!p) return nullptr;
+    p->layers.resize(c->layers.size());
+    for (size_t li = 0; li < c->layers.size(); ++li) {
+        std::vector<GroupDev> f, b;
+        for (const GroupTab &g : c->layers[li].fwd) f.push_back(dev(g));
+        for (const GroupTab &g : c->layers[li].bwd) b.push_back(dev(g));
+        p->layers[li].fwd = make_group_sets(f);
+        p->layers[li].bwd = make_group_sets(b);
+    }
+    return p;
+}
+
 struct Ws {
     int64_t Bs;
     size_t l_off, f_off, n_off, r_off, mx_off, xt_off, total;
@@ -127,6 +147,7 @@ pc_status pc_compile(const pc_dag *dag, void *stream, pc_circuit **out)
     if (!c) return fail(PC_ERR_ARG, "out of host memory");
     pc_status st = compile_host(dag, c, /*tables_on_host=*/false);      // validation, layering, EM and flow maps
     if (st == PC_OK) st = build_tables_device(dag, c, stream);          // groups (Alg. 2) + tables filled by HIP kernels
+    if (st == PC_OK && !(c->plan = make_plan(c))) st = fail(PC_ERR_ARG, "out of host memory");
     if (st != PC_OK) { pc_destroy(c); return st; }
     const char *env = std::getenv("PC_FORCE_GENERIC");
     set_force_generic(env && env[0] == '1');
@@ -139,6 +160,7 @@ void pc_destroy(pc_circuit *c)
     if (!c) return;
     if (c->d_arena) (void)hipFree(c->d_arena);
     delete (Profiler *)c->profiler;
+    delete (LaunchPlan *)c->plan;
     delete c;
 }
 
@@ -243,13 +265,15 @@ pc_status pc_forward(pc_circuit *c, const float *theta, const float *tables, con
     launch_prepare_x(x, mask, B, c->n_vars, w.Bs, c->n_cats, xT, s);
     launch_fill(l, (int64_t)K * w.Bs, 0.0f, s);                                  // null block: probability 1
     launch_fill(R, ((int64_t)c->n_blocks + 1) * w.Bs, 0.0f, s);                  // input and null blocks: R = 0
-    for (const LayerTab &L : c->layers) {
+    const LaunchPlan &plan = *(const LaunchPlan *)c->plan;
+    for (size_t li = 0; li < c->layers.size(); ++li) {
+        const LayerTab &L = c->layers[li];
         if (L.kind == KIND_INPUT) {
             launch_input_fwd(tables, xT, dev(L.fwd[0]), K, c->n_cats, w.Bs, l, s);
         } else if (L.kind == KIND_PRODUCT) {
-            for (const GroupTab &g : L.fwd) launch_prod_fwd(l, R, dev(g), K, w.Bs, s);
+            launch_prod_fwd(l, R, plan.layers[li].fwd, K, w.Bs, s);
         } else {
-            for (const GroupTab &g : L.fwd) launch_sum_fwd(theta, l, R, dev(g), K, w.Bs, s);
+            launch_sum_fwd(theta, l, R, plan.layers[li].fwd, K, w.Bs, s);
         }
     }
     launch_readout(l, R, (int64_t)(c->root_block + 1) * K, (int64_t)c->root_block + 1, w.Bs, B, ll, s);
@@ -286,15 +310,16 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
     const bool batched_params = param_flow_by_block(K);
     // no clearing of F: every block's flow is stored by the first layer that feeds it, blocks nobody feeds are
     // initialised here
+    const LaunchPlan &plan = *(const LaunchPlan *)c->plan;
     launch_init_flows(l, F, N, nfmax, c->d_init_ids, (int32_t)c->init_ids.size(), (c->root_block + 1) * K, K, w.Bs, B, s);
     for (size_t li = c->layers.size(); li-- > 0;) {
         const LayerTab &L = c->layers[li];
         if (L.kind == KIND_SUM) {
-            for (const GroupTab &g : L.bwd) launch_sum_bwd_child(theta, l, R, N, nfmax, F, dev(g), K, w.Bs, s);
+            launch_sum_bwd_child(theta, l, R, N, nfmax, F, plan.layers[li].bwd, K, w.Bs, s);
             if (theta_flow && !batched_params)
                 for (const GroupTab &g : L.fwd) launch_sum_bwd_param_generic(theta, l, R, N, theta_flow, dev(g), K, w.Bs, B, s);
         } else if (L.kind == KIND_PRODUCT) {
-            for (const GroupTab &g : L.bwd) launch_prod_bwd(l, F, N, nfmax, dev(g), K, w.Bs, s);
+            launch_prod_bwd(l, F, N, nfmax, plan.layers[li].bwd, K, w.Bs, s);
         } else if (table_flow) {
             launch_input_bwd(F, xT, dev(L.fwd[0]), K, c->n_cats, w.Bs, table_flow, s);
         }

@@ -75,6 +75,7 @@ struct pc_circuit {
 
     // optional per-kernel-class timing (pc_profile_*)
     void *profiler = nullptr;                         // pc::Profiler*, owned
+    void *plan = nullptr;                             // launch plan (group sets per layer), owned
     int64_t prof_launches[16] = {0};
     double prof_ms[16] = {0.0};
 

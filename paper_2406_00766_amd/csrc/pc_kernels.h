@@ -14,6 +14,16 @@ struct GroupDev {            // device view of one table group
     const int32_t *aux;      // per row: real neighbours << 8 | bit 0 flow final after this layer | bit 1 first layer to write it
 };
 
+// Table groups of one layer that one launch covers (a kernel argument, passed by value).  Rows of the launch are
+// numbered through the groups; group g holds rows first[g] .. first[g + 1].
+constexpr int PC_MAX_SET = 8;
+struct GroupSet {
+    int32_t n;
+    int32_t first[PC_MAX_SET + 1];
+    int32_t width[PC_MAX_SET];
+    const int32_t *ids[PC_MAX_SET], *nbr[PC_MAX_SET], *par[PC_MAX_SET], *aux[PC_MAX_SET];
+};
+
 struct ParamFlowDev {        // parameter blocks with the (sum block, child block) pairs that use them
     int32_t n_pb;
     const int32_t *pb, *ptr, *sum, *child;
@@ -54,11 +64,16 @@ void launch_input_fwd(const float *tables, const int32_t *xT, const GroupDev &g,
                       float *l, hipStream_t s);
 void launch_input_bwd(const float *F, const int32_t *xT, const GroupDev &g, int32_t K, int32_t n_cats, int64_t Bs,
                       float *table_flow, hipStream_t s);
-void launch_prod_fwd(float *l, float *R, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s);
-void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s);
-void launch_sum_fwd(const float *theta, float *l, float *R, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s);
+// The four layer launchers take all table groups of the layer, packed into sets by make_group_sets: the groups of a
+// layer are independent of one another, and one launch covers a whole set.
+std::vector<GroupSet> make_group_sets(const std::vector<GroupDev> &groups);
+void launch_prod_fwd(float *l, float *R, const std::vector<GroupSet> &sets, int32_t K, int64_t Bs, hipStream_t s);
+void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const std::vector<GroupSet> &sets, int32_t K,
+                     int64_t Bs, hipStream_t s);
+void launch_sum_fwd(const float *theta, float *l, float *R, const std::vector<GroupSet> &sets, int32_t K, int64_t Bs,
+                    hipStream_t s);
 void launch_sum_bwd_child(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *F,
-                          const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s);
+                          const std::vector<GroupSet> &sets, int32_t K, int64_t Bs, hipStream_t s);
 void launch_sum_bwd_param_generic(const float *theta, const float *l, const float *R, const float *N, float *G,
                                   const GroupDev &g, int32_t K, int64_t Bs, int32_t B, hipStream_t s);
 bool param_flow_by_block(int32_t K);

@@ -18,8 +18,10 @@
 // running maximum of the log-sum-exp is a per-lane scalar.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <cstring>
 
 #include "pc_kernels.h"
 
@@ -241,6 +243,29 @@ __global__ __launch_bounds__(256) void k_input_bwd_direct(const float *__restric
     }
 }
 
+// Group of launch row `row` in a set (wave-uniform).  Every field of the argument is at a fixed offset, so all of
+// them are fetched at once with the other kernel arguments and the group's are picked with scalar selects: no load
+// depends on the group index.  Kernels are instantiated for one group (MULTI = false: the deep narrow circuits,
+// where even the selects show in a launch of a few microseconds) and for several.
+struct GroupRow { int32_t r, width; const int32_t *ids, *nbr, *par, *aux; };
+template <bool MULTI>
+__device__ inline GroupRow locate_row(const GroupSet &gs, int row)
+{
+    GroupRow o{row, gs.width[0], gs.ids[0], gs.nbr[0], gs.par[0], gs.aux[0]};
+    if (!MULTI) return o;                                               // a set of one group: nothing to pick
+#pragma unroll
+    for (int i = 1; i < PC_MAX_SET; ++i) {
+        const bool here = i < gs.n && row >= gs.first[i];
+        o.r = here ? row - gs.first[i] : o.r;
+        o.width = here ? gs.width[i] : o.width;
+        o.ids = here ? gs.ids[i] : o.ids;
+        o.nbr = here ? gs.nbr[i] : o.nbr;
+        o.par = here ? gs.par[i] : o.par;
+        o.aux = here ? gs.aux[i] : o.aux;
+    }
+    return o;
+}
+
 // ------------------------------------------------------------------------------------------
 // product layers: forward adds child log-probs (Sec. 3); backward adds parent flows (Def. 2)
 // ------------------------------------------------------------------------------------------
@@ -273,19 +298,19 @@ __device__ inline void block_col_max(float (&mx)[4], float (*red)[64], int wave,
 
 // forward (Sec. 3): s = sum of the children's residuals; the column maximum over the K rows is rounded to an
 // integer and moved into R
-template <int RPT, int U>
-__global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *__restrict__ R,
-                                                  const int32_t *__restrict__ ids, const int32_t *__restrict__ nbr,
-                                                  const int32_t *__restrict__ flags, int32_t width, int32_t K, int64_t Bs)
+template <int RPT, int U, bool MULTI>
+__global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *__restrict__ R, const GroupSet gs,
+                                                  int32_t K, int64_t Bs)
 {
     __shared__ float red[4][64];
-    const int r = blockIdx.x;
+    const GroupRow gr = locate_row<MULTI>(gs, blockIdx.x);
+    const int r = gr.r;
     const int rg = threadIdx.x >> 4, cl = threadIdx.x & 15, wave = threadIdx.x >> 6;
     const int64_t b = (int64_t)blockIdx.y * 64 + cl * 4;
     const bool in = b < Bs;                                            // Bs is a multiple of 32: b..b+3 all inside
-    const int32_t *row_nbr = nbr + (int64_t)r * width;
-    const int32_t cnt = flags[r] >> 8;
-    const int32_t id = ids[r];
+    const int32_t *row_nbr = gr.nbr + (int64_t)r * gr.width;
+    const int32_t cnt = gr.aux[r] >> 8;
+    const int32_t id = gr.ids[r];
     float4 s[RPT];
     float mx[4] = {PC_NEG_INF, PC_NEG_INF, PC_NEG_INF, PC_NEG_INF};
     float4 rsum = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -344,20 +369,19 @@ __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *
 // F_child += sum of the parents' flows ('=' where this is the first layer that feeds the block, flag bit 1, so
 // the flow buffer is never cleared).  Where this layer is the last one that feeds a SUM block (flag bit 0) its
 // flow is final, so log_nf = log F - l (Alg. 3 / 4) and its column maximum per block are produced here.
-template <int RPT, int U>
+template <int RPT, int U, bool MULTI>
 __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, float *__restrict__ F, float *__restrict__ N,
-                                                  float *__restrict__ nfmax, const int32_t *__restrict__ ids,
-                                                  const int32_t *__restrict__ nbr, const int32_t *__restrict__ flags,
-                                                  int32_t width, int32_t K, int64_t Bs)
+                                                  float *__restrict__ nfmax, const GroupSet gs, int32_t K, int64_t Bs)
 {
     __shared__ float red[4][64];
-    const int r = blockIdx.x;
+    const GroupRow gr = locate_row<MULTI>(gs, blockIdx.x);
+    const int r = gr.r;
     const int rg = threadIdx.x >> 4, cl = threadIdx.x & 15, wave = threadIdx.x >> 6;
     const int64_t b = (int64_t)blockIdx.y * 64 + cl * 4;
     const bool in = b < Bs;
-    const int32_t *row_nbr = nbr + (int64_t)r * width;
-    const int32_t id = ids[r];
-    const int32_t fl = flags[r];                                        // uniform over the workgroup
+    const int32_t *row_nbr = gr.nbr + (int64_t)r * gr.width;
+    const int32_t id = gr.ids[r];
+    const int32_t fl = gr.aux[r];                                       // uniform over the workgroup
     const bool final_flow = (fl & 1) != 0, first = (fl & 2) != 0;
     const int32_t cnt = fl >> 8;
     float4 f[RPT], lv[RPT];
@@ -784,13 +808,11 @@ __global__ __launch_bounds__(256) void k_param_flow_small(const float *__restric
 // buffer descriptor of the main-loop loads: raw (stride 0), 2 GiB window from the chunk's base, 32-bit data format
 #define PC_BUF_RANGE 0x7fffffff
 #define PC_BUF_FLAGS 0x00020000
-template <int K, int RT, int SPLIT, bool BWD>
+template <int K, int RT, int SPLIT, bool BWD, bool MULTI>
 __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ theta, float *__restrict__ l,
                                                      float *__restrict__ R, const float *__restrict__ N,
                                                      const float *__restrict__ nfmax, float *__restrict__ F,
-                                                     const int32_t *__restrict__ ids, const int32_t *__restrict__ nbr,
-                                                     const int32_t *__restrict__ par, const int32_t *__restrict__ flags,
-                                                     int32_t width, int64_t Bs)
+                                                     const GroupSet gs, int64_t Bs)
 {
     constexpr int KC = 32;
     constexpr int TM = 32 * RT;
@@ -809,13 +831,14 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
     const int ct = wave / SPLIT, sp = wave % SPLIT;
-    const int r = blockIdx.x / SUB, sub = blockIdx.x % SUB;
+    const GroupRow gr = locate_row<MULTI>(gs, blockIdx.x / SUB);
+    const int r = gr.r, sub = blockIdx.x % SUB;
     const int64_t col0 = ((int64_t)blockIdx.y * NCT + ct) * 32;
     const bool active = col0 < Bs;                                      // wave-uniform
     const int64_t col = (active ? col0 : 0) + l32;
-    const int32_t *row_nbr = nbr + (int64_t)r * width, *row_par = par + (int64_t)r * width;
-    const int32_t id = ids[r];
-    const int32_t fl = flags[r];                                        // wave-uniform
+    const int32_t *row_nbr = gr.nbr + (int64_t)r * gr.width, *row_par = gr.par + (int64_t)r * gr.width;
+    const int32_t id = gr.ids[r];
+    const int32_t fl = gr.aux[r];                                       // wave-uniform
     // backward: the first layer of the sweep that feeds this block stores its flow, later ones accumulate
     const bool first = (fl & 2) != 0;
     float *buf = lds + wave * WSZ;
@@ -1553,33 +1576,72 @@ void launch_input_bwd(const float *F, const int32_t *xT, const GroupDev &g, int3
 }
 
 // rows per thread and neighbours in flight by block size: about 16 outstanding 16-byte loads per thread
+#define PC_DISPATCH_PROD_M(KERNEL, MULTI, ...)                                                             \
+    do {                                                                                                   \
+        if (K <= 16) hipLaunchKernelGGL((KERNEL<1, 8, MULTI>), __VA_ARGS__);                               \
+        else if (K <= 32) hipLaunchKernelGGL((KERNEL<2, 8, MULTI>), __VA_ARGS__);                          \
+        else if (K <= 64) hipLaunchKernelGGL((KERNEL<4, 4, MULTI>), __VA_ARGS__);                          \
+        else hipLaunchKernelGGL((KERNEL<8, 2, MULTI>), __VA_ARGS__);                                       \
+    } while (0)
 #define PC_DISPATCH_PROD(KERNEL, ...)                                                                      \
     do {                                                                                                   \
-        if (K <= 16) hipLaunchKernelGGL((KERNEL<1, 8>), __VA_ARGS__);                                      \
-        else if (K <= 32) hipLaunchKernelGGL((KERNEL<2, 8>), __VA_ARGS__);                                 \
-        else if (K <= 64) hipLaunchKernelGGL((KERNEL<4, 4>), __VA_ARGS__);                                 \
-        else hipLaunchKernelGGL((KERNEL<8, 2>), __VA_ARGS__);                                              \
+        if (gs.n > 1) PC_DISPATCH_PROD_M(KERNEL, true, __VA_ARGS__);                                       \
+        else PC_DISPATCH_PROD_M(KERNEL, false, __VA_ARGS__);                                               \
     } while (0)
 
-void launch_prod_fwd(float *l, float *R, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
+// Sets of at most PC_MAX_SET groups, widest rows first (the longest rows start first, so they do not trail the launch).
+std::vector<GroupSet> make_group_sets(const std::vector<GroupDev> &groups)
 {
-    if (g.n_rows == 0) return;
-    Timed timed(KC_PROD_FWD, s);
-    dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 63) / 64));
-    PC_DISPATCH_PROD(k_prod_fwd, grid, dim3(256), 0, s, l, R, g.ids, g.nbr, g.aux, g.width, K, Bs);
+    std::vector<const GroupDev *> order;
+    for (const GroupDev &g : groups)
+        if (g.n_rows > 0) order.push_back(&g);
+    std::stable_sort(order.begin(), order.end(), [](const GroupDev *a, const GroupDev *b) { return a->width > b->width; });
+    std::vector<GroupSet> sets;
+    for (size_t i = 0; i < order.size(); ++i) {
+        if (i % PC_MAX_SET == 0) { sets.emplace_back(); std::memset(&sets.back(), 0, sizeof(GroupSet)); }
+        GroupSet &gs = sets.back();
+        const GroupDev &g = *order[i];
+        const int k = gs.n++;
+        gs.first[k + 1] = gs.first[k] + g.n_rows;
+        gs.width[k] = g.width;
+        gs.ids[k] = g.ids; gs.nbr[k] = g.nbr; gs.par[k] = g.par; gs.aux[k] = g.aux;
+    }
+    return sets;
+}
+static inline int32_t set_rows(const GroupSet &gs) { return gs.first[gs.n]; }
+static inline int32_t set_width(const GroupSet &gs)
+{
+    int32_t w = 0;
+    for (int k = 0; k < gs.n; ++k) w = std::max(w, gs.width[k]);
+    return w;
 }
 
-void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
+void launch_prod_fwd(float *l, float *R, const std::vector<GroupSet> &sets, int32_t K, int64_t Bs, hipStream_t s)
 {
-    if (g.n_rows == 0) return;
-    Timed timed(KC_PROD_BWD, s);
-    dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 63) / 64));
-    PC_DISPATCH_PROD(k_prod_bwd, grid, dim3(256), 0, s, l, F, N, nfmax, g.ids, g.nbr, g.aux, g.width, K, Bs);
+    for (const GroupSet &gs : sets) {
+        Timed timed(KC_PROD_FWD, s);
+        dim3 grid((unsigned)set_rows(gs), (unsigned)((Bs + 63) / 64));
+        PC_DISPATCH_PROD(k_prod_fwd, grid, dim3(256), 0, s, l, R, gs, K, Bs);
+    }
+}
+
+void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const std::vector<GroupSet> &sets, int32_t K,
+                     int64_t Bs, hipStream_t s)
+{
+    for (const GroupSet &gs : sets) {
+        Timed timed(KC_PROD_BWD, s);
+        dim3 grid((unsigned)set_rows(gs), (unsigned)((Bs + 63) / 64));
+        PC_DISPATCH_PROD(k_prod_bwd, grid, dim3(256), 0, s, l, F, N, nfmax, gs, K, Bs);
+    }
 }
 
 // forward / backward-to-children: (K, rows per wave tile / 32, waves sharing one tile)
 #define PC_SUM_CASE(KK, RR, SS, BWD, ...)                                                                  \
-    if (K == KK && rt == RR && split == SS) { hipLaunchKernelGGL((k_sum_mfma<KK, RR, SS, BWD>), __VA_ARGS__); break; }
+    if (K == KK && rt == RR && split == SS) {                                                              \
+        if (gs.n > 1) hipLaunchKernelGGL((k_sum_mfma<KK, RR, SS, BWD, true>), __VA_ARGS__);                \
+        else hipLaunchKernelGGL((k_sum_mfma<KK, RR, SS, BWD, false>), __VA_ARGS__);                        \
+        break;                                                                                             \
+    }
 #define PC_DISPATCH_SUM(BWD, ...)                                                                         \
     do {                                                                                                  \
         PC_SUM_CASE(32, 1, 1, BWD, __VA_ARGS__) PC_SUM_CASE(32, 1, 2, BWD, __VA_ARGS__) PC_SUM_CASE(32, 1, 4, BWD, __VA_ARGS__)    \
@@ -1603,47 +1665,64 @@ static void pick_sum_shape(int32_t K, int32_t n_rows, int32_t width, int64_t Bs,
     while (split < 4 && tiles * split < want && (int64_t)width * (K / 32) >= 2 * split) split <<= 1;
 }
 
-void launch_sum_fwd(const float *theta, float *l, float *R, const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
+void launch_sum_fwd(const float *theta, float *l, float *R, const std::vector<GroupSet> &sets, int32_t K, int64_t Bs,
+                    hipStream_t s)
 {
-    Timed timed(KC_SUM_FWD, s);
-    if (g.n_rows == 0) return;
     if (use_mfma(K)) {
-        int rt, split;
-        pick_sum_shape(K, g.n_rows, g.width, Bs, rt, split);
-        const int64_t cols_per_wg = 32 * (4 / split);
-        dim3 grid((unsigned)(g.n_rows * (K / (32 * rt))), (unsigned)((Bs + cols_per_wg - 1) / cols_per_wg));
-        PC_DISPATCH_SUM(false, grid, dim3(256), 0, s, theta, l, R, (const float *)nullptr, (const float *)nullptr,
-                        (float *)nullptr, g.ids, g.nbr, g.par, g.aux, g.width, Bs);
-    } else if (use_small(K)) {
-        dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 255) / 256));
-        PC_DISPATCH_SMALL(k_sum_fwd_small, grid, dim3(256), 0, s, theta, l, R, g.ids, g.nbr, g.par, g.aux, g.width, Bs);
-    } else {
-        const int64_t items = (int64_t)g.n_rows * K * Bs;
-        hipLaunchKernelGGL(k_sum_fwd_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, l, R, g.ids, g.nbr, g.par,
-                           g.n_rows, g.width, K, Bs);
+        for (const GroupSet &gs : sets) {
+            Timed timed(KC_SUM_FWD, s);
+            int rt, split;
+            pick_sum_shape(K, set_rows(gs), set_width(gs), Bs, rt, split);
+            const int64_t cols_per_wg = 32 * (4 / split);
+            dim3 grid((unsigned)(set_rows(gs) * (K / (32 * rt))), (unsigned)((Bs + cols_per_wg - 1) / cols_per_wg));
+            PC_DISPATCH_SUM(false, grid, dim3(256), 0, s, theta, l, R, (const float *)nullptr, (const float *)nullptr,
+                            (float *)nullptr, gs, Bs);
+        }
+        return;
+    }
+    // other block sizes: one launch per group
+    for (const GroupSet &gs : sets) for (int k = 0; k < gs.n; ++k) {
+        const GroupDev g{gs.first[k + 1] - gs.first[k], gs.width[k], gs.ids[k], gs.nbr[k], gs.par[k], false, gs.aux[k]};
+        Timed timed(KC_SUM_FWD, s);
+        if (use_small(K)) {
+            dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 255) / 256));
+            PC_DISPATCH_SMALL(k_sum_fwd_small, grid, dim3(256), 0, s, theta, l, R, g.ids, g.nbr, g.par, g.aux, g.width, Bs);
+        } else {
+            const int64_t items = (int64_t)g.n_rows * K * Bs;
+            hipLaunchKernelGGL(k_sum_fwd_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, l, R, g.ids, g.nbr, g.par,
+                               g.n_rows, g.width, K, Bs);
+        }
     }
 }
 
 void launch_sum_bwd_child(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *F,
-                          const GroupDev &g, int32_t K, int64_t Bs, hipStream_t s)
+                          const std::vector<GroupSet> &sets, int32_t K, int64_t Bs, hipStream_t s)
 {
-    Timed timed(KC_SUM_BWD_CHILD, s);
-    if (g.n_rows == 0) return;
     if (use_mfma(K)) {
-        int rt, split;
-        pick_sum_shape(K, g.n_rows, g.width, Bs, rt, split);
-        const int64_t cols_per_wg = 32 * (4 / split);
-        dim3 grid((unsigned)(g.n_rows * (K / (32 * rt))), (unsigned)((Bs + cols_per_wg - 1) / cols_per_wg));
-        PC_DISPATCH_SUM(true, grid, dim3(256), 0, s, theta, const_cast<float *>(l), const_cast<float *>(R), N, nfmax,
-                        F, g.ids, g.nbr, g.par, g.aux, g.width, Bs);
-    } else if (use_small(K)) {
-        dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 255) / 256));
-        PC_DISPATCH_SMALL(k_sum_bwd_small, grid, dim3(256), 0, s, theta, l, R, N, nfmax, F, g.ids, g.nbr, g.par, g.aux,
-                          g.width, Bs);
-    } else {
-        const int64_t items = (int64_t)g.n_rows * K * Bs;
-        hipLaunchKernelGGL(k_sum_bwd_child_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, l, R, N, F, g.ids, g.nbr,
-                           g.par, g.aux, g.n_rows, g.width, K, Bs);
+        for (const GroupSet &gs : sets) {
+            Timed timed(KC_SUM_BWD_CHILD, s);
+            int rt, split;
+            pick_sum_shape(K, set_rows(gs), set_width(gs), Bs, rt, split);
+            const int64_t cols_per_wg = 32 * (4 / split);
+            dim3 grid((unsigned)(set_rows(gs) * (K / (32 * rt))), (unsigned)((Bs + cols_per_wg - 1) / cols_per_wg));
+            PC_DISPATCH_SUM(true, grid, dim3(256), 0, s, theta, const_cast<float *>(l), const_cast<float *>(R), N, nfmax,
+                            F, gs, Bs);
+        }
+        return;
+    }
+    // other block sizes: one launch per group
+    for (const GroupSet &gs : sets) for (int k = 0; k < gs.n; ++k) {
+        const GroupDev g{gs.first[k + 1] - gs.first[k], gs.width[k], gs.ids[k], gs.nbr[k], gs.par[k], false, gs.aux[k]};
+        Timed timed(KC_SUM_BWD_CHILD, s);
+        if (use_small(K)) {
+            dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 255) / 256));
+            PC_DISPATCH_SMALL(k_sum_bwd_small, grid, dim3(256), 0, s, theta, l, R, N, nfmax, F, g.ids, g.nbr, g.par, g.aux,
+                              g.width, Bs);
+        } else {
+            const int64_t items = (int64_t)g.n_rows * K * Bs;
+            hipLaunchKernelGGL(k_sum_bwd_child_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, l, R, N, F, g.ids, g.nbr,
+                               g.par, g.aux, g.n_rows, g.width, K, Bs);
+        }
     }
 }
 

@@ -142,6 +142,18 @@ def test_block_sparse_sum_layer(n_sets, M, K, keep, B):
     assert_device_tables_match_oracle(got["circuit"].handle, w)
 
 
+def test_layer_with_more_groups_than_one_launch_covers():
+    """Alg. 2 with G = 16 and tol = 0 gives one group per distinct child count; a launch covers eight groups."""
+    import dataclasses
+    w = dataclasses.replace(W.sum_layer(3, 512, 32, 70, W.SEED_BASE + 11, keep=0.5), max_groups=16, tol_permille=0)
+    print(f"case many groups {w.name}", flush=True)
+    got, _ = check_all(w)
+    h = got["circuit"].handle
+    assert_device_tables_match_oracle(h, w)
+    n_layers = pcb.pc_get_sizes(h).n_layers
+    assert max(pcb.pc_get_layer(h, li).n_fwd_groups for li in range(n_layers)) > 8
+
+
 @pytest.mark.parametrize("seed,K,B", [(s, K, B) for s in range(4) for K, B in ((32, 70), (4, 33))] +
                          [(7, 64, 40), (8, 128, 33), (9, 3, 20), (10, 16, 65), (11, 1, 64)])
 def test_random_dags_with_skip_connections_tying_and_unused_blocks(seed, K, B):
