@@ -794,7 +794,8 @@ __global__ __launch_bounds__(256) void k_param_flow_small(const float *__restric
 //     LDS tile only to reach the MFMA A-operand layout (LDS operations of one wave complete in order, so
 //     no barrier and no double buffer are needed), then read back whole into registers;
 //   * the KC x 32 neighbour values go straight from L2 into the MFMA B-operand layout;
-//   * loads of the wave's next chunk are issued before the arithmetic of the current one.
+//   * in the pipelined schedule (see the chunk loop) loads of the wave's next chunk are issued before the
+//     arithmetic of the current one; the plain schedule leaves that overlap to the other waves of the SIMD.
 //   forward : value = l (log-prob residual) + (R_child - R_sum); the chunk maximum is taken in registers
 //   backward: value = N (log F - l of the parent) + (R_child - R_parent); the block maximum is nfmax
 // Values are shifted by the running per-sample maximum, exponentiated in registers and multiplied on
@@ -866,11 +867,11 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
                 lown[rt][e] = l[((int64_t)(id + sub * TM) + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4)) * Bs + col];
     }
 
-    // Software pipeline over the wave's chunks.  One register set `th` carries a theta sub-block from global
-    // memory to the LDS tile; two sets (A, B) hold the MFMA A operands read back from the tile and the neighbour
-    // values / block scalars of two consecutive chunks.  In the middle of the arithmetic of chunk c the tile is
+    // Registers of the chunk loop.  One set `th` carries a theta sub-block from global memory to the LDS tile; a set
+    // (A) holds the MFMA A operands read back from the tile and the neighbour values / block scalars of a chunk.
+    // The pipelined schedule has a second set (B): in the middle of the arithmetic of chunk c the tile is
     // overwritten with the theta of chunk c+1 and read back into the other operand set, so neither the LDS round
-    // trip nor a global load is ever waited for at a chunk boundary.
+    // trip nor a global load is waited for at a chunk boundary.
     floatx4 th[NF4];
     float arA[NQ][RT], arB[NQ][RT];
     float vA[NQ], vB[NQ];
@@ -981,41 +982,60 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
     } while (0)
 
     float sh2 = 0.0f;
-    if (sp < n_chunks) {
-        PC_ISSUE_TH(sp);
-        PC_ISSUE_V(sp, vA, rbA, bmA);
-        PC_COMMIT();
-        if (sp + SPLIT < n_chunks) { PC_ISSUE_TH(sp + SPLIT); PC_ISSUE_V(sp + SPLIT, vB, rbB, bmB); }
-        PC_READ_A(arA);
-    }
-    // pairs of chunks (c on set A, c + SPLIT on set B); a last single chunk follows the loop, so the loop has one
-    // exit and the accumulators stay in place
-    int c = sp;
-    for (; c + SPLIT < n_chunks; c += 2 * SPLIT) {
-        const bool more1 = c + 2 * SPLIT < n_chunks, more2 = c + 3 * SPLIT < n_chunks;
-        // chunk c on set A; chunk c + SPLIT is staged into set B meanwhile
-        PC_PRE(vA, rbA, bmA);
-        PC_MATH(arA, vA, 0);
-        PC_COMMIT();
-        if (more1) PC_ISSUE_TH(c + 2 * SPLIT);
-        PC_READ_A(arB);
-        PC_MATH(arA, vA, NQ / 2);
-        if (more1) PC_ISSUE_V(c + 2 * SPLIT, vA, rbA, bmA);
-        // chunk c + SPLIT on set B; chunk c + 2 SPLIT is staged into set A meanwhile
-        PC_PRE(vB, rbB, bmB);
-        PC_MATH(arB, vB, 0);
-        if (more1) {
+    // Two schedules of the chunk loop.  The plain one (load, stage, multiply, chunk after chunk) keeps one operand
+    // set, needs 75-150 registers and leaves 3-6 waves per SIMD to hide its waits; it is the faster one wherever a
+    // launch has waves to fill those slots, and also for the forward kernel at two waves per SIMD.  The software
+    // pipeline (two operand sets, 190-230 registers, two waves per SIMD) wins only for the backward kernel on
+    // launches of a few large tiles (SPLIT = 4: the reduction had to be split to fill the chip), where no third
+    // wave exists and the 32 four-byte LDS reads per chunk of the transposed operand would be waited for in full.
+    constexpr bool PIPELINED = BWD && RT == 2 && SPLIT == 4;
+    if (!PIPELINED) {
+        for (int c = sp; c < n_chunks; c += SPLIT) {
+            PC_ISSUE_TH(c);
+            PC_ISSUE_V(c, vA, rbA, bmA);
             PC_COMMIT();
-            if (more2) PC_ISSUE_TH(c + 3 * SPLIT);
+            PC_READ_A(arA);
+            PC_PRE(vA, rbA, bmA);
+            PC_MATH(arA, vA, 0);
+            PC_MATH(arA, vA, NQ / 2);
+        }
+    } else {
+        if (sp < n_chunks) {
+            PC_ISSUE_TH(sp);
+            PC_ISSUE_V(sp, vA, rbA, bmA);
+            PC_COMMIT();
+            if (sp + SPLIT < n_chunks) { PC_ISSUE_TH(sp + SPLIT); PC_ISSUE_V(sp + SPLIT, vB, rbB, bmB); }
             PC_READ_A(arA);
         }
-        PC_MATH(arB, vB, NQ / 2);
-        if (more2) PC_ISSUE_V(c + 3 * SPLIT, vB, rbB, bmB);
-    }
-    if (c < n_chunks) {                                                 // a last chunk, staged in set A
-        PC_PRE(vA, rbA, bmA);
-        PC_MATH(arA, vA, 0);
-        PC_MATH(arA, vA, NQ / 2);
+        // pairs of chunks (c on set A, c + SPLIT on set B); a last single chunk follows the loop, so the loop has one
+        // exit and the accumulators stay in place
+        int c = sp;
+        for (; c + SPLIT < n_chunks; c += 2 * SPLIT) {
+            const bool more1 = c + 2 * SPLIT < n_chunks, more2 = c + 3 * SPLIT < n_chunks;
+            // chunk c on set A; chunk c + SPLIT is staged into set B meanwhile
+            PC_PRE(vA, rbA, bmA);
+            PC_MATH(arA, vA, 0);
+            PC_COMMIT();
+            if (more1) PC_ISSUE_TH(c + 2 * SPLIT);
+            PC_READ_A(arB);
+            PC_MATH(arA, vA, NQ / 2);
+            if (more1) PC_ISSUE_V(c + 2 * SPLIT, vA, rbA, bmA);
+            // chunk c + SPLIT on set B; chunk c + 2 SPLIT is staged into set A meanwhile
+            PC_PRE(vB, rbB, bmB);
+            PC_MATH(arB, vB, 0);
+            if (more1) {
+                PC_COMMIT();
+                if (more2) PC_ISSUE_TH(c + 3 * SPLIT);
+                PC_READ_A(arA);
+            }
+            PC_MATH(arB, vB, NQ / 2);
+            if (more2) PC_ISSUE_V(c + 3 * SPLIT, vB, rbB, bmB);
+        }
+        if (c < n_chunks) {                                                 // a last chunk, staged in set A
+            PC_PRE(vA, rbA, bmA);
+            PC_MATH(arA, vA, 0);
+            PC_MATH(arA, vA, NQ / 2);
+        }
     }
 #undef PC_ISSUE_TH
 #undef PC_ISSUE_V
