@@ -607,36 +607,54 @@ __global__ __launch_bounds__(256) void k_sum_fwd_small(const float *__restrict__
 #pragma unroll
     for (int i = 0; i < K; ++i) acc[i] = 0.0f;
     float m = PC_NEG_INF, Rrow = PC_NEG_INF;                            // Rrow: largest child reference seen so far
-    for (int j = 0; j < cnt; ++j) {
-        const int32_t ns = row_nbr[j];
-        const float *th = theta + row_par[j];
-        float v[K];
+    // U neighbours at a time: their ids first, then all their loads together -- one memory round trip per U
+    // neighbours (with one thread per sample column nothing else hides that latency at the smallest block sizes)
+    constexpr int U = K == 1 ? 8 : K == 2 ? 4 : K == 4 ? 2 : 1;
+    for (int j0 = 0; j0 < cnt; j0 += U) {
+        int32_t nsv[U], pov[U];
 #pragma unroll
-        for (int jj = 0; jj < K; ++jj) v[jj] = l[(int64_t)(ns + jj) * Bs + b];
-        const float RB = R[(int64_t)(ns / K) * Bs + b];
-        const float Rn = fmaxf(Rrow, RB);
-        m += Rrow - Rn;                                                 // exact integer shift; -inf stays -inf
-        Rrow = Rn;
-        const float d = RB - Rrow;
-        float bm = v[0];
-#pragma unroll
-        for (int jj = 1; jj < K; ++jj) bm = fmaxf(bm, v[jj]);
-        bm += d;
-        if (bm > m + PC_LAZY) {
-            const float sc = pc_half_scale(m - bm);                     // m = -inf: the accumulators are 0
-#pragma unroll
-            for (int i = 0; i < K; ++i) acc[i] = acc[i] * sc * sc;
-            m = bm;
+        for (int u = 0; u < U; ++u) {
+            const int jc = j0 + u < cnt ? j0 + u : cnt - 1;             // past the end: the last neighbour again, unused
+            nsv[u] = row_nbr[jc];
+            pov[u] = row_par[jc];
         }
-        const float sh = m > PC_NEG_INF ? d - m + PC_UP : 0.0f;         // dead column: v = -inf -> p = 0
-        float pv[K];
+        float vv[U][K], RBv[U];
 #pragma unroll
-        for (int jj = 0; jj < K; ++jj) pv[jj] = __expf(v[jj] + sh);
+        for (int u = 0; u < U; ++u) {
 #pragma unroll
-        for (int i = 0; i < K; ++i) {
+            for (int jj = 0; jj < K; ++jj) vv[u][jj] = l[(int64_t)(nsv[u] + jj) * Bs + b];
+            RBv[u] = R[(int64_t)(nsv[u] / K) * Bs + b];
+        }
 #pragma unroll
-            for (int jj = 0; jj < K; ++jj) acc[i] = fmaf(th[i * K + jj], pv[jj], acc[i]);
-            if (K == 16 && i % 4 == 3) __builtin_amdgcn_sched_barrier(0);   // keeps the 256 weights from all being live in scalar registers
+        for (int u = 0; u < U; ++u) {
+            if (j0 + u >= cnt) break;                                   // uniform over the workgroup
+            const float *th = theta + pov[u];
+            const float(&v)[K] = vv[u];
+            const float RB = RBv[u];
+            const float Rn = fmaxf(Rrow, RB);
+            m += Rrow - Rn;                                             // exact integer shift; -inf stays -inf
+            Rrow = Rn;
+            const float d = RB - Rrow;
+            float bm = v[0];
+#pragma unroll
+            for (int jj = 1; jj < K; ++jj) bm = fmaxf(bm, v[jj]);
+            bm += d;
+            if (bm > m + PC_LAZY) {
+                const float sc = pc_half_scale(m - bm);                 // m = -inf: the accumulators are 0
+#pragma unroll
+                for (int i = 0; i < K; ++i) acc[i] = acc[i] * sc * sc;
+                m = bm;
+            }
+            const float sh = m > PC_NEG_INF ? d - m + PC_UP : 0.0f;     // dead column: v = -inf -> p = 0
+            float pv[K];
+#pragma unroll
+            for (int jj = 0; jj < K; ++jj) pv[jj] = __expf(v[jj] + sh);
+#pragma unroll
+            for (int i = 0; i < K; ++i) {
+#pragma unroll
+                for (int jj = 0; jj < K; ++jj) acc[i] = fmaf(th[i * K + jj], pv[jj], acc[i]);
+                if (K == 16 && i % 4 == 3) __builtin_amdgcn_sched_barrier(0);   // keeps the 256 weights from all being live in scalar registers
+            }
         }
     }
 #pragma unroll
@@ -667,28 +685,45 @@ __global__ __launch_bounds__(256) void k_sum_bwd_small(const float *__restrict__
 #pragma unroll
     for (int jj = 0; jj < K; ++jj) acc[jj] = 0.0f;
     float m = PC_NEG_INF;
-    for (int j = 0; j < cnt; ++j) {
-        const int32_t ms = row_nbr[j];
-        const float *th = theta + row_par[j];
-        float nv[K];
+    constexpr int U = K == 1 ? 8 : K == 2 ? 4 : K == 4 ? 2 : 1;         // neighbours in flight, as in the forward kernel
+    for (int j0 = 0; j0 < cnt; j0 += U) {
+        int32_t msv[U], pov[U];
 #pragma unroll
-        for (int i = 0; i < K; ++i) nv[i] = N[(int64_t)(ms + i) * Bs + b];
-        const float d = Rc - R[(int64_t)(ms / K) * Bs + b];
-        const float bm = nfmax[(int64_t)(ms / K) * Bs + b] + d;
-        if (bm > m + PC_LAZY) {
-            const float sc = pc_half_scale(m - bm);
-#pragma unroll
-            for (int jj = 0; jj < K; ++jj) acc[jj] = acc[jj] * sc * sc;
-            m = bm;
+        for (int u = 0; u < U; ++u) {
+            const int jc = j0 + u < cnt ? j0 + u : cnt - 1;
+            msv[u] = row_nbr[jc];
+            pov[u] = row_par[jc];
         }
-        const float sh = m > PC_NEG_INF ? d - m + PC_UP : 0.0f;
-        float pv[K];
+        float nvv[U][K], Rp[U], bmv[U];
 #pragma unroll
-        for (int i = 0; i < K; ++i) pv[i] = __expf(nv[i] + sh);
+        for (int u = 0; u < U; ++u) {
 #pragma unroll
-        for (int i = 0; i < K; ++i)
+            for (int i = 0; i < K; ++i) nvv[u][i] = N[(int64_t)(msv[u] + i) * Bs + b];
+            Rp[u] = R[(int64_t)(msv[u] / K) * Bs + b];
+            bmv[u] = nfmax[(int64_t)(msv[u] / K) * Bs + b];
+        }
 #pragma unroll
-            for (int jj = 0; jj < K; ++jj) acc[jj] = fmaf(th[i * K + jj], pv[i], acc[jj]);
+        for (int u = 0; u < U; ++u) {
+            if (j0 + u >= cnt) break;                                   // uniform over the workgroup
+            const float *th = theta + pov[u];
+            const float(&nv)[K] = nvv[u];
+            const float d = Rc - Rp[u];
+            const float bm = bmv[u] + d;
+            if (bm > m + PC_LAZY) {
+                const float sc = pc_half_scale(m - bm);
+#pragma unroll
+                for (int jj = 0; jj < K; ++jj) acc[jj] = acc[jj] * sc * sc;
+                m = bm;
+            }
+            const float sh = m > PC_NEG_INF ? d - m + PC_UP : 0.0f;
+            float pv[K];
+#pragma unroll
+            for (int i = 0; i < K; ++i) pv[i] = __expf(nv[i] + sh);
+#pragma unroll
+            for (int i = 0; i < K; ++i)
+#pragma unroll
+                for (int jj = 0; jj < K; ++jj) acc[jj] = fmaf(th[i * K + jj], pv[i], acc[jj]);
+        }
     }
 #pragma unroll
     for (int jj = 0; jj < K; ++jj) {
