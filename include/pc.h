@@ -8,8 +8,9 @@
  *     (PC_ERR_ARG otherwise).  The handle (pc_circuit) owns only its compiled int32 tables and a few
  *     KB of reduction scratch.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Forward, backward
- *     and the EM step only enqueue work; they never synchronise the device.  A kernel fault
- *     surfaces as PC_ERR_HIP from the next call that checks the runtime's error state.
+ *     and the EM step only enqueue kernels (no memset or copy nodes, no allocation); they never
+ *     synchronise the device, so a caller may capture them into a HIP graph and replay it.  A kernel
+ *     fault surfaces as PC_ERR_HIP from the next call that checks the runtime's error state.
  *   - Every call returns a pc_status; pc_last_error() gives a thread-local message for the last
  *     non-OK status.  No exceptions cross this boundary.
  *   - Node blocks hold K node slots.  The compiled node offset of user block u is (u+1)*K; rows

@@ -300,6 +300,37 @@ def test_em_on_tied_hmm_matches_oracle_and_improves_likelihood():
     assert ll1 >= ll0
 
 
+def test_forward_and_backward_replayed_from_a_captured_graph():
+    """pc_forward / pc_backward only enqueue kernels, so a caller may capture them into a HIP graph.  The graph is
+    replayed several times with eager work and synchronisations in between; every replay must reproduce the eager
+    result (log-likelihoods and parameter flows bit for bit: no atomics on those paths)."""
+    w = W.reduced(2)
+    c = pcb.Circuit(w)
+    c.set_batch(w.x)
+    c.forward(); c.backward()
+    torch.cuda.synchronize()
+    ref_ll, ref_tf, ref_gf = c.ll.clone(), c.theta_flow.clone(), c.table_flow.clone()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        c.forward(); c.backward()                              # warm-up on the capture stream
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            c.forward(); c.backward()
+    torch.cuda.synchronize()
+    for replay in range(4):
+        c.theta_flow.zero_(); c.table_flow.zero_(); c.ll.fill_(float("nan"))     # eager work between the replays
+        c._ws.fill_(255)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(c.ll, ref_ll), f"replay {replay}"
+        assert torch.equal(c.theta_flow, ref_tf), f"replay {replay}"
+        assert torch.allclose(c.table_flow, ref_gf, rtol=1e-5, atol=1e-7), f"replay {replay}"
+    del graph
+    c.close()
+
+
 def test_forward_is_deterministic_and_state_errors():
     w = W.reduced(5)
     c = pcb.Circuit(w)
