@@ -338,6 +338,8 @@ pc_status pc_em_step(pc_circuit *c, float *theta, float *tables, float *theta_fl
     if (!c || !theta || !tables || !theta_flow || !table_flow) return fail(PC_ERR_ARG, "NULL argument");
     if (!c->on_device) return fail(PC_ERR_STATE, "circuit was compiled without a device");
     if (!(step >= 0.0f && step <= 1.0f) || !(pseudocount >= 0.0f)) return fail(PC_ERR_ARG, "step in [0,1], pseudocount >= 0");
+    if (misaligned(theta) || misaligned(tables) || misaligned(theta_flow) || misaligned(table_flow))
+        return fail(PC_ERR_ARG, "theta, tables and their flow arrays must be 16-byte aligned");
     ProfScope prof(c);
     EmDev em{c->n_em_groups, c->d_pb_group, c->d_pb_rows, c->d_pb_cols, c->d_group_nch, c->d_zrow, c->d_ztab};
     launch_em(theta, tables, theta_flow, table_flow, em, c->K, c->n_param_blocks, c->n_tables, c->n_cats, step,

@@ -1568,6 +1568,63 @@ __global__ __launch_bounds__(256) void k_em_theta(float *__restrict__ theta, flo
     for (int t = threadIdx.x; t < K * K; t += 256) G[base + t] = 0.0f;
 }
 
+// Row sums and update for K a power of two >= 4: a thread owns four consecutive columns of one row (16-byte
+// accesses); the K / 4 lanes of a row are neighbours in a wave, so a row sum is a few shuffles.
+__global__ __launch_bounds__(256) void k_em_rowsum_v4(const float *__restrict__ G, const int32_t *__restrict__ pb_group,
+                                                      const int32_t *__restrict__ pb_rows, const int32_t *__restrict__ pb_cols,
+                                                      int32_t K, float *__restrict__ zrow)
+{
+    const int pb = blockIdx.x + 1;
+    const int g = pb_group[pb];
+    if (g < 0) return;
+    const int rows = pb_rows[pb], cols = pb_cols[pb];
+    const int k4n = K / 4;
+    const float4 *src = reinterpret_cast<const float4 *>(G + (int64_t)pb * K * K);
+    for (int q0 = 0; q0 < K * k4n; q0 += 256) {                         // uniform trip count: shuffles see whole waves
+        const int q = q0 + threadIdx.x;
+        const int i = q / k4n, kq = q - i * k4n;
+        float sum = 0.0f;
+        if (i < rows) {
+            const float4 v = src[q];
+            const int j0 = kq * 4;
+            sum = (j0 < cols ? v.x : 0.0f) + (j0 + 1 < cols ? v.y : 0.0f) + (j0 + 2 < cols ? v.z : 0.0f) +
+                  (j0 + 3 < cols ? v.w : 0.0f);
+        }
+        for (int o = k4n >> 1; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+        if (kq == 0 && i < rows) atomicAdd(zrow + (int64_t)g * K + i, sum);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_em_theta_v4(float *__restrict__ theta, float *__restrict__ G,
+                                                     const int32_t *__restrict__ pb_group, const int32_t *__restrict__ pb_rows,
+                                                     const int32_t *__restrict__ pb_cols, const int32_t *__restrict__ group_nch,
+                                                     const float *__restrict__ zrow, int32_t K, float step, float pc)
+{
+    const int pb = blockIdx.x + 1;
+    const int g = pb_group[pb];
+    const int k4n = K / 4;
+    float4 *th4 = reinterpret_cast<float4 *>(theta + (int64_t)pb * K * K);
+    float4 *g4 = reinterpret_cast<float4 *>(G + (int64_t)pb * K * K);
+    const int rows = g >= 0 ? pb_rows[pb] : 0, cols = g >= 0 ? pb_cols[pb] : 0;
+    const float share = g >= 0 ? pc / (float)group_nch[g] : 0.0f;
+    for (int q = threadIdx.x; q < K * k4n; q += 256) {
+        const int i = q / k4n, j0 = (q - i * k4n) * 4;
+        if (i < rows && j0 < cols) {
+            const float z = zrow[(int64_t)g * K + i] + pc;
+            if (z > 0.0f) {
+                const float4 fl = g4[q];
+                float4 w = th4[q];
+                w.x = (1.0f - step) * w.x + step * ((fl.x + share) / z);
+                if (j0 + 1 < cols) w.y = (1.0f - step) * w.y + step * ((fl.y + share) / z);
+                if (j0 + 2 < cols) w.z = (1.0f - step) * w.z + step * ((fl.z + share) / z);
+                if (j0 + 3 < cols) w.w = (1.0f - step) * w.w + step * ((fl.w + share) / z);
+                th4[q] = w;
+            }
+        }
+        g4[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+
 // ztab[t*K + k] += sum over a slab of categories of table_flow[t][c][k]
 __global__ __launch_bounds__(256) void k_em_tabsum(const float *__restrict__ Gt, int32_t K, int32_t n_cats,
                                                    int32_t cats_per_block, float *__restrict__ ztab)
@@ -1579,6 +1636,41 @@ __global__ __launch_bounds__(256) void k_em_tabsum(const float *__restrict__ Gt,
         float s = 0.0f;
         for (int c = c0; c < c1; ++c) s += Gt[((int64_t)t * n_cats + c) * K + k];
         atomicAdd(ztab + (int64_t)t * K + k, s);
+    }
+}
+
+// The same for K a multiple of 4 (K <= 128): a thread owns four consecutive nodes, the 256 threads cover
+// 1024 / K categories per pass with 16-byte loads (four in flight per thread), partial sums meet in LDS.
+__global__ __launch_bounds__(256) void k_em_tabsum_v4(const float *__restrict__ Gt, int32_t K, int32_t n_cats,
+                                                      int32_t cats_per_block, float *__restrict__ ztab)
+{
+    __shared__ float4 red[256];
+    const int t = blockIdx.x;
+    const int c0 = blockIdx.y * cats_per_block;
+    const int c1 = min(n_cats, c0 + cats_per_block);
+    const int k4n = K / 4, kq = threadIdx.x % k4n, rs = threadIdx.x / k4n, R = 256 / k4n;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (rs < R) {
+        const float4 *src = reinterpret_cast<const float4 *>(Gt + (int64_t)t * n_cats * K) + kq;
+        for (int c = c0 + rs; c < c1; c += 4 * R) {
+            float4 v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                v[j] = c + j * R < c1 ? src[(int64_t)(c + j * R) * k4n] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { acc.x += v[j].x; acc.y += v[j].y; acc.z += v[j].z; acc.w += v[j].w; }
+        }
+    }
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x < k4n) {
+        float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int r2 = 0; r2 < R; ++r2) {
+            const float4 v = red[r2 * k4n + threadIdx.x];
+            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+        }
+        float *dst = ztab + (int64_t)t * K + threadIdx.x * 4;
+        atomicAdd(dst + 0, sum.x); atomicAdd(dst + 1, sum.y); atomicAdd(dst + 2, sum.z); atomicAdd(dst + 3, sum.w);
     }
 }
 
@@ -1597,6 +1689,33 @@ __global__ __launch_bounds__(256) void k_em_tables(float *__restrict__ tables, f
             tables[i] = (1.0f - step) * tables[i] + step * nw;
         }
         Gt[i] = 0.0f;
+    }
+}
+
+// The same for K a multiple of 4: one table per blockIdx.x, a thread owns four consecutive nodes of one category
+// (16-byte accesses, 32-bit index arithmetic, the column sums of the table read once per thread).
+__global__ __launch_bounds__(256) void k_em_tables_v4(float *__restrict__ tables, float *__restrict__ Gt,
+                                                      const float *__restrict__ ztab, int32_t K, int32_t n_cats,
+                                                      float step, float pc)
+{
+    const float share = pc / (float)n_cats;
+    const int t = blockIdx.x;
+    const int k4n = K / 4, kq = threadIdx.x % k4n, rs = threadIdx.x / k4n, R = 256 / k4n;
+    if (rs >= R) return;
+    const float4 zr = *reinterpret_cast<const float4 *>(ztab + (int64_t)t * K + kq * 4);
+    const float4 z = make_float4(zr.x + pc, zr.y + pc, zr.z + pc, zr.w + pc);
+    float4 *tb = reinterpret_cast<float4 *>(tables + (int64_t)t * n_cats * K) + kq;
+    float4 *gb = reinterpret_cast<float4 *>(Gt + (int64_t)t * n_cats * K) + kq;
+    for (int c = blockIdx.y * R + rs; c < n_cats; c += gridDim.y * R) {
+        const int64_t at = (int64_t)c * k4n;
+        const float4 g = gb[at];
+        float4 w = tb[at];
+        if (z.x > 0.0f) w.x = (1.0f - step) * w.x + step * ((g.x + share) / z.x);
+        if (z.y > 0.0f) w.y = (1.0f - step) * w.y + step * ((g.y + share) / z.y);
+        if (z.z > 0.0f) w.z = (1.0f - step) * w.z + step * ((g.z + share) / z.z);
+        if (z.w > 0.0f) w.w = (1.0f - step) * w.w + step * ((g.w + share) / z.w);
+        tb[at] = w;
+        gb[at] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
 }
 
@@ -1951,18 +2070,38 @@ void launch_em(float *theta, float *tables, float *theta_flow, float *table_flow
     launch_fill(em.zrow, (int64_t)em.n_groups * K, 0.0f, s);
     launch_fill(em.ztab, (int64_t)n_tables * K, 0.0f, s);
     Timed timed(KC_EM, s);
-    if (n_param_blocks > 0) {
+    if (n_param_blocks > 0 && K >= 4 && (K & (K - 1)) == 0) {          // 16-byte accesses
+        hipLaunchKernelGGL(k_em_rowsum_v4, dim3(n_param_blocks), dim3(256), 0, s, theta_flow, em.pb_group, em.pb_rows,
+                           em.pb_cols, K, em.zrow);
+        hipLaunchKernelGGL(k_em_theta_v4, dim3(n_param_blocks), dim3(256), 0, s, theta, theta_flow, em.pb_group, em.pb_rows,
+                           em.pb_cols, em.group_nch, em.zrow, K, step, pc);
+    } else if (n_param_blocks > 0) {
         hipLaunchKernelGGL(k_em_rowsum, dim3(n_param_blocks), dim3(256), 0, s, theta_flow, em.pb_group, em.pb_rows,
                            em.pb_cols, K, em.zrow);
         hipLaunchKernelGGL(k_em_theta, dim3(n_param_blocks), dim3(256), 0, s, theta, theta_flow, em.pb_group, em.pb_rows,
                            em.pb_cols, em.group_nch, em.zrow, K, step, pc);
     }
-    const int cats_per_block = 64;
-    dim3 grid((unsigned)n_tables, (unsigned)((n_cats + cats_per_block - 1) / cats_per_block));
-    hipLaunchKernelGGL(k_em_tabsum, grid, dim3(256), 0, s, table_flow, K, n_cats, cats_per_block, em.ztab);
-    const int64_t total = (int64_t)n_tables * n_cats * K;
-    hipLaunchKernelGGL(k_em_tables, dim3(grid_for(total)), dim3(256), 0, s, tables, table_flow, em.ztab, K, n_cats, total,
-                       step, pc);
+    if ((K & 3) == 0) {                                                // 16-byte accesses
+        const int rows_per_pass = 256 / (K / 4);
+        // about 2048 workgroups when the tables are few, at least four loads per thread
+        const int64_t max_slabs = std::max<int64_t>(1, n_cats / (4 * rows_per_pass));
+        const int64_t slabs = std::min<int64_t>(max_slabs, std::max<int64_t>(1, 2048 / n_tables));
+        const int cats_per_block = (int)((n_cats + slabs - 1) / slabs);
+        dim3 grid((unsigned)n_tables, (unsigned)((n_cats + cats_per_block - 1) / cats_per_block));
+        hipLaunchKernelGGL(k_em_tabsum_v4, grid, dim3(256), 0, s, table_flow, K, n_cats, cats_per_block, em.ztab);
+        // enough workgroups per table to fill the chip when there are few tables, one pass otherwise
+        const int per_table = (int)std::min<int64_t>((n_cats + rows_per_pass - 1) / rows_per_pass,
+                                                     std::max<int64_t>(1, 4096 / n_tables));
+        hipLaunchKernelGGL(k_em_tables_v4, dim3((unsigned)n_tables, (unsigned)per_table), dim3(256), 0, s, tables, table_flow,
+                           em.ztab, K, n_cats, step, pc);
+    } else {
+        const int cats_per_block = 64;
+        dim3 grid((unsigned)n_tables, (unsigned)((n_cats + cats_per_block - 1) / cats_per_block));
+        hipLaunchKernelGGL(k_em_tabsum, grid, dim3(256), 0, s, table_flow, K, n_cats, cats_per_block, em.ztab);
+        const int64_t total = (int64_t)n_tables * n_cats * K;
+        hipLaunchKernelGGL(k_em_tables, dim3(grid_for(total)), dim3(256), 0, s, tables, table_flow, em.ztab, K, n_cats, total,
+                           step, pc);
+    }
 }
 
 }  // namespace pc
