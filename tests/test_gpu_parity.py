@@ -283,6 +283,32 @@ def test_flows_accumulate_over_calls_and_em_step_matches_oracle():
         c.set_batch(w.x); c.forward(); c.backward()
 
 
+@pytest.mark.parametrize("K", [1, 3, 4, 8, 12, 16, 64, 128])
+def test_em_step_at_every_block_size(K):
+    """The EM kernels have 16-byte forms (K a multiple of 4 for the tables, a power of two for the parameters) and plain
+    ones; random DAGs have sum blocks with fewer than K real nodes, tied parameter blocks and unused blocks."""
+    w = W.random_circuit(5, 4, 4, K, 40, 700 + K, tie_prob=0.4)
+    print(f"case em {w.name}", flush=True)
+    c = pcb.Circuit(w)
+    c.set_batch(w.x)
+    for step, pc in ((1.0, 0.0), (0.4, 0.05)):
+        c.forward(); c.backward()
+        torch.cuda.synchronize()
+        th0 = c.theta.cpu().numpy().reshape(w.theta.shape).copy()
+        tb0 = c.tables.cpu().numpy().reshape(w.tables.shape).copy()
+        tf = c.theta_flow.double().cpu().numpy().reshape(w.theta.shape)
+        gf = c.table_flow.double().cpu().numpy().reshape(w.tables.shape)
+        ref_th, ref_tb = orc.em_step(w, th0, tb0, tf, gf, step=step, pseudocount=pc)
+        c.em_step(step, pc)
+        torch.cuda.synchronize()
+        th = c.theta.cpu().numpy().reshape(w.theta.shape)
+        tb = c.tables.cpu().numpy().reshape(w.tables.shape)
+        assert np.allclose(th, ref_th, rtol=1e-4, atol=1e-9), f"theta, step {step}"
+        assert np.allclose(tb, ref_tb, rtol=1e-4, atol=1e-9), f"tables, step {step}"
+        assert float(c.theta_flow.abs().max()) == 0.0 and float(c.table_flow.abs().max()) == 0.0
+    c.close()
+
+
 def test_em_on_tied_hmm_matches_oracle_and_improves_likelihood():
     w = W.reduced(4, B=96)
     c = pcb.Circuit(w)
