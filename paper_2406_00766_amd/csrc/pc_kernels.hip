@@ -19,6 +19,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -1845,13 +1846,17 @@ void launch_input_bwd(const float *F, const int32_t *xT, const GroupDev &g, int3
     while (lps < K && lps < 64) lps <<= 1;
     const size_t tile_bytes = ((size_t)K * 65 + 64) * 4;
     const size_t hist_bytes = (size_t)n_cats * K * 4 + tile_bytes;
-    static bool attr_set = false;
-    if (!attr_set) {
+    // more than 64 KB of dynamic LDS has to be allowed per kernel, once on every device the library runs on
+    static std::atomic<uint64_t> attr_set{0};
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    const uint64_t bit = 1ull << (dev & 63);
+    if (!(attr_set.load(std::memory_order_relaxed) & bit)) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k_input_bwd_hist), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   96 * 1024);
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k_input_bwd_sorted), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   96 * 1024);
-        attr_set = true;
+        attr_set.fetch_or(bit, std::memory_order_relaxed);
     }
     // slab of samples for the sorted variant: the [K x SB] tile has to fit in LDS twice per CU
     int SB = 1024;
