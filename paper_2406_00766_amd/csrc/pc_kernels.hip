@@ -938,12 +938,17 @@ __global__ __launch_bounds__(256) void k_param_flow_small(const float *__restric
 // round-robin (split of the reduction dimension, so that small batches still fill every SIMD with two
 // waves -- a wave cannot overlap its own VALU work with its own MFMAs, a second wave can), the other
 // factor 4/SPLIT spans adjacent column tiles.  Per chunk and wave:
-//   * the theta sub-block [TM x KC] is fetched with coalesced 16-byte loads and staged in a wave-private
-//     LDS tile only to reach the MFMA A-operand layout (LDS operations of one wave complete in order, so
-//     no barrier and no double buffer are needed), then read back whole into registers;
+//   * forward: the theta sub-block [TM x KC] (row = sum node, contiguous along the children) is fetched with
+//     coalesced 16-byte loads and staged in a wave-private LDS tile only to reach the MFMA A-operand layout (LDS
+//     operations of one wave complete in order, so no barrier and no double buffer are needed), then read back
+//     whole into registers with 16-byte reads;
+//   * backward: the operand is the transpose -- lane i needs theta[parent][child i] -- and that IS coalesced in
+//     memory (32 consecutive children of one parent row), so it goes straight from L2 into the A-operand layout;
 //   * the KC x 32 neighbour values go straight from L2 into the MFMA B-operand layout;
-//   * in the pipelined schedule (see the chunk loop) loads of the wave's next chunk are issued before the
-//     arithmetic of the current one; the plain schedule leaves that overlap to the other waves of the SIMD.
+//   * the chunks follow one another without software pipelining: the loop needs 75-150 registers, so 3-6 waves
+//     share a SIMD and hide each other's waits.  (A pipelined version -- two operand sets, theta of chunk c+1
+//     staged during the arithmetic of chunk c, 190-230 registers, two waves per SIMD -- was slower in every
+//     configuration measured, and so was prefetching only the next theta sub-block.)
 //   forward : value = l (log-prob residual) + (R_child - R_sum); the chunk maximum is taken in registers
 //   backward: value = N (log F - l of the parent) + (R_child - R_parent); the block maximum is nfmax
 // Values are shifted by the running per-sample maximum, exponentiated in registers and multiplied on
@@ -969,9 +974,9 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
     constexpr int NQ = KC / 2;                                          // MFMA steps per chunk
     constexpr int CPB = K / KC;                                         // chunks per neighbour block
     constexpr int NCT = 4 / SPLIT;                                      // column tiles per workgroup
-    constexpr int NF4 = TM * KC / 4 / 64;                               // 16-byte loads per lane per chunk
-    constexpr int LDA = BWD ? TM : KC + 4;                              // LDS row stride (floats); KC+4: b128 reads conflict-free
-    constexpr int TILE = (BWD ? KC : TM) * LDA;
+    constexpr int NF4 = TM * KC / 4 / 64;                               // forward: 16-byte loads per lane per chunk
+    constexpr int LDA = KC + 4;                                         // LDS row stride (floats): b128 reads conflict-free
+    constexpr int TILE = BWD ? 0 : TM * LDA;                            // the backward kernel stages nothing
     constexpr int XCH = RT * 16 * 64 + 128;                             // one partial accumulator, its maxima and references
     constexpr int WSZ = TILE > XCH ? TILE : XCH;
     static_assert(K % TM == 0 && (SPLIT == 1 || SPLIT == 2 || SPLIT == 4), "tile shape");
@@ -1015,182 +1020,109 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
                 lown[rt][e] = l[((int64_t)(id + sub * TM) + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4)) * Bs + col];
     }
 
-    // Registers of the chunk loop.  One set `th` carries a theta sub-block from global memory to the LDS tile; a set
-    // (A) holds the MFMA A operands read back from the tile and the neighbour values / block scalars of a chunk.
-    // The pipelined schedule has a second set (B): in the middle of the arithmetic of chunk c the tile is
-    // overwritten with the theta of chunk c+1 and read back into the other operand set, so neither the LDS round
-    // trip nor a global load is waited for at a chunk boundary.
-    floatx4 th[NF4];
-    float arA[NQ][RT], arB[NQ][RT];
-    float vA[NQ], vB[NQ];
-    float rbA = 0.0f, rbB = 0.0f, bmA = PC_NEG_INF, bmB = PC_NEG_INF;
+    // Operands of one chunk: `ar` the MFMA A operands (theta), `v` the neighbour values with their block scalars;
+    // forward only: `th` carries the theta sub-block from global memory to the LDS tile.
+    // All loads of the loop are buffer loads: a wave-uniform descriptor per chunk (base = first row of the chunk), a
+    // loop-invariant per-lane byte offset and a compile-time scalar offset, so they need no vector address
+    // arithmetic (the vector ALU issues instead of the matrix cores, not beside them).
+    floatx4 th[BWD ? 1 : NF4];
+    float ar[NQ][RT], v[NQ];
+    float rb = 0.0f, bm = PC_NEG_INF;
     const float *vsrc = BWD ? N : l;
-    // per-lane parts of the load addresses (32-bit offsets from wave-uniform bases, so the loads take a scalar
-    // base and need no vector address arithmetic): neighbour-value rows 0-3 of a group of 8, theta sub-block
-    // The loads of the main loop are buffer loads: a wave-uniform descriptor per chunk (base = first row of the
-    // chunk), a loop-invariant per-lane byte offset and a loop-invariant scalar row offset, so they need no
-    // vector address arithmetic (the vector ALU issues instead of the matrix cores, not beside them).
-    int voff[4];                                                        // rows 0-3 of a group of 8 rows
+    int voff[4];                                                        // neighbour values: rows 0-3 of a group of 8 rows
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) voff[rr] = (int)(((int64_t)(4 * half + rr) * Bs + col) * 4);
     int soff[NQ / 4];                                                   // groups of 8 rows
 #pragma unroll
     for (int g = 0; g < NQ / 4; ++g) soff[g] = __builtin_amdgcn_readfirstlane((int)((int64_t)(8 * g) * Bs * 4));
-    const int toff = BWD ? ((lane / (TM / 4)) * K + (lane % (TM / 4)) * 4) * 4
-                         : ((lane / (KC / 4)) * K + (lane % (KC / 4)) * 4) * 4;
-
-    // loads of chunk C (macros, so the arrays stay in registers).  Row bases are wave-uniform (scalar
-    // registers); only the 32-bit lane offset is per lane.  Nothing is computed on the loaded values here:
-    // any arithmetic would wait for the load.
-#define PC_ISSUE_TH(C)                                                                                                \
-    do {                                                                                                              \
-        const int j_ = (C) / CPB, kc_ = (C) % CPB;                                                                    \
-        const int32_t ps_ = row_par[j_];                                                                              \
-        const float *tb_ = BWD ? theta + (int64_t)ps_ + (int64_t)(kc_ * KC) * K + sub * TM                            \
-                               : theta + (int64_t)ps_ + (int64_t)(sub * TM) * K + kc_ * KC;                           \
-        const __amdgpu_buffer_rsrc_t rt_ = __builtin_amdgcn_make_buffer_rsrc((void *)tb_, 0, PC_BUF_RANGE, PC_BUF_FLAGS); \
-        _Pragma("unroll") for (int i = 0; i < NF4; ++i) {               /* 64 lanes cover 64 / (TM/4 or KC/4) rows */   \
-            const int so_ = (BWD ? i * (64 / (TM / 4)) * K : i * (64 / (KC / 4)) * K) * 4;                            \
-            th[i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rt_, toff, so_, 0));           \
-        }                                                                                                             \
-    } while (0)
-#define PC_ISSUE_V(C, V, RB, BM)                                                                                      \
-    do {                                                                                                              \
-        const int j_ = (C) / CPB, kc_ = (C) % CPB;                                                                    \
-        const int32_t ns_ = row_nbr[j_];                                                                              \
-        const float *src_ = vsrc + (int64_t)(ns_ + kc_ * KC) * Bs;                                                    \
-        const __amdgpu_buffer_rsrc_t rv_ = __builtin_amdgcn_make_buffer_rsrc((void *)src_, 0, PC_BUF_RANGE, PC_BUF_FLAGS); \
-        _Pragma("unroll") for (int q = 0; q < NQ; ++q)                                                                \
-            V[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv_, voff[q % 4], soff[q / 4], 0)); \
-        const float *rrow_ = R + (int64_t)(ns_ / K) * Bs;                                                             \
-        RB = rrow_[(uint32_t)col];                                                                                    \
-        if (BWD) { const float *mrow_ = nfmax + (int64_t)(ns_ / K) * Bs; BM = mrow_[(uint32_t)col]; }                 \
-    } while (0)
-    // theta registers -> LDS tile
-#define PC_COMMIT()                                                                                                   \
-    do {                                                                                                              \
-        _Pragma("unroll") for (int i = 0; i < NF4; ++i) {                                                             \
-            const int t = lane + i * 64;                                                                              \
-            const int o = BWD ? (t / (TM / 4)) * LDA + (t % (TM / 4)) * 4 : (t / (KC / 4)) * LDA + (t % (KC / 4)) * 4; \
-            *reinterpret_cast<floatx4 *>(buf + o) = th[i];                                                            \
-        }                                                                                                             \
-    } while (0)
-    // LDS tile -> MFMA A operands of the whole chunk
-#define PC_READ_A(AR)                                                                                                 \
-    do {                                                                                                              \
-        _Pragma("unroll") for (int rt = 0; rt < RT; ++rt) {                                                           \
-            if (BWD) {                                                                                                \
-                _Pragma("unroll") for (int q = 0; q < NQ; ++q)                                                        \
-                    AR[q][rt] = buf[(8 * (q / 4) + 4 * half + (q % 4)) * LDA + rt * 32 + l32];                        \
-            } else {                                                                                                  \
-                _Pragma("unroll") for (int g = 0; g < NQ / 4; ++g) {                                                  \
-                    const floatx4 a4 = *reinterpret_cast<const floatx4 *>(buf + (rt * 32 + l32) * LDA + 8 * g + 4 * half); \
-                    AR[4 * g + 0][rt] = a4[0]; AR[4 * g + 1][rt] = a4[1];                                             \
-                    AR[4 * g + 2][rt] = a4[2]; AR[4 * g + 3][rt] = a4[3];                                             \
-                }                                                                                                     \
-            }                                                                                                         \
-        }                                                                                                             \
-    } while (0)
-    // per-chunk scalars: reference, maximum, rescale of the accumulator; leaves sh2 for the exponentials
-#define PC_PRE(V, RB, BM)                                                                                             \
-    do {                                                                                                              \
-        if (!BWD) {                                                     /* a larger reference: m moves by an exact integer */ \
-            const float Rn = fmaxf(Rrow, RB);                                                                         \
-            m += Rrow - Rn;                                             /* -inf stays -inf (RB is finite) */          \
-            Rrow = Rn;                                                                                                \
-        }                                                                                                             \
-        const float d = BWD ? Rrow - RB : RB - Rrow;                    /* exact integer <= 0 */                      \
-        float cmax;                                                                                                   \
-        if (BWD) {                                                                                                    \
-            cmax = BM + d;                                                                                            \
-        } else {                                                                                                      \
-            cmax = PC_NEG_INF;                                                                                        \
-            _Pragma("unroll") for (int q = 0; q < NQ; ++q) cmax = fmaxf(cmax, V[q]);                                  \
-            cmax = fmaxf(cmax, __shfl_xor(cmax, 32)) + d;                                                             \
-        }                                                                                                             \
-        const float m_new = cmax > m + PC_LAZY ? cmax : m;              /* -inf + 8 = -inf: the first finite chunk sets it */  \
-        const bool dead = !(m_new > PC_NEG_INF);                        /* every term of this column so far is 0 */   \
-        if (__any(m_new != m)) {                                                                                      \
-            const float scale = dead ? 1.0f : pc_half_scale(m - m_new); /* m = -inf: acc is 0 anyway */               \
-            _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                         \
-                _Pragma("unroll") for (int e = 0; e < 16; ++e) acc[rt][e] = acc[rt][e] * scale * scale;               \
-        }                                                                                                             \
-        m = m_new;                                                                                                    \
-        /* exp(v + d - m) = exp2(v * log2e + sh2); dead column: v = -inf -> 0 */                                      \
-        sh2 = dead ? 0.0f : (d - m_new + PC_UP) * PC_LOG2E;                                                           \
-    } while (0)
-    // MFMA steps [Q0, Q0 + NQ/2) of a chunk
-#define PC_MATH(AR, V, Q0)                                                                                            \
-    do {                                                                                                              \
-        _Pragma("unroll") for (int q = (Q0); q < (Q0) + NQ / 2; ++q) {                                                \
-            const float p = __builtin_amdgcn_exp2f(fmaf(V[q], PC_LOG2E, sh2));                                        \
-            _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                         \
-                acc[rt] = __builtin_amdgcn_mfma_f32_32x32x2f32(AR[q][rt], p, acc[rt], 0, 0, 0);                       \
-        }                                                                                                             \
-    } while (0)
+    // theta: forward, 16-byte pieces of rows of the sub-block; backward, one child column of parent rows 0 / 4
+    const int toff = BWD ? ((4 * half) * K + l32) * 4 : ((lane / (KC / 4)) * K + (lane % (KC / 4)) * 4) * 4;
 
     float sh2 = 0.0f;
-    // Two schedules of the chunk loop.  The plain one (load, stage, multiply, chunk after chunk) keeps one operand
-    // set, needs 75-150 registers and leaves 3-6 waves per SIMD to hide its waits; it is the faster one wherever a
-    // launch has waves to fill those slots, and also for the forward kernel at two waves per SIMD.  The software
-    // pipeline (two operand sets, 190-230 registers, two waves per SIMD) wins only for the backward kernel on
-    // launches of a few large tiles (SPLIT = 4: the reduction had to be split to fill the chip), where no third
-    // wave exists and the 32 four-byte LDS reads per chunk of the transposed operand would be waited for in full.
-    constexpr bool PIPELINED = BWD && RT == 2 && SPLIT == 4;
-    if (!PIPELINED) {
-        for (int c = sp; c < n_chunks; c += SPLIT) {
-            PC_ISSUE_TH(c);
-            PC_ISSUE_V(c, vA, rbA, bmA);
-            PC_COMMIT();
-            PC_READ_A(arA);
-            PC_PRE(vA, rbA, bmA);
-            PC_MATH(arA, vA, 0);
-            PC_MATH(arA, vA, NQ / 2);
-        }
-    } else {
-        if (sp < n_chunks) {
-            PC_ISSUE_TH(sp);
-            PC_ISSUE_V(sp, vA, rbA, bmA);
-            PC_COMMIT();
-            if (sp + SPLIT < n_chunks) { PC_ISSUE_TH(sp + SPLIT); PC_ISSUE_V(sp + SPLIT, vB, rbB, bmB); }
-            PC_READ_A(arA);
-        }
-        // pairs of chunks (c on set A, c + SPLIT on set B); a last single chunk follows the loop, so the loop has one
-        // exit and the accumulators stay in place
-        int c = sp;
-        for (; c + SPLIT < n_chunks; c += 2 * SPLIT) {
-            const bool more1 = c + 2 * SPLIT < n_chunks, more2 = c + 3 * SPLIT < n_chunks;
-            // chunk c on set A; chunk c + SPLIT is staged into set B meanwhile
-            PC_PRE(vA, rbA, bmA);
-            PC_MATH(arA, vA, 0);
-            PC_COMMIT();
-            if (more1) PC_ISSUE_TH(c + 2 * SPLIT);
-            PC_READ_A(arB);
-            PC_MATH(arA, vA, NQ / 2);
-            if (more1) PC_ISSUE_V(c + 2 * SPLIT, vA, rbA, bmA);
-            // chunk c + SPLIT on set B; chunk c + 2 SPLIT is staged into set A meanwhile
-            PC_PRE(vB, rbB, bmB);
-            PC_MATH(arB, vB, 0);
-            if (more1) {
-                PC_COMMIT();
-                if (more2) PC_ISSUE_TH(c + 3 * SPLIT);
-                PC_READ_A(arA);
+    for (int c = sp; c < n_chunks; c += SPLIT) {
+        const int j = c / CPB, kc = c % CPB;
+        // ---- loads of the chunk (nothing is computed on the loaded values here: any arithmetic would wait) ----
+        {
+            const int32_t ps = row_par[j];
+            const float *tb = BWD ? theta + (int64_t)ps + (int64_t)(kc * KC) * K + sub * TM
+                                  : theta + (int64_t)ps + (int64_t)(sub * TM) * K + kc * KC;
+            const __amdgpu_buffer_rsrc_t rth = __builtin_amdgcn_make_buffer_rsrc((void *)tb, 0, PC_BUF_RANGE, PC_BUF_FLAGS);
+            if (BWD) {
+#pragma unroll
+                for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt)
+                        ar[q][rt] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                                                  rth, toff, ((8 * (q / 4) + (q % 4)) * K + rt * 32) * 4, 0));
+            } else {
+#pragma unroll
+                for (int i = 0; i < NF4; ++i)                           // 64 lanes cover 64 / (KC / 4) rows
+                    th[i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                            rth, toff, i * (64 / (KC / 4)) * K * 4, 0));
             }
-            PC_MATH(arB, vB, NQ / 2);
-            if (more2) PC_ISSUE_V(c + 3 * SPLIT, vB, rbB, bmB);
+            const int32_t ns = row_nbr[j];
+            const float *src = vsrc + (int64_t)(ns + kc * KC) * Bs;
+            const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void *)src, 0, PC_BUF_RANGE, PC_BUF_FLAGS);
+#pragma unroll
+            for (int q = 0; q < NQ; ++q)
+                v[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, voff[q % 4], soff[q / 4], 0));
+            rb = (R + (int64_t)(ns / K) * Bs)[(uint32_t)col];
+            if (BWD) bm = (nfmax + (int64_t)(ns / K) * Bs)[(uint32_t)col];
         }
-        if (c < n_chunks) {                                                 // a last chunk, staged in set A
-            PC_PRE(vA, rbA, bmA);
-            PC_MATH(arA, vA, 0);
-            PC_MATH(arA, vA, NQ / 2);
+        // ---- forward: theta registers -> LDS tile -> A operands of the whole chunk ----
+        if (!BWD) {
+#pragma unroll
+            for (int i = 0; i < NF4; ++i) {
+                const int t = lane + i * 64;
+                *reinterpret_cast<floatx4 *>(buf + (t / (KC / 4)) * LDA + (t % (KC / 4)) * 4) = th[i];
+            }
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int g = 0; g < NQ / 4; ++g) {
+                    const floatx4 a4 = *reinterpret_cast<const floatx4 *>(buf + (rt * 32 + l32) * LDA + 8 * g + 4 * half);
+                    ar[4 * g + 0][rt] = a4[0]; ar[4 * g + 1][rt] = a4[1];
+                    ar[4 * g + 2][rt] = a4[2]; ar[4 * g + 3][rt] = a4[3];
+                }
+        }
+        // ---- per-chunk scalars: reference, maximum, rescale of the accumulator; leaves sh2 for the exponentials ----
+        {
+            if (!BWD) {                                                 // a larger reference: m moves by an exact integer
+                const float Rn = fmaxf(Rrow, rb);
+                m += Rrow - Rn;                                         // -inf stays -inf (rb is finite)
+                Rrow = Rn;
+            }
+            const float d = BWD ? Rrow - rb : rb - Rrow;                // exact integer <= 0
+            float cmax;
+            if (BWD) {
+                cmax = bm + d;
+            } else {
+                cmax = PC_NEG_INF;
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) cmax = fmaxf(cmax, v[q]);
+                cmax = fmaxf(cmax, __shfl_xor(cmax, 32)) + d;
+            }
+            const float m_new = cmax > m + PC_LAZY ? cmax : m;          // -inf + 8 = -inf: the first finite chunk sets it
+            const bool dead = !(m_new > PC_NEG_INF);                    // every term of this column so far is 0
+            if (__any(m_new != m)) {
+                const float scale = dead ? 1.0f : pc_half_scale(m - m_new);   // m = -inf: acc is 0 anyway
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[rt][e] = acc[rt][e] * scale * scale;
+            }
+            m = m_new;
+            // exp(v + d - m) = exp2(v * log2e + sh2); dead column: v = -inf -> 0
+            sh2 = dead ? 0.0f : (d - m_new + PC_UP) * PC_LOG2E;
+        }
+        // ---- the chunk's MFMA steps ----
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(v[q], PC_LOG2E, sh2));
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) acc[rt] = __builtin_amdgcn_mfma_f32_32x32x2f32(ar[q][rt], p, acc[rt], 0, 0, 0);
         }
     }
-#undef PC_ISSUE_TH
-#undef PC_ISSUE_V
-#undef PC_COMMIT
-#undef PC_READ_A
-#undef PC_PRE
-#undef PC_MATH
 
     if (SPLIT > 1) {                                                    // merge the partial sums of the SPLIT waves of a tile
         __syncthreads();
