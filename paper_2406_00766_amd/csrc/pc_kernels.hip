@@ -1332,7 +1332,11 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
     constexpr int Q = K / 2, QT = Q / 32;                               // a wave's quarter: Q x Q, QT x QT MFMA tiles
     constexpr int NL = K / 32;                                          // 16-byte loads per thread, chunk and array
     static_assert(K == 64 || K == 128, "workgroup-shared parameter-flow kernel");
-    __shared__ float lds[2 * TILE];
+    // K = 64 (short reductions, many small workgroups): one LDS tile, one register set, operands in two halves --
+    // 68 registers and 18 KB of LDS, seven waves per SIMD hide the waits and the second barrier per chunk.
+    // K = 128: two tiles, loads two chunks ahead (two workgroups per CU either way: the loop has to hide its own waits).
+    constexpr bool ONE = K == 64;
+    __shared__ float lds[(ONE ? 1 : 2) * TILE];
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
@@ -1418,7 +1422,37 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
                     acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(areg[q][rt], breg[q][ct], acc[rt][ct], 0, 0, 0); \
     } while (0)
 
+    // the same in two halves of eight steps (half the operand registers)
+#define PC_MATH_HALVES(T)                                                                                             \
+    do {                                                                                                              \
+        const float *Qt_ = lds + (T) * TILE + r0 * LD, *Pt_ = lds + (T) * TILE + (K + c0) * LD;                       \
+        _Pragma("unroll") for (int h2 = 0; h2 < 2; ++h2) {                                                            \
+            float areg[8][QT], breg[8][QT];                                                                           \
+            _Pragma("unroll") for (int rt = 0; rt < QT; ++rt)                                                         \
+                _Pragma("unroll") for (int g = 0; g < 2; ++g) {                                                       \
+                    const floatx4 a4 = *reinterpret_cast<const floatx4 *>(Qt_ + (rt * 32 + l32) * LD + 8 * (2 * h2 + g) + 4 * half); \
+                    areg[4 * g + 0][rt] = a4[0]; areg[4 * g + 1][rt] = a4[1]; areg[4 * g + 2][rt] = a4[2]; areg[4 * g + 3][rt] = a4[3]; \
+                    const floatx4 b4 = *reinterpret_cast<const floatx4 *>(Pt_ + (rt * 32 + l32) * LD + 8 * (2 * h2 + g) + 4 * half); \
+                    breg[4 * g + 0][rt] = b4[0]; breg[4 * g + 1][rt] = b4[1]; breg[4 * g + 2][rt] = b4[2]; breg[4 * g + 3][rt] = b4[3]; \
+                }                                                                                                     \
+            _Pragma("unroll") for (int q = 0; q < 8; ++q)                                                             \
+                _Pragma("unroll") for (int rt = 0; rt < QT; ++rt)                                                     \
+                    _Pragma("unroll") for (int ct = 0; ct < QT; ++ct)                                                 \
+                        acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(areg[q][rt], breg[q][ct], acc[rt][ct], 0, 0, 0); \
+        }                                                                                                             \
+    } while (0)
+
     // n_chunks is the same for all four waves, so every wave reaches every barrier
+    if (ONE) {
+        if (n_chunks > 0) PC_ISSUE(0, nfA, lcA, mxA, rsA, rcA);
+        for (int c = 0; c < n_chunks; ++c) {
+            if (c > 0) __syncthreads();                                 // the tile has been read by everybody
+            PC_STAGE(0, nfA, lcA, mxA, rsA, rcA);
+            if (c + 1 < n_chunks) PC_ISSUE(c + 1, nfA, lcA, mxA, rsA, rcA);
+            __syncthreads();
+            PC_MATH_HALVES(0);
+        }
+    } else {
     if (n_chunks > 0) PC_ISSUE(0, nfA, lcA, mxA, rsA, rcA);
     if (n_chunks > 1) PC_ISSUE(1, nfB, lcB, mxB, rsB, rcB);
     int c = 0;
@@ -1437,9 +1471,11 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
         __syncthreads();
         PC_MATH(0);
     }
+    }
 #undef PC_ISSUE
 #undef PC_STAGE
 #undef PC_MATH
+#undef PC_MATH_HALVES
 
 #pragma unroll
     for (int rt = 0; rt < QT; ++rt)
