@@ -1136,7 +1136,7 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
         }
         __syncthreads();
         if (sp != 0) return;
-#pragma unroll
+#pragma unroll 1                                                        // unrolled, the loads of all partners are hoisted: 45 registers
         for (int s = 1; s < SPLIT; ++s) {
             const float *ob = lds + (wave + s) * WSZ;
             float mo = ob[RT * 16 * 64 + lane];
