@@ -325,7 +325,7 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
         }
     }
     if (theta_flow && batched_params) {
-        ParamFlowDev pf{(int32_t)c->pf_pb.size(), c->d_pf_pb, c->d_pf_ptr, c->d_pf_sum, c->d_pf_child};
+        ParamFlowDev pf{(int32_t)c->pf_pb.size(), c->d_pf_pb, c->d_pf_ptr, c->d_pf_sum, c->d_pf_child, (int64_t)c->pf_sum.size()};
         launch_param_flow(theta, l, R, N, nfmax, theta_flow, pf, K, w.Bs, s);
     }
     PC_HIP(hipGetLastError());

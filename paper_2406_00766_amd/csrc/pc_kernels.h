@@ -27,6 +27,7 @@ struct GroupSet {
 struct ParamFlowDev {        // parameter blocks with the (sum block, child block) pairs that use them
     int32_t n_pb;
     const int32_t *pb, *ptr, *sum, *child;
+    int64_t n_pairs;         // entries of sum / child
 };
 
 struct EmDev {

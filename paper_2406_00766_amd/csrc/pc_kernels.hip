@@ -1319,7 +1319,7 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restr
 // the K / 2 + K / 2 rows of its quarter.  The tile is double-buffered, so one barrier per chunk suffices, and the loads run two chunks ahead of
 // the arithmetic: a chunk's matrix work (1.7 us) is shorter than a trip to HBM, which some of a chunk's loads
 // always take.
-template <int K>
+template <int K, bool ONE>
 __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__restrict__ theta, const float *__restrict__ l,
                                                                const float *__restrict__ R, const float *__restrict__ N,
                                                                const float *__restrict__ nfmax, float *__restrict__ G,
@@ -1332,10 +1332,11 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
     constexpr int Q = K / 2, QT = Q / 32;                               // a wave's quarter: Q x Q, QT x QT MFMA tiles
     constexpr int NL = K / 32;                                          // 16-byte loads per thread, chunk and array
     static_assert(K == 64 || K == 128, "workgroup-shared parameter-flow kernel");
-    // K = 64 (short reductions, many small workgroups): one LDS tile, one register set, operands in two halves --
-    // 68 registers and 18 KB of LDS, seven waves per SIMD hide the waits and the second barrier per chunk.
-    // K = 128: two tiles, loads two chunks ahead (two workgroups per CU either way: the loop has to hide its own waits).
-    constexpr bool ONE = K == 64;
+    // ONE (short reductions -- a parameter block used by one pair, B / 32 chunks -- and many small workgroups): one LDS
+    // tile, one register set, operands in two halves: at K = 64 68 registers and 18 KB of LDS, seven waves per SIMD hide
+    // the waits and the second barrier per chunk.  Otherwise (long reductions: tied blocks, e.g. the 31 layers of an
+    // HMM): two tiles, loads two chunks ahead -- two workgroups of K = 128 fit a CU either way, and the loop has to hide
+    // its own waits.
     __shared__ float lds[(ONE ? 1 : 2) * TILE];
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -2030,11 +2031,14 @@ void launch_param_flow(const float *theta, const float *l, const float *R, const
         hipLaunchKernelGGL((k_param_flow_mfma<32, 1, 1>), dim3((unsigned)((pf.n_pb + 3) / 4)), dim3(256), 0, s, theta, l, R, N,
                            nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, Bs);
     } else if (K == 64) {
-        hipLaunchKernelGGL((k_param_flow_mfma_wg<64>), dim3((unsigned)pf.n_pb), dim3(256), 0, s, theta, l, R, N, nfmax, G,
+        hipLaunchKernelGGL((k_param_flow_mfma_wg<64, true>), dim3((unsigned)pf.n_pb), dim3(256), 0, s, theta, l, R, N, nfmax, G,
                            pf.pb, pf.ptr, pf.sum, pf.child, Bs);
+    } else if ((int64_t)pf.n_pairs * (Bs / 32) < 64 * (int64_t)pf.n_pb) {     // fewer than 64 chunks per block on average
+        hipLaunchKernelGGL((k_param_flow_mfma_wg<128, true>), dim3((unsigned)pf.n_pb), dim3(256), 0, s, theta, l, R, N, nfmax,
+                           G, pf.pb, pf.ptr, pf.sum, pf.child, Bs);
     } else {
-        hipLaunchKernelGGL((k_param_flow_mfma_wg<128>), dim3((unsigned)pf.n_pb), dim3(256), 0, s, theta, l, R, N, nfmax, G,
-                           pf.pb, pf.ptr, pf.sum, pf.child, Bs);
+        hipLaunchKernelGGL((k_param_flow_mfma_wg<128, false>), dim3((unsigned)pf.n_pb), dim3(256), 0, s, theta, l, R, N, nfmax,
+                           G, pf.pb, pf.ptr, pf.sum, pf.child, Bs);
     }
 }
 
