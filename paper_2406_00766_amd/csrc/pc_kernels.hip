@@ -1195,7 +1195,7 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
 // to reach the MFMA operand layouts (batch index on k: step q pairs lanes 0-31 with sample 8*(q/4) + q%4
 // and lanes 32-63 with sample 8*(q/4) + 4 + q%4); loads of the next chunk are issued before the
 // arithmetic of the current one.
-template <int K, int RT, int CT>
+template <int K, int RT, int CT, bool ONE>
 __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restrict__ theta, const float *__restrict__ l,
                                                             const float *__restrict__ R, const float *__restrict__ N,
                                                             const float *__restrict__ nfmax, float *__restrict__ G,
@@ -1207,7 +1207,11 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restr
     constexpr int TPB = (K / TMW) * (K / TNW);                          // wave tiles per parameter block
     constexpr int LD = 36;                                              // LDS row stride: 16-byte rows, b128 reads conflict-free
     constexpr int NA4 = TMW * 8 / 64, NB4 = TNW * 8 / 64;               // 16-byte loads per lane per chunk
-    __shared__ float lds[4 * (TMW + TNW) * LD];
+    // ONE (short reductions): a single tile per wave, used for N's factors and then for l's (LDS operations of one wave
+    // complete in order) -- half the LDS, twice the workgroups per CU; the second staging then waits for the first
+    // operand read, which costs more than it gains once a block has 16 chunks or more.
+    constexpr int TLD = ONE ? (TMW > TNW ? TMW : TNW) : TMW + TNW;
+    __shared__ float lds[4 * TLD * LD];
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
@@ -1217,7 +1221,7 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restr
     const int r0 = (tin / (K / TNW)) * TMW, c0 = (tin % (K / TNW)) * TNW;
     const int32_t pb = pf_pb[pidx];
     const int i0 = pf_ptr[pidx], i1 = pf_ptr[pidx + 1];
-    float *Qs = lds + wave * (TMW + TNW) * LD, *Ps = Qs + TMW * LD;
+    float *Qs = lds + wave * TLD * LD, *Ps = ONE ? Qs : Qs + TMW * LD;
     const int srow = lane >> 3, sc4 = (lane & 7) * 4;                   // staging: 8 lanes x 16 bytes per row of 32 samples
 
     floatx16 acc[RT][CT];
@@ -1263,6 +1267,16 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restr
             for (int e = 0; e < 4; ++e) q[e] = __builtin_amdgcn_exp2f(fmaf(nf_next[i][e], PC_LOG2E, qa[e]));
             *reinterpret_cast<floatx4 *>(Qs + (8 * i + srow) * LD + sc4) = q;
         }
+        // operands of the whole chunk into registers (LDS operations of one wave complete in order); with a single tile
+        // the first operand has to be read before the second is staged
+        float areg[16][RT], breg[16][CT];
+#define PC_READ_AREG()                                                                                                \
+    _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                                                 \
+        _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                                               \
+            const floatx4 a4 = *reinterpret_cast<const floatx4 *>(Qs + (rt * 32 + l32) * LD + 8 * g + 4 * half);      \
+            areg[4 * g + 0][rt] = a4[0]; areg[4 * g + 1][rt] = a4[1]; areg[4 * g + 2][rt] = a4[2]; areg[4 * g + 3][rt] = a4[3]; \
+        }
+        if (ONE) PC_READ_AREG();
 #pragma unroll
         for (int i = 0; i < NB4; ++i) {
             floatx4 p;
@@ -1272,16 +1286,8 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restr
             *reinterpret_cast<floatx4 *>(Ps + (8 * i + srow) * LD + sc4) = p;
         }
         if (c + 1 < n_chunks) PC_ISSUE(c + 1);
-
-        // operands of the whole chunk into registers (LDS operations of one wave complete in order)
-        float areg[16][RT], breg[16][CT];
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const floatx4 a4 = *reinterpret_cast<const floatx4 *>(Qs + (rt * 32 + l32) * LD + 8 * g + 4 * half);
-                areg[4 * g + 0][rt] = a4[0]; areg[4 * g + 1][rt] = a4[1]; areg[4 * g + 2][rt] = a4[2]; areg[4 * g + 3][rt] = a4[3];
-            }
+        if (!ONE) PC_READ_AREG();
+#undef PC_READ_AREG
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
@@ -2028,8 +2034,12 @@ void launch_param_flow(const float *theta, const float *l, const float *R, const
         else PC_PF_SMALL(16, 8);
 #undef PC_PF_SMALL
     } else if (K == 32) {
-        hipLaunchKernelGGL((k_param_flow_mfma<32, 1, 1>), dim3((unsigned)((pf.n_pb + 3) / 4)), dim3(256), 0, s, theta, l, R, N,
-                           nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, Bs);
+        if ((int64_t)pf.n_pairs * (Bs / 32) < 12 * (int64_t)pf.n_pb)    // fewer than 12 chunks per block on average
+            hipLaunchKernelGGL((k_param_flow_mfma<32, 1, 1, true>), dim3((unsigned)((pf.n_pb + 3) / 4)), dim3(256), 0, s, theta, l,
+                               R, N, nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, Bs);
+        else
+            hipLaunchKernelGGL((k_param_flow_mfma<32, 1, 1, false>), dim3((unsigned)((pf.n_pb + 3) / 4)), dim3(256), 0, s, theta, l,
+                               R, N, nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, Bs);
     } else if (K == 64) {
         hipLaunchKernelGGL((k_param_flow_mfma_wg<64, true>), dim3((unsigned)pf.n_pb), dim3(256), 0, s, theta, l, R, N, nfmax, G,
                            pf.pb, pf.ptr, pf.sum, pf.child, Bs);
