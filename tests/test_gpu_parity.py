@@ -142,6 +142,24 @@ def test_block_sparse_sum_layer(n_sets, M, K, keep, B):
     assert_device_tables_match_oracle(got["circuit"].handle, w)
 
 
+@pytest.mark.parametrize("make", [
+    # long tied reductions at K = 128 (39 pairs x 3 chunks per parameter block): the two-tile parameter-flow kernel
+    lambda: W.hmm(40, 256, 60, 128, 70, 41),
+    # K = 32, 40 pairs x 3 chunks: the two-tile per-wave kernel; the short form is what the other K = 32 cases take
+    lambda: W.hmm(41, 64, 30, 32, 70, 42),
+    # 256 categories, K = 64, B = 300: the input-layer flows go through two slabs of samples (256 + 64), some masked
+    lambda: W.hclt(12, 128, 64, 300, 43, n_cats=256),
+    # more than 1024 categories: per-sample atomics
+    lambda: W.hmm(5, 64, 1500, 32, 130, 44, tokens="zipf"),
+])
+def test_kernel_variants_selected_by_shape(make):
+    w = make()
+    print(f"case variant {w.name}", flush=True)
+    rng = np.random.default_rng(5)
+    mask = (rng.random(w.x.shape) < 0.15).astype(np.uint8)
+    check_all(w, mask)
+
+
 def test_layer_with_more_groups_than_one_launch_covers():
     """Alg. 2 with G = 16 and tol = 0 gives one group per distinct child count; a launch covers eight groups."""
     import dataclasses
