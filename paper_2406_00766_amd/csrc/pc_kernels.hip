@@ -386,14 +386,16 @@ __device__ inline GroupRow locate_row(const GroupSet &gs, int row)
 // rg, rg+16, ... of 4 adjacent columns (16-byte accesses along the batch), so a K-row block is K/16 rows
 // deep per thread and all its loads are independent.  Column maxima over the K rows go through one
 // shuffle stage (4 row groups per wave) and one LDS stage (4 waves).
+template <int CL>
 __device__ inline void block_col_max(float (&mx)[4], float (*red)[64], int wave, int cl)
 {
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
+        if (CL == 8) mx[v] = fmaxf(mx[v], __shfl_xor(mx[v], 8));
         mx[v] = fmaxf(mx[v], __shfl_xor(mx[v], 16));
         mx[v] = fmaxf(mx[v], __shfl_xor(mx[v], 32));
     }
-    if ((threadIdx.x & 63) < 16) {
+    if ((threadIdx.x & 63) < CL) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) red[wave][cl * 4 + v] = mx[v];
     }
@@ -411,15 +413,16 @@ __device__ inline void block_col_max(float (&mx)[4], float (*red)[64], int wave,
 
 // forward (Sec. 3): s = sum of the children's residuals; the column maximum over the K rows is rounded to an
 // integer and moved into R
-template <int RPT, int U, bool MULTI>
+template <int RPT, int U, bool MULTI, int CL>
 __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *__restrict__ R, const GroupSet gs,
                                                   int32_t K, int64_t Bs)
 {
     __shared__ float red[4][64];
     const GroupRow gr = locate_row<MULTI>(gs, blockIdx.x);
     const int r = gr.r;
-    const int rg = threadIdx.x >> 4, cl = threadIdx.x & 15, wave = threadIdx.x >> 6;
-    const int64_t b = (int64_t)blockIdx.y * 64 + cl * 4;
+    constexpr int RG = 256 / CL;                                        // row groups: a thread owns rows rg, rg + RG, ...
+    const int rg = threadIdx.x / CL, cl = threadIdx.x % CL, wave = threadIdx.x >> 6;
+    const int64_t b = (int64_t)blockIdx.y * (4 * CL) + cl * 4;
     const bool in = b < Bs;                                            // Bs is a multiple of 32: b..b+3 all inside
     const int32_t *row_nbr = gr.nbr + (int64_t)r * gr.width;
     const int32_t cnt = gr.aux[r] >> 8;
@@ -440,7 +443,7 @@ __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *
                 const bool on = j0 + u < cnt;                          // uniform over the workgroup
 #pragma unroll
                 for (int i = 0; i < RPT; ++i) {
-                    const int k = rg + 16 * i;
+                    const int k = rg + RG * i;
                     t[u][i] = (on && k < K) ? *reinterpret_cast<const float4 *>(l + (int64_t)(ch[u] + k) * Bs + b)
                                             : make_float4(0.f, 0.f, 0.f, 0.f);
                 }
@@ -458,12 +461,12 @@ __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *
         }
 #pragma unroll
         for (int i = 0; i < RPT; ++i)
-            if (rg + 16 * i < K) {
+            if (rg + RG * i < K) {
                 mx[0] = fmaxf(mx[0], s[i].x); mx[1] = fmaxf(mx[1], s[i].y);
                 mx[2] = fmaxf(mx[2], s[i].z); mx[3] = fmaxf(mx[3], s[i].w);
             }
     }
-    block_col_max(mx, red, wave, cl);
+    block_col_max<CL>(mx, red, wave, cl);
     if (!in) return;
     float sh[4];
 #pragma unroll
@@ -472,7 +475,7 @@ __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *
         *reinterpret_cast<float4 *>(R + (int64_t)(id / K) * Bs + b) = make_float4(rsum.x + sh[0], rsum.y + sh[1], rsum.z + sh[2], rsum.w + sh[3]);
 #pragma unroll
     for (int i = 0; i < RPT; ++i) {
-        const int k = rg + 16 * i;
+        const int k = rg + RG * i;
         if (k < K)
             *reinterpret_cast<float4 *>(l + (int64_t)(id + k) * Bs + b) = make_float4(s[i].x - sh[0], s[i].y - sh[1], s[i].z - sh[2], s[i].w - sh[3]);
     }
@@ -482,15 +485,16 @@ __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *
 // F_child += sum of the parents' flows ('=' where this is the first layer that feeds the block, flag bit 1, so
 // the flow buffer is never cleared).  Where this layer is the last one that feeds a SUM block (flag bit 0) its
 // flow is final, so log_nf = log F - l (Alg. 3 / 4) and its column maximum per block are produced here.
-template <int RPT, int U, bool MULTI>
+template <int RPT, int U, bool MULTI, int CL>
 __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, float *__restrict__ F, float *__restrict__ N,
                                                   float *__restrict__ nfmax, const GroupSet gs, int32_t K, int64_t Bs)
 {
     __shared__ float red[4][64];
     const GroupRow gr = locate_row<MULTI>(gs, blockIdx.x);
     const int r = gr.r;
-    const int rg = threadIdx.x >> 4, cl = threadIdx.x & 15, wave = threadIdx.x >> 6;
-    const int64_t b = (int64_t)blockIdx.y * 64 + cl * 4;
+    constexpr int RG = 256 / CL;                                        // row groups: a thread owns rows rg, rg + RG, ...
+    const int rg = threadIdx.x / CL, cl = threadIdx.x % CL, wave = threadIdx.x >> 6;
+    const int64_t b = (int64_t)blockIdx.y * (4 * CL) + cl * 4;
     const bool in = b < Bs;
     const int32_t *row_nbr = gr.nbr + (int64_t)r * gr.width;
     const int32_t id = gr.ids[r];
@@ -501,7 +505,7 @@ __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, f
     if (in) {
 #pragma unroll
         for (int i = 0; i < RPT; ++i) {
-            const int k = rg + 16 * i;
+            const int k = rg + RG * i;
             f[i] = (k < K && !first) ? *reinterpret_cast<const float4 *>(F + (int64_t)(id + k) * Bs + b)
                                      : make_float4(0.f, 0.f, 0.f, 0.f);
             // the block's own log-probabilities, needed only for log_nf: fetched with everything else
@@ -518,7 +522,7 @@ __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, f
                 const bool on = j0 + u < cnt;                          // uniform over the workgroup
 #pragma unroll
                 for (int i = 0; i < RPT; ++i) {
-                    const int k = rg + 16 * i;
+                    const int k = rg + RG * i;
                     t[u][i] = (on && k < K) ? *reinterpret_cast<const float4 *>(F + (int64_t)(pa[u] + k) * Bs + b)
                                             : make_float4(0.f, 0.f, 0.f, 0.f);
                 }
@@ -532,7 +536,7 @@ __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, f
         }
 #pragma unroll
         for (int i = 0; i < RPT; ++i) {
-            const int k = rg + 16 * i;
+            const int k = rg + RG * i;
             if (k < K) *reinterpret_cast<float4 *>(F + (int64_t)(id + k) * Bs + b) = f[i];
         }
     }
@@ -541,7 +545,7 @@ __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, f
     if (in) {
 #pragma unroll
         for (int i = 0; i < RPT; ++i) {
-            const int k = rg + 16 * i;
+            const int k = rg + RG * i;
             if (k < K) {
                 float4 nf;
                 nf.x = (f[i].x > 0.0f && lv[i].x > PC_NEG_INF) ? __logf(f[i].x) - lv[i].x : PC_NEG_INF;
@@ -553,7 +557,7 @@ __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, f
             }
         }
     }
-    block_col_max(mx, red, wave, cl);
+    block_col_max<CL>(mx, red, wave, cl);
     if (in && rg == 0) *reinterpret_cast<float4 *>(nfmax + (int64_t)(id / K) * Bs + b) = make_float4(mx[0], mx[1], mx[2], mx[3]);
 }
 
@@ -1857,16 +1861,22 @@ void launch_input_bwd(const float *F, const int32_t *xT, const GroupDev &g, int3
 // neighbours in flight cost a fifth of the occupancy and 15 % of the PD's product-layer time)
 #define PC_DISPATCH_PROD_M(KERNEL, MULTI, ...)                                                             \
     do {                                                                                                   \
-        if (K <= 16) hipLaunchKernelGGL((KERNEL<1, 8, MULTI>), __VA_ARGS__);                               \
-        else if (K <= 32) hipLaunchKernelGGL((KERNEL<2, 4, MULTI>), __VA_ARGS__);                          \
-        else if (K <= 64) hipLaunchKernelGGL((KERNEL<4, 4, MULTI>), __VA_ARGS__);                          \
-        else hipLaunchKernelGGL((KERNEL<8, 2, MULTI>), __VA_ARGS__);                                       \
+        if (narrow) {                                /* 32 columns per workgroup: twice the workgroups, half the rows per thread */ \
+            if (K <= 32) hipLaunchKernelGGL((KERNEL<1, 8, MULTI, 8>), __VA_ARGS__);                        \
+            else if (K <= 64) hipLaunchKernelGGL((KERNEL<2, 4, MULTI, 8>), __VA_ARGS__);                   \
+            else hipLaunchKernelGGL((KERNEL<4, 4, MULTI, 8>), __VA_ARGS__);                                \
+        } else if (K <= 16) hipLaunchKernelGGL((KERNEL<1, 8, MULTI, 16>), __VA_ARGS__);                    \
+        else if (K <= 32) hipLaunchKernelGGL((KERNEL<2, 4, MULTI, 16>), __VA_ARGS__);                      \
+        else if (K <= 64) hipLaunchKernelGGL((KERNEL<4, 4, MULTI, 16>), __VA_ARGS__);                      \
+        else hipLaunchKernelGGL((KERNEL<8, 2, MULTI, 16>), __VA_ARGS__);                                   \
     } while (0)
 #define PC_DISPATCH_PROD(KERNEL, ...)                                                                      \
     do {                                                                                                   \
         if (gs.n > 1) PC_DISPATCH_PROD_M(KERNEL, true, __VA_ARGS__);                                       \
         else PC_DISPATCH_PROD_M(KERNEL, false, __VA_ARGS__);                                               \
     } while (0)
+// small launches (the deep narrow circuits) use 32-column workgroups
+static inline bool prod_narrow(const GroupSet &gs, int64_t Bs) { return (int64_t)gs.first[gs.n] * ((Bs + 63) / 64) < 1024; }
 
 // Sets of at most PC_MAX_SET groups, widest rows first (the longest rows start first, so they do not trail the launch).
 std::vector<GroupSet> make_group_sets(const std::vector<GroupDev> &groups)
@@ -1899,7 +1909,8 @@ void launch_prod_fwd(float *l, float *R, const std::vector<GroupSet> &sets, int3
 {
     for (const GroupSet &gs : sets) {
         Timed timed(KC_PROD_FWD, s);
-        dim3 grid((unsigned)set_rows(gs), (unsigned)((Bs + 63) / 64));
+        const bool narrow = prod_narrow(gs, Bs);
+        dim3 grid((unsigned)set_rows(gs), (unsigned)(narrow ? (Bs + 31) / 32 : (Bs + 63) / 64));
         PC_DISPATCH_PROD(k_prod_fwd, grid, dim3(256), 0, s, l, R, gs, K, Bs);
     }
 }
@@ -1909,7 +1920,8 @@ void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const std
 {
     for (const GroupSet &gs : sets) {
         Timed timed(KC_PROD_BWD, s);
-        dim3 grid((unsigned)set_rows(gs), (unsigned)((Bs + 63) / 64));
+        const bool narrow = prod_narrow(gs, Bs);
+        dim3 grid((unsigned)set_rows(gs), (unsigned)(narrow ? (Bs + 31) / 32 : (Bs + 63) / 64));
         PC_DISPATCH_PROD(k_prod_bwd, grid, dim3(256), 0, s, l, F, N, nfmax, gs, K, Bs);
     }
 }
