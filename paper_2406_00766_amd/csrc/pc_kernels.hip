@@ -1415,26 +1415,8 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
         }                                                                                                             \
     } while (0)
 
-    // this wave's operands of the whole chunk from tile T, then the products
-#define PC_MATH(T)                                                                                                    \
-    do {                                                                                                              \
-        const float *Qt_ = lds + (T) * TILE + r0 * LD, *Pt_ = lds + (T) * TILE + (K + c0) * LD;                       \
-        float areg[16][QT], breg[16][QT];                                                                             \
-        _Pragma("unroll") for (int rt = 0; rt < QT; ++rt)                                                             \
-            _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                                           \
-                const floatx4 a4 = *reinterpret_cast<const floatx4 *>(Qt_ + (rt * 32 + l32) * LD + 8 * g + 4 * half); \
-                areg[4 * g + 0][rt] = a4[0]; areg[4 * g + 1][rt] = a4[1]; areg[4 * g + 2][rt] = a4[2]; areg[4 * g + 3][rt] = a4[3]; \
-                const floatx4 b4 = *reinterpret_cast<const floatx4 *>(Pt_ + (rt * 32 + l32) * LD + 8 * g + 4 * half); \
-                breg[4 * g + 0][rt] = b4[0]; breg[4 * g + 1][rt] = b4[1]; breg[4 * g + 2][rt] = b4[2]; breg[4 * g + 3][rt] = b4[3]; \
-            }                                                                                                         \
-        _Pragma("unroll") for (int q = 0; q < 16; ++q)                                                                \
-            _Pragma("unroll") for (int rt = 0; rt < QT; ++rt)                                                         \
-                _Pragma("unroll") for (int ct = 0; ct < QT; ++ct)                                                     \
-                    acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(areg[q][rt], breg[q][ct], acc[rt][ct], 0, 0, 0); \
-    } while (0)
-
-    // the same in two halves of eight steps (half the operand registers)
-#define PC_MATH_HALVES(T)                                                                                             \
+    // this wave's operands from tile T, then the products -- in two halves of eight steps (half the operand registers)
+#define PC_MATH(T)                                                                                             \
     do {                                                                                                              \
         const float *Qt_ = lds + (T) * TILE + r0 * LD, *Pt_ = lds + (T) * TILE + (K + c0) * LD;                       \
         _Pragma("unroll") for (int h2 = 0; h2 < 2; ++h2) {                                                            \
@@ -1461,7 +1443,7 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
             PC_STAGE(0, nfA, lcA, mxA, rsA, rcA);
             if (c + 1 < n_chunks) PC_ISSUE(c + 1, nfA, lcA, mxA, rsA, rcA);
             __syncthreads();
-            PC_MATH_HALVES(0);
+            PC_MATH(0);
         }
     } else {
     if (n_chunks > 0) PC_ISSUE(0, nfA, lcA, mxA, rsA, rcA);
@@ -1486,7 +1468,6 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
 #undef PC_ISSUE
 #undef PC_STAGE
 #undef PC_MATH
-#undef PC_MATH_HALVES
 
 #pragma unroll
     for (int rt = 0; rt < QT; ++rt)
