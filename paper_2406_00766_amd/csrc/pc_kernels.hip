@@ -1326,9 +1326,10 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restr
 // quarters of one K x K parameter block, and every fetched row is used by two of them.  Per chunk of 32 samples the
 // 256 threads fetch and exponentiate the K rows of N and the K rows of l ONCE (K / 32 + K / 32 sixteen-byte loads per
 // thread; the per-wave kernel needs four times as many at K = 128) into a workgroup tile in LDS; each wave then reads
-// the K / 2 + K / 2 rows of its quarter.  The tile is double-buffered, so one barrier per chunk suffices, and the loads run two chunks ahead of
-// the arithmetic: a chunk's matrix work (1.7 us) is shorter than a trip to HBM, which some of a chunk's loads
-// always take.
+// the K / 2 + K / 2 rows of its quarter.  Two forms (template parameter ONE, see inside): for long reductions the tile
+// is double-buffered, so one barrier per chunk suffices, and the loads run two chunks ahead of the arithmetic -- a
+// chunk's matrix work (1.7 us) is shorter than a trip to HBM, which some of a chunk's loads always take; for short
+// reductions one tile and one register set, and many more waves per SIMD.
 template <int K, bool ONE>
 __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__restrict__ theta, const float *__restrict__ l,
                                                                const float *__restrict__ R, const float *__restrict__ N,
