@@ -1470,17 +1470,27 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
 #undef PC_STAGE
 #undef PC_MATH
 
+    // flows out: all loads of a 32 x 32 tile first, then the arithmetic, then the stores (a load between two stores
+    // would be waited for on its own); theta = 0: no flow (and never 0 * inf)
 #pragma unroll
     for (int rt = 0; rt < QT; ++rt)
 #pragma unroll
-        for (int ct = 0; ct < QT; ++ct)
+        for (int ct = 0; ct < QT; ++ct) {
+            floatx16 thv, gv;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int i = r0 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
                 const int64_t at = (int64_t)pb + (int64_t)i * K + c0 + ct * 32 + l32;
-                const float th = theta[at];
-                if (th > 0.0f) G[at] += th * acc[rt][ct][e] * PC_SPLIT_OUT;   // theta = 0: no flow (and never 0 * inf)
+                thv[e] = theta[at];
+                gv[e] = G[at];
             }
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int i = r0 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                const int64_t at = (int64_t)pb + (int64_t)i * K + c0 + ct * 32 + l32;
+                G[at] = gv[e] + (thv[e] > 0.0f ? thv[e] * acc[rt][ct][e] * PC_SPLIT_OUT : 0.0f);
+            }
+        }
 }
 
 // ------------------------------------------------------------------------------------------
