@@ -1163,21 +1163,38 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
     }
     if (!active) return;
     if (!BWD && sub == 0 && half == 0) R[(int64_t)(id / K) * Bs + col] = Rrow;
-    const int64_t base = (int64_t)(id + sub * TM);
+    // Results out.  The rows are addressed through one buffer descriptor at the tile's first row with a scalar offset
+    // per row.  Backward: log and exp are the hardware's base-2 instructions (the accumulator of a column with any
+    // term is a normal number -- the largest term is at least FLT_MIN * e^PC_UP -- so no denormal care is needed).
+    float *out = BWD ? F : l;
+    const __amdgpu_buffer_rsrc_t ro =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(out + (int64_t)(id + sub * TM) * Bs), 0, PC_BUF_RANGE, PC_BUF_FLAGS);
+    const int ooff = (int)(((int64_t)(4 * half) * Bs + col) * 4);        // rows 4 * half + (0..3) of a group of 8 rows
+    const float mb = (m - PC_UP) * PC_LOG2E;
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            const int i = rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+            const int so = __builtin_amdgcn_readfirstlane((int)((int64_t)(rt * 32 + 8 * (e / 4) + (e % 4)) * Bs * 4));
             const float a = acc[rt][e];
-            const int64_t at = (base + i) * Bs + col;
             if (BWD) {
+                const float lg = __builtin_amdgcn_logf(a);              // log2; a = 0 -> -inf
                 const float lc = lown[rt][e];
-                const float add = (a > 0.0f && lc > PC_NEG_INF) ? __expf(__logf(a) + (m - PC_UP) + lc) : 0.0f;
-                if (first) F[at] = add;
-                else if (add > 0.0f) F[at] += add;
+                // exp(ln a + (m - PC_UP) + lc); a = 0 or lc = -inf gives exp2(-inf) = 0
+                const float add = __builtin_amdgcn_exp2f(lg + fmaf(lc, PC_LOG2E, mb));
+                if (first) {
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, add), ro, ooff, so, 0);
+                } else if (add > 0.0f) {
+                    const float old = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ro, ooff, so, 0));
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, old + add), ro, ooff, so, 0);
+                }
             } else {
-                l[at] = a > 0.0f ? m - PC_UP + __logf(a) : PC_NEG_INF;
+                // ln a + (m - PC_UP), with the logarithm taken of a / 2^24: the accumulator of a live column is around
+                // e^PC_UP, and a base-2 logarithm near 0 is far more accurate in absolute terms than one near 29 --
+                // these errors add up from layer to layer (a log-likelihood near 0 has an absolute tolerance of 1e-5).
+                // a = 0: -inf.  (a >= FLT_MIN * e^PC_UP > 2^-98, so a / 2^24 is a normal number.)
+                const float v = fmaf(__builtin_amdgcn_logf(a * 0x1p-24f), 0.6931471805599453f, m + (16.635532333f - PC_UP));
+                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), ro, ooff, so, 0);
             }
         }
 }
