@@ -356,27 +356,19 @@ __global__ __launch_bounds__(256) void k_input_bwd_sorted(const float *__restric
     }
 }
 
-// Group of launch row `row` in a set (wave-uniform).  Every field of the argument is at a fixed offset, so all of
-// them are fetched at once with the other kernel arguments and the group's are picked with scalar selects: no load
-// depends on the group index.  Kernels are instantiated for one group (MULTI = false: the deep narrow circuits,
-// where even the selects show in a launch of a few microseconds) and for several.
+// Group of launch row `row` in a set (wave-uniform).  Kernels are instantiated for one group (MULTI = false: the deep
+// narrow circuits, where anything extra shows in a launch of a few microseconds) and for several: there the group
+// index is found with a few scalar compares and the group's fields are read from the argument at that index (one
+// more dependent scalar load, which launches with several groups -- thousands of workgroups -- hide).
 struct GroupRow { int32_t r, width; const int32_t *ids, *nbr, *par, *aux; };
 template <bool MULTI>
 __device__ inline GroupRow locate_row(const GroupSet &gs, int row)
 {
-    GroupRow o{row, gs.width[0], gs.ids[0], gs.nbr[0], gs.par[0], gs.aux[0]};
-    if (!MULTI) return o;                                               // a set of one group: nothing to pick
+    if (!MULTI) return GroupRow{row, gs.width[0], gs.ids[0], gs.nbr[0], gs.par[0], gs.aux[0]};   // a set of one group
+    int g = 0;                                                          // groups are in row order: count the starts passed
 #pragma unroll
-    for (int i = 1; i < PC_MAX_SET; ++i) {
-        const bool here = i < gs.n && row >= gs.first[i];
-        o.r = here ? row - gs.first[i] : o.r;
-        o.width = here ? gs.width[i] : o.width;
-        o.ids = here ? gs.ids[i] : o.ids;
-        o.nbr = here ? gs.nbr[i] : o.nbr;
-        o.par = here ? gs.par[i] : o.par;
-        o.aux = here ? gs.aux[i] : o.aux;
-    }
-    return o;
+    for (int i = 1; i < PC_MAX_SET; ++i) g += (i < gs.n && row >= gs.first[i]) ? 1 : 0;
+    return GroupRow{row - gs.first[g], gs.width[g], gs.ids[g], gs.nbr[g], gs.par[g], gs.aux[g]};
 }
 
 // ------------------------------------------------------------------------------------------
