@@ -1007,13 +1007,20 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
     float m = PC_NEG_INF;
     // backward: the rows' own log-probabilities are needed only at the end; fetched now, their latency is hidden
     // behind the whole reduction (short reductions are latency-bound)
+    // (the tile's rows through one buffer descriptor at its first row: per-lane offset = rows 4 * half + (0..3) of a
+    // group of 8 rows and the column, scalar offset per row -- no per-element address arithmetic)
     floatx16 lown[BWD ? RT : 1];
+    const int ooff = (int)(((int64_t)(4 * half) * Bs + col) * 4);
     if (BWD) {
+        const __amdgpu_buffer_rsrc_t rl =
+            __builtin_amdgcn_make_buffer_rsrc((void *)(l + (int64_t)(id + sub * TM) * Bs), 0, PC_BUF_RANGE, PC_BUF_FLAGS);
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                lown[rt][e] = l[((int64_t)(id + sub * TM) + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4)) * Bs + col];
+            for (int e = 0; e < 16; ++e) {
+                const int so = __builtin_amdgcn_readfirstlane((int)((int64_t)(rt * 32 + 8 * (e / 4) + (e % 4)) * Bs * 4));
+                lown[rt][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rl, ooff, so, 0));
+            }
     }
 
     // Operands of one chunk: `ar` the MFMA A operands (theta), `v` the neighbour values with their block scalars;
@@ -1161,7 +1168,6 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
     float *out = BWD ? F : l;
     const __amdgpu_buffer_rsrc_t ro =
         __builtin_amdgcn_make_buffer_rsrc((void *)(out + (int64_t)(id + sub * TM) * Bs), 0, PC_BUF_RANGE, PC_BUF_FLAGS);
-    const int ooff = (int)(((int64_t)(4 * half) * Bs + col) * 4);        // rows 4 * half + (0..3) of a group of 8 rows
     const float mb = (m - PC_UP) * PC_LOG2E;
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
