@@ -2060,15 +2060,17 @@ void launch_param_flow(const float *theta, const float *l, const float *R, const
         else
             hipLaunchKernelGGL((k_param_flow_mfma<32, 1, 1, false>), dim3((unsigned)((pf.n_pb + 3) / 4)), dim3(256), 0, s, theta, l,
                                R, N, nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, Bs);
-    } else if (K == 64) {
-        hipLaunchKernelGGL((k_param_flow_mfma_wg<64, true>), dim3((unsigned)pf.n_pb), dim3(256), 0, s, theta, l, R, N, nfmax, G,
-                           pf.pb, pf.ptr, pf.sum, pf.child, Bs);
-    } else if ((int64_t)pf.n_pairs * (Bs / 32) < 64 * (int64_t)pf.n_pb) {     // fewer than 64 chunks per block on average
-        hipLaunchKernelGGL((k_param_flow_mfma_wg<128, true>), dim3((unsigned)pf.n_pb), dim3(256), 0, s, theta, l, R, N, nfmax,
-                           G, pf.pb, pf.ptr, pf.sum, pf.child, Bs);
     } else {
-        hipLaunchKernelGGL((k_param_flow_mfma_wg<128, false>), dim3((unsigned)pf.n_pb), dim3(256), 0, s, theta, l, R, N, nfmax,
-                           G, pf.pb, pf.ptr, pf.sum, pf.child, Bs);
+        // short reductions (fewer than 64 chunks per block on average): the single-tile form
+        const bool one = (int64_t)pf.n_pairs * (Bs / 32) < 64 * (int64_t)pf.n_pb;
+#define PC_PF_WG(KK, ONE)                                                                                           \
+    hipLaunchKernelGGL((k_param_flow_mfma_wg<KK, ONE>), dim3((unsigned)pf.n_pb), dim3(256), 0, s, theta, l, R, N, nfmax, G, \
+                       pf.pb, pf.ptr, pf.sum, pf.child, Bs)
+        if (K == 64 && one) PC_PF_WG(64, true);
+        else if (K == 64) PC_PF_WG(64, false);
+        else if (one) PC_PF_WG(128, true);
+        else PC_PF_WG(128, false);
+#undef PC_PF_WG
     }
 }
 

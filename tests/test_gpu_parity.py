@@ -145,6 +145,7 @@ def test_block_sparse_sum_layer(n_sets, M, K, keep, B):
 @pytest.mark.parametrize("make", [
     # long tied reductions at K = 128 (39 pairs x 3 chunks per parameter block): the two-tile parameter-flow kernel
     lambda: W.hmm(40, 256, 60, 128, 70, 41),
+    lambda: W.hmm(40, 128, 60, 64, 70, 45),                # the same at K = 64
     # K = 32, 40 pairs x 3 chunks: the two-tile per-wave kernel; the short form is what the other K = 32 cases take
     lambda: W.hmm(41, 64, 30, 32, 70, 42),
     # 256 categories, K = 64, B = 300: the input-layer flows go through two slabs of samples (256 + 64), some masked
