@@ -944,7 +944,9 @@ __global__ __launch_bounds__(256) void k_param_flow_small(const float *__restric
 //   * the chunks follow one another without software pipelining: the loop needs 75-150 registers, so 3-6 waves
 //     share a SIMD and hide each other's waits.  (A pipelined version -- two operand sets, theta of chunk c+1
 //     staged during the arithmetic of chunk c, 190-230 registers, two waves per SIMD -- was slower in every
-//     configuration measured, and so was prefetching only the next theta sub-block.)
+//     configuration measured, and so was prefetching only the next theta sub-block.)  The exception is a launch
+//     too small to put more than one wave on a SIMD (the top layers of a deep narrow circuit, a root): there the
+//     PF instantiation requests the next chunk before it works on the current one.
 //   forward : value = l (log-prob residual) + (R_child - R_sum); the chunk maximum is taken in registers
 //   backward: value = N (log F - l of the parent) + (R_child - R_parent); the block maximum is nfmax
 // Values are shifted by the running per-sample maximum, exponentiated in registers and multiplied on
@@ -958,7 +960,7 @@ __global__ __launch_bounds__(256) void k_param_flow_small(const float *__restric
 // buffer descriptor of the main-loop loads: raw (stride 0), 2 GiB window from the chunk's base, 32-bit data format
 #define PC_BUF_RANGE 0x7fffffff
 #define PC_BUF_FLAGS 0x00020000
-template <int K, int RT, int SPLIT, bool BWD, bool MULTI>
+template <int K, int RT, int SPLIT, bool BWD, bool MULTI, bool PF>
 __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ theta, float *__restrict__ l,
                                                      float *__restrict__ R, const float *__restrict__ N,
                                                      const float *__restrict__ nfmax, float *__restrict__ F,
@@ -1028,9 +1030,11 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
     // All loads of the loop are buffer loads: a wave-uniform descriptor per chunk (base = first row of the chunk), a
     // loop-invariant per-lane byte offset and a compile-time scalar offset, so they need no vector address
     // arithmetic (the vector ALU issues instead of the matrix cores, not beside them).
-    floatx4 th[BWD ? 1 : NF4];
-    float ar[NQ][RT], v[NQ];
-    float rb = 0.0f, bm = PC_NEG_INF;
+    struct Operands {
+        floatx4 th[BWD ? 1 : NF4];
+        float ar[NQ][RT], v[NQ];
+        float rb, bm;
+    };
     const float *vsrc = BWD ? N : l;
     int voff[4];                                                        // neighbour values: rows 0-3 of a group of 8 rows
 #pragma unroll
@@ -1042,67 +1046,68 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
     const int toff = BWD ? ((4 * half) * K + l32) * 4 : ((lane / (KC / 4)) * K + (lane % (KC / 4)) * 4) * 4;
 
     float sh2 = 0.0f;
-    for (int c = sp; c < n_chunks; c += SPLIT) {
+    // loads of chunk c into an operand set (nothing is computed on the loaded values here: any arithmetic would wait)
+    auto load_chunk = [&](int c, Operands &o) {
         const int j = c / CPB, kc = c % CPB;
-        // ---- loads of the chunk (nothing is computed on the loaded values here: any arithmetic would wait) ----
-        {
-            const int32_t ps = row_par[j];
-            const float *tb = BWD ? theta + (int64_t)ps + (int64_t)(kc * KC) * K + sub * TM
-                                  : theta + (int64_t)ps + (int64_t)(sub * TM) * K + kc * KC;
-            const __amdgpu_buffer_rsrc_t rth = __builtin_amdgcn_make_buffer_rsrc((void *)tb, 0, PC_BUF_RANGE, PC_BUF_FLAGS);
-            if (BWD) {
-#pragma unroll
-                for (int q = 0; q < NQ; ++q)
-#pragma unroll
-                    for (int rt = 0; rt < RT; ++rt)
-                        ar[q][rt] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                                                  rth, toff, ((8 * (q / 4) + (q % 4)) * K + rt * 32) * 4, 0));
-            } else {
-#pragma unroll
-                for (int i = 0; i < NF4; ++i)                           // 64 lanes cover 64 / (KC / 4) rows
-                    th[i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(
-                                                            rth, toff, i * (64 / (KC / 4)) * K * 4, 0));
-            }
-            const int32_t ns = row_nbr[j];
-            const float *src = vsrc + (int64_t)(ns + kc * KC) * Bs;
-            const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void *)src, 0, PC_BUF_RANGE, PC_BUF_FLAGS);
+        const int32_t ps = row_par[j];
+        const float *tb = BWD ? theta + (int64_t)ps + (int64_t)(kc * KC) * K + sub * TM
+                              : theta + (int64_t)ps + (int64_t)(sub * TM) * K + kc * KC;
+        const __amdgpu_buffer_rsrc_t rth = __builtin_amdgcn_make_buffer_rsrc((void *)tb, 0, PC_BUF_RANGE, PC_BUF_FLAGS);
+        if (BWD) {
 #pragma unroll
             for (int q = 0; q < NQ; ++q)
-                v[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, voff[q % 4], soff[q / 4], 0));
-            rb = (R + (int64_t)(ns / K) * Bs)[(uint32_t)col];
-            if (BWD) bm = (nfmax + (int64_t)(ns / K) * Bs)[(uint32_t)col];
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+                    o.ar[q][rt] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                                                rth, toff, ((8 * (q / 4) + (q % 4)) * K + rt * 32) * 4, 0));
+        } else {
+#pragma unroll
+            for (int i = 0; i < NF4; ++i)                               // 64 lanes cover 64 / (KC / 4) rows
+                o.th[i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                          rth, toff, i * (64 / (KC / 4)) * K * 4, 0));
         }
+        const int32_t ns = row_nbr[j];
+        const float *src = vsrc + (int64_t)(ns + kc * KC) * Bs;
+        const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void *)src, 0, PC_BUF_RANGE, PC_BUF_FLAGS);
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+            o.v[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, voff[q % 4], soff[q / 4], 0));
+        o.rb = (R + (int64_t)(ns / K) * Bs)[(uint32_t)col];
+        if (BWD) o.bm = (nfmax + (int64_t)(ns / K) * Bs)[(uint32_t)col];
+    };
+    // arithmetic of a loaded chunk
+    auto run_chunk = [&](Operands &o) {
         // ---- forward: theta registers -> LDS tile -> A operands of the whole chunk ----
         if (!BWD) {
 #pragma unroll
             for (int i = 0; i < NF4; ++i) {
                 const int t = lane + i * 64;
-                *reinterpret_cast<floatx4 *>(buf + (t / (KC / 4)) * LDA + (t % (KC / 4)) * 4) = th[i];
+                *reinterpret_cast<floatx4 *>(buf + (t / (KC / 4)) * LDA + (t % (KC / 4)) * 4) = o.th[i];
             }
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
                 for (int g = 0; g < NQ / 4; ++g) {
                     const floatx4 a4 = *reinterpret_cast<const floatx4 *>(buf + (rt * 32 + l32) * LDA + 8 * g + 4 * half);
-                    ar[4 * g + 0][rt] = a4[0]; ar[4 * g + 1][rt] = a4[1];
-                    ar[4 * g + 2][rt] = a4[2]; ar[4 * g + 3][rt] = a4[3];
+                    o.ar[4 * g + 0][rt] = a4[0]; o.ar[4 * g + 1][rt] = a4[1];
+                    o.ar[4 * g + 2][rt] = a4[2]; o.ar[4 * g + 3][rt] = a4[3];
                 }
         }
         // ---- per-chunk scalars: reference, maximum, rescale of the accumulator; leaves sh2 for the exponentials ----
         {
             if (!BWD) {                                                 // a larger reference: m moves by an exact integer
-                const float Rn = fmaxf(Rrow, rb);
+                const float Rn = fmaxf(Rrow, o.rb);
                 m += Rrow - Rn;                                         // -inf stays -inf (rb is finite)
                 Rrow = Rn;
             }
-            const float d = BWD ? Rrow - rb : rb - Rrow;                // exact integer <= 0
+            const float d = BWD ? Rrow - o.rb : o.rb - Rrow;            // exact integer <= 0
             float cmax;
             if (BWD) {
-                cmax = bm + d;
+                cmax = o.bm + d;
             } else {
                 cmax = PC_NEG_INF;
 #pragma unroll
-                for (int q = 0; q < NQ; ++q) cmax = fmaxf(cmax, v[q]);
+                for (int q = 0; q < NQ; ++q) cmax = fmaxf(cmax, o.v[q]);
                 cmax = fmaxf(cmax, __shfl_xor(cmax, 32)) + d;
             }
             const float m_new = cmax > m + PC_LAZY ? cmax : m;          // -inf + 8 = -inf: the first finite chunk sets it
@@ -1121,10 +1126,30 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
         // ---- the chunk's MFMA steps ----
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(v[q], PC_LOG2E, sh2));
+            const float p = __builtin_amdgcn_exp2f(fmaf(o.v[q], PC_LOG2E, sh2));
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt) acc[rt] = __builtin_amdgcn_mfma_f32_32x32x2f32(ar[q][rt], p, acc[rt], 0, 0, 0);
+            for (int rt = 0; rt < RT; ++rt) acc[rt] = __builtin_amdgcn_mfma_f32_32x32x2f32(o.ar[q][rt], p, acc[rt], 0, 0, 0);
         }
+    };
+    if (!PF) {
+        Operands o;
+        for (int c = sp; c < n_chunks; c += SPLIT) {
+            load_chunk(c, o);
+            run_chunk(o);
+        }
+    } else {
+        // small launches (one wave per SIMD or fewer): nobody else hides this wave's loads, so the next chunk is
+        // requested before the current one is worked on -- two operand sets, chunks in pairs
+        Operands oa, ob;
+        if (sp < n_chunks) load_chunk(sp, oa);
+        int c = sp;
+        for (; c + SPLIT < n_chunks; c += 2 * SPLIT) {
+            load_chunk(c + SPLIT, ob);
+            run_chunk(oa);
+            if (c + 2 * SPLIT < n_chunks) load_chunk(c + 2 * SPLIT, oa);
+            run_chunk(ob);
+        }
+        if (c < n_chunks) run_chunk(oa);
     }
 
     if (SPLIT > 1) {                                                    // merge the partial sums of the SPLIT waves of a tile
@@ -1937,8 +1962,9 @@ void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const std
 // forward / backward-to-children: (K, rows per wave tile / 32, waves sharing one tile)
 #define PC_SUM_CASE(KK, RR, SS, BWD, ...)                                                                  \
     if (K == KK && rt == RR && split == SS) {                                                              \
-        if (gs.n > 1) hipLaunchKernelGGL((k_sum_mfma<KK, RR, SS, BWD, true>), __VA_ARGS__);                \
-        else hipLaunchKernelGGL((k_sum_mfma<KK, RR, SS, BWD, false>), __VA_ARGS__);                        \
+        if (gs.n > 1) hipLaunchKernelGGL((k_sum_mfma<KK, RR, SS, BWD, true, false>), __VA_ARGS__);         \
+        else if (RR == 1 && prefetch) hipLaunchKernelGGL((k_sum_mfma<KK, 1, SS, BWD, false, true>), __VA_ARGS__); \
+        else hipLaunchKernelGGL((k_sum_mfma<KK, RR, SS, BWD, false, false>), __VA_ARGS__);                 \
         break;                                                                                             \
     }
 #define PC_DISPATCH_SUM(BWD, ...)                                                                         \
@@ -1974,6 +2000,7 @@ void launch_sum_fwd(const float *theta, float *l, float *R, const std::vector<Gr
             pick_sum_shape(K, set_rows(gs), set_width(gs), Bs, rt, split);
             const int64_t cols_per_wg = 32 * (4 / split);
             dim3 grid((unsigned)(set_rows(gs) * (K / (32 * rt))), (unsigned)((Bs + cols_per_wg - 1) / cols_per_wg));
+            const bool prefetch = (int64_t)grid.x * grid.y * 4 <= 1024;    // at most one wave per SIMD
             PC_DISPATCH_SUM(false, grid, dim3(256), 0, s, theta, l, R, (const float *)nullptr, (const float *)nullptr,
                             (float *)nullptr, gs, Bs);
         }
@@ -2004,6 +2031,7 @@ void launch_sum_bwd_child(const float *theta, const float *l, const float *R, co
             pick_sum_shape(K, set_rows(gs), set_width(gs), Bs, rt, split);
             const int64_t cols_per_wg = 32 * (4 / split);
             dim3 grid((unsigned)(set_rows(gs) * (K / (32 * rt))), (unsigned)((Bs + cols_per_wg - 1) / cols_per_wg));
+            const bool prefetch = (int64_t)grid.x * grid.y * 4 <= 1024;    // at most one wave per SIMD
             PC_DISPATCH_SUM(true, grid, dim3(256), 0, s, theta, const_cast<float *>(l), const_cast<float *>(R), N, nfmax,
                             F, gs, Bs);
         }
