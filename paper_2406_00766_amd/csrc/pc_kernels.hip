@@ -960,7 +960,7 @@ __global__ __launch_bounds__(256) void k_param_flow_small(const float *__restric
 // buffer descriptor of the main-loop loads: raw (stride 0), 2 GiB window from the chunk's base, 32-bit data format
 #define PC_BUF_RANGE 0x7fffffff
 #define PC_BUF_FLAGS 0x00020000
-template <int K, int RT, int SPLIT, bool BWD, bool MULTI, bool PF>
+template <int K, int RT, int SPLIT, bool BWD, bool MULTI, int MODE>
 __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ theta, float *__restrict__ l,
                                                      float *__restrict__ R, const float *__restrict__ N,
                                                      const float *__restrict__ nfmax, float *__restrict__ F,
@@ -1046,6 +1046,7 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
     const int toff = BWD ? ((4 * half) * K + l32) * 4 : ((lane / (KC / 4)) * K + (lane % (KC / 4)) * 4) * 4;
 
     float sh2 = 0.0f;
+    constexpr bool PF = MODE == 1, WAIT_ALL = MODE == 2;                // schedules chosen by the launcher, see below
     // loads of chunk c into an operand set (nothing is computed on the loaded values here: any arithmetic would wait)
     auto load_chunk = [&](int c, Operands &o) {
         const int j = c / CPB, kc = c % CPB;
@@ -1124,6 +1125,14 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
             sh2 = dead ? 0.0f : (d - m_new + PC_UP) * PC_LOG2E;
         }
         // ---- the chunk's MFMA steps ----
+        // WAIT_ALL (backward, long reductions, at most two waves per SIMD): all loads of the chunk are waited for
+        // before the first MFMA.  Left alone, the compiler lets each MFMA wait for just its own operand, and the matrix
+        // pipe then runs in stop-and-go behind the loads for the whole chunk (config 4: 82 -> 78 us per layer).  With
+        // more waves per SIMD, or rows of a few chunks, it is faster the other way (dense 1024 x 1024 layers at K = 32:
+        // 2.2 against 3.4 ms), and a run-time test here costs as much as the wait itself -- hence an instantiation of
+        // its own.  (The forward kernel waits in any case: its
+        // chunk maximum needs every value.)  0x0F70 = vmcnt(0), the other counters at their maxima.
+        if (WAIT_ALL) __builtin_amdgcn_s_waitcnt(0x0F70);
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             const float p = __builtin_amdgcn_exp2f(fmaf(o.v[q], PC_LOG2E, sh2));
@@ -1962,9 +1971,10 @@ void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const std
 // forward / backward-to-children: (K, rows per wave tile / 32, waves sharing one tile)
 #define PC_SUM_CASE(KK, RR, SS, BWD, ...)                                                                  \
     if (K == KK && rt == RR && split == SS) {                                                              \
-        if (gs.n > 1) hipLaunchKernelGGL((k_sum_mfma<KK, RR, SS, BWD, true, false>), __VA_ARGS__);         \
-        else if (RR == 1 && prefetch) hipLaunchKernelGGL((k_sum_mfma<KK, 1, SS, BWD, false, true>), __VA_ARGS__); \
-        else hipLaunchKernelGGL((k_sum_mfma<KK, RR, SS, BWD, false, false>), __VA_ARGS__);                 \
+        if (gs.n > 1) hipLaunchKernelGGL((k_sum_mfma<KK, RR, SS, BWD, true, 0>), __VA_ARGS__);             \
+        else if (RR == 1 && prefetch) hipLaunchKernelGGL((k_sum_mfma<KK, 1, SS, BWD, false, 1>), __VA_ARGS__); \
+        else if (BWD && wait_all) hipLaunchKernelGGL((k_sum_mfma<KK, RR, SS, BWD, false, BWD ? 2 : 0>), __VA_ARGS__); \
+        else hipLaunchKernelGGL((k_sum_mfma<KK, RR, SS, BWD, false, 0>), __VA_ARGS__);                     \
         break;                                                                                             \
     }
 #define PC_DISPATCH_SUM(BWD, ...)                                                                         \
@@ -2001,6 +2011,9 @@ void launch_sum_fwd(const float *theta, float *l, float *R, const std::vector<Gr
             const int64_t cols_per_wg = 32 * (4 / split);
             dim3 grid((unsigned)(set_rows(gs) * (K / (32 * rt))), (unsigned)((Bs + cols_per_wg - 1) / cols_per_wg));
             const bool prefetch = (int64_t)grid.x * grid.y * 4 <= 1024;    // at most one wave per SIMD
+            // long reductions at two waves per SIMD or fewer: see WAIT_ALL in the kernel
+            const bool wait_all = (int64_t)set_width(gs) * (K / 32) >= 16 * split && (int64_t)grid.x * grid.y * 4 <= 2048;
+            (void)wait_all;
             PC_DISPATCH_SUM(false, grid, dim3(256), 0, s, theta, l, R, (const float *)nullptr, (const float *)nullptr,
                             (float *)nullptr, gs, Bs);
         }
@@ -2032,6 +2045,9 @@ void launch_sum_bwd_child(const float *theta, const float *l, const float *R, co
             const int64_t cols_per_wg = 32 * (4 / split);
             dim3 grid((unsigned)(set_rows(gs) * (K / (32 * rt))), (unsigned)((Bs + cols_per_wg - 1) / cols_per_wg));
             const bool prefetch = (int64_t)grid.x * grid.y * 4 <= 1024;    // at most one wave per SIMD
+            // long reductions at two waves per SIMD or fewer: see WAIT_ALL in the kernel
+            const bool wait_all = (int64_t)set_width(gs) * (K / 32) >= 16 * split && (int64_t)grid.x * grid.y * 4 <= 2048;
+            (void)wait_all;
             PC_DISPATCH_SUM(true, grid, dim3(256), 0, s, theta, const_cast<float *>(l), const_cast<float *>(R), N, nfmax,
                             F, gs, Bs);
         }
