@@ -150,6 +150,8 @@ def test_block_sparse_sum_layer(n_sets, M, K, keep, B):
     lambda: W.hmm(41, 64, 30, 32, 70, 42),
     # 256 categories, K = 64, B = 300: the input-layer flows go through two slabs of samples (256 + 64), some masked
     lambda: W.hclt(12, 128, 64, 300, 43, n_cats=256),
+    # 64 chunks per row, few waves: the backward instantiation that waits for a chunk's loads at once
+    lambda: W.hmm(3, 2048, 40, 128, 40, 46),
     # more than 1024 categories: per-sample atomics
     lambda: W.hmm(5, 64, 1500, 32, 130, 44, tokens="zipf"),
 ])
