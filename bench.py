@@ -22,9 +22,9 @@ PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 # HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, scale factor 1.00) from the rocprofv3 --pmc runs summarised in
 # profiles/cfg4_hmm_T32_H4096_B256_hbm_traffic.txt; counters cannot be read from inside this process.
 MEASURED_TRAFFIC = {
-    ("cfg4_hmm_T32_H4096_V50257_B256", "sum_bwd_child"): (50077.3 + 4096.0) * 1024,
+    ("cfg4_hmm_T32_H4096_V50257_B256", "sum_bwd_child"): (51565.5 + 4096.0) * 1024,
     ("cfg4_hmm_T32_H4096_V50257_B256", "sum_fwd"): (49346.5 + 4128.0) * 1024,
-    ("cfg4_hmm_T32_H4096_V50257_B256", "sum_bwd_param"): (996618.7 + 67584.0) * 1024,
+    ("cfg4_hmm_T32_H4096_V50257_B256", "sum_bwd_param"): (955890.3 + 67584.0) * 1024,
 }
 
 
