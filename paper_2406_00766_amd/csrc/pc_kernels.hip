@@ -1254,7 +1254,7 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restr
                                                             const float *__restrict__ nfmax, float *__restrict__ G,
                                                             const int32_t *__restrict__ pf_pb, const int32_t *__restrict__ pf_ptr,
                                                             const int32_t *__restrict__ pf_sum, const int32_t *__restrict__ pf_child,
-                                                            int32_t n_pb, int64_t Bs)
+                                                            int32_t n_pb, int32_t n_split, int64_t Bs)
 {
     constexpr int TMW = 32 * RT, TNW = 32 * CT;
     constexpr int TPB = (K / TMW) * (K / TNW);                          // wave tiles per parameter block
@@ -1268,7 +1268,11 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restr
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
-    const int64_t tile = (int64_t)blockIdx.x * 4 + wave;
+    // n_split > 1 (a handful of parameter blocks with many tied pairs each, e.g. a small HMM): the pairs of a block
+    // are dealt to n_split waves, which add their partial flows atomically
+    const int64_t wtile = (int64_t)blockIdx.x * 4 + wave;
+    const int64_t tile = wtile / n_split;
+    const int spl = (int)(wtile % n_split);
     const int pidx = (int)(tile / TPB), tin = (int)(tile % TPB);
     if (pidx >= n_pb) return;                                           // wave-uniform; no workgroup barrier below
     const int r0 = (tin / (K / TNW)) * TMW, c0 = (tin % (K / TNW)) * TNW;
@@ -1286,12 +1290,13 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restr
             for (int e = 0; e < 16; ++e) acc[rt][ct][e] = 0.0f;
 
     const int chunks_per_inst = (int)(Bs / 32);
-    const int n_chunks = (i1 - i0) * chunks_per_inst;
+    const int n_mine = i1 - i0 > spl ? (i1 - i0 - spl + n_split - 1) / n_split : 0;   // pairs spl, spl + n_split, ...
+    const int n_chunks = n_mine * chunks_per_inst;
     floatx4 nf_next[NA4], lc_next[NB4], mx_next, rs_next, rc_next;
 
 #define PC_ISSUE(C)                                                                                                   \
     do {                                                                                                              \
-        const int inst_ = i0 + (C) / chunks_per_inst;                                                                 \
+        const int inst_ = i0 + spl + ((C) / chunks_per_inst) * n_split;                                               \
         const int64_t b0_ = (int64_t)((C) % chunks_per_inst) * 32 + sc4;                                              \
         const int32_t ms_ = pf_sum[inst_], ns_ = pf_child[inst_];                                                     \
         const float *np_ = N + (int64_t)(ms_ + r0 + srow) * Bs + b0_;                                                 \
@@ -1367,7 +1372,10 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restr
                 const int i = r0 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
                 const int64_t at = (int64_t)pb + (int64_t)i * K + c0 + ct * 32 + l32;
                 const float th = theta[at];
-                if (th > 0.0f) G[at] += th * acc[rt][ct][e] * PC_SPLIT_OUT;   // theta = 0: no flow (and never 0 * inf)
+                if (th > 0.0f) {                                        // theta = 0: no flow (and never 0 * inf)
+                    if (n_split > 1) atomicAdd(G + at, th * acc[rt][ct][e] * PC_SPLIT_OUT);
+                    else G[at] += th * acc[rt][ct][e] * PC_SPLIT_OUT;
+                }
             }
 }
 
@@ -2098,12 +2106,16 @@ void launch_param_flow(const float *theta, const float *l, const float *R, const
         else PC_PF_SMALL(16, 8);
 #undef PC_PF_SMALL
     } else if (K == 32) {
-        if ((int64_t)pf.n_pairs * (Bs / 32) < 12 * (int64_t)pf.n_pb)    // fewer than 12 chunks per block on average
-            hipLaunchKernelGGL((k_param_flow_mfma<32, 1, 1, true>), dim3((unsigned)((pf.n_pb + 3) / 4)), dim3(256), 0, s, theta, l,
-                               R, N, nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, Bs);
+        // few blocks with many tied pairs each: split the pairs over waves until the launch has some 256 of them
+        const int64_t avg_pairs = pf.n_pairs / pf.n_pb;
+        const int n_split = (int)std::max<int64_t>(1, std::min<int64_t>(avg_pairs, 256 / pf.n_pb));
+        const unsigned wgs = (unsigned)(((int64_t)pf.n_pb * n_split + 3) / 4);
+        if ((int64_t)pf.n_pairs * (Bs / 32) < 12 * (int64_t)pf.n_pb * n_split)   // fewer than 12 chunks per wave on average
+            hipLaunchKernelGGL((k_param_flow_mfma<32, 1, 1, true>), dim3(wgs), dim3(256), 0, s, theta, l,
+                               R, N, nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, n_split, Bs);
         else
-            hipLaunchKernelGGL((k_param_flow_mfma<32, 1, 1, false>), dim3((unsigned)((pf.n_pb + 3) / 4)), dim3(256), 0, s, theta, l,
-                               R, N, nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, Bs);
+            hipLaunchKernelGGL((k_param_flow_mfma<32, 1, 1, false>), dim3(wgs), dim3(256), 0, s, theta, l,
+                               R, N, nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, n_split, Bs);
     } else {
         // short reductions (fewer than 64 chunks per block on average): the single-tile form
         const bool one = (int64_t)pf.n_pairs * (Bs / 32) < 64 * (int64_t)pf.n_pb;
