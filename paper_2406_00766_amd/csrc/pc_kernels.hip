@@ -1393,7 +1393,7 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
                                                                const float *__restrict__ nfmax, float *__restrict__ G,
                                                                const int32_t *__restrict__ pf_pb, const int32_t *__restrict__ pf_ptr,
                                                                const int32_t *__restrict__ pf_sum, const int32_t *__restrict__ pf_child,
-                                                               int64_t Bs)
+                                                               int32_t n_split, int64_t Bs)
 {
     constexpr int LD = 36;                                              // LDS row stride: 16-byte rows, b128 reads conflict-free
     constexpr int TILE = 2 * K * LD;                                    // K rows of factors from N, K rows from l
@@ -1410,7 +1410,9 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
     const int r0 = (wave >> 1) * Q, c0 = (wave & 1) * Q;                // this wave's quarter of the block
-    const int pidx = blockIdx.x;
+    // n_split > 1: the pairs of a block are dealt to n_split workgroups, which add their partial flows atomically
+    // (a handful of blocks with many tied pairs each would otherwise keep a handful of workgroups busy)
+    const int pidx = blockIdx.x / n_split, spl = blockIdx.x % n_split;
     const int32_t pb = pf_pb[pidx];
     const int i0 = pf_ptr[pidx], i1 = pf_ptr[pidx + 1];
     const int srow = threadIdx.x >> 3, sc4 = (threadIdx.x & 7) * 4;     // staging: 8 threads x 16 bytes per row, 32 rows per pass
@@ -1424,7 +1426,8 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
             for (int e = 0; e < 16; ++e) acc[rt][ct][e] = 0.0f;
 
     const int chunks_per_inst = (int)(Bs / 32);
-    const int n_chunks = (i1 - i0) * chunks_per_inst;
+    const int n_mine = i1 - i0 > spl ? (i1 - i0 - spl + n_split - 1) / n_split : 0;   // pairs spl, spl + n_split, ...
+    const int n_chunks = n_mine * chunks_per_inst;
     // two register sets of fetched tiles (loads two chunks ahead)
     floatx4 nfA[NL], lcA[NL], mxA, rsA, rcA;
     floatx4 nfB[NL], lcB[NL], mxB, rsB, rcB;
@@ -1435,7 +1438,7 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
 
 #define PC_ISSUE(C, NF, LC, MX, RS, RC)                                                                               \
     do {                                                                                                              \
-        const int inst_ = i0 + (C) / chunks_per_inst;                                                                 \
+        const int inst_ = i0 + spl + ((C) / chunks_per_inst) * n_split;                                               \
         const int64_t b0_ = (int64_t)((C) % chunks_per_inst) * 32;                                                    \
         const int32_t ms_ = pf_sum[inst_], ns_ = pf_child[inst_];                                                     \
         const __amdgpu_buffer_rsrc_t rn_ = __builtin_amdgcn_make_buffer_rsrc((void *)(N + (int64_t)ms_ * Bs + b0_), 0, PC_BUF_RANGE, PC_BUF_FLAGS); \
@@ -1545,7 +1548,9 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
             for (int e = 0; e < 16; ++e) {
                 const int i = r0 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
                 const int64_t at = (int64_t)pb + (int64_t)i * K + c0 + ct * 32 + l32;
-                G[at] = gv[e] + (thv[e] > 0.0f ? thv[e] * acc[rt][ct][e] * PC_SPLIT_OUT : 0.0f);
+                const float inc = thv[e] > 0.0f ? thv[e] * acc[rt][ct][e] * PC_SPLIT_OUT : 0.0f;
+                if (n_split > 1) { if (inc != 0.0f) atomicAdd(G + at, inc); }
+                else G[at] = gv[e] + inc;
             }
         }
 }
@@ -2117,11 +2122,13 @@ void launch_param_flow(const float *theta, const float *l, const float *R, const
             hipLaunchKernelGGL((k_param_flow_mfma<32, 1, 1, false>), dim3(wgs), dim3(256), 0, s, theta, l,
                                R, N, nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, pf.n_pb, n_split, Bs);
     } else {
-        // short reductions (fewer than 64 chunks per block on average): the single-tile form
-        const bool one = (int64_t)pf.n_pairs * (Bs / 32) < 64 * (int64_t)pf.n_pb;
+        // few blocks with many tied pairs each: split the pairs over workgroups until the launch has some 256 of them
+        const int n_split = (int)std::max<int64_t>(1, std::min<int64_t>(pf.n_pairs / pf.n_pb, 256 / pf.n_pb));
+        // short reductions (fewer than 64 chunks per workgroup on average): the single-tile form
+        const bool one = (int64_t)pf.n_pairs * (Bs / 32) < 64 * (int64_t)pf.n_pb * n_split;
 #define PC_PF_WG(KK, ONE)                                                                                           \
-    hipLaunchKernelGGL((k_param_flow_mfma_wg<KK, ONE>), dim3((unsigned)pf.n_pb), dim3(256), 0, s, theta, l, R, N, nfmax, G, \
-                       pf.pb, pf.ptr, pf.sum, pf.child, Bs)
+    hipLaunchKernelGGL((k_param_flow_mfma_wg<KK, ONE>), dim3((unsigned)pf.n_pb * n_split), dim3(256), 0, s, theta, l, R, N, \
+                       nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, n_split, Bs)
         if (K == 64 && one) PC_PF_WG(64, true);
         else if (K == 64) PC_PF_WG(64, false);
         else if (one) PC_PF_WG(128, true);
