@@ -24,7 +24,7 @@ PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 MEASURED_TRAFFIC = {
     ("cfg4_hmm_T32_H4096_V50257_B256", "sum_bwd_child"): (51565.5 + 4096.0) * 1024,
     ("cfg4_hmm_T32_H4096_V50257_B256", "sum_fwd"): (49346.5 + 4128.0) * 1024,
-    ("cfg4_hmm_T32_H4096_V50257_B256", "sum_bwd_param"): (955890.3 + 67584.0) * 1024,
+    ("cfg4_hmm_T32_H4096_V50257_B256", "sum_bwd_param"): (957554.9 + 67584.0) * 1024,
 }
 
 
