@@ -404,8 +404,11 @@ __device__ inline void block_col_max(float (&mx)[4], float (*red)[64], int wave,
 // instead of one per neighbour (small layers are latency-bound).  RPT = rows per thread = ceil(K / 16).
 
 // forward (Sec. 3): s = sum of the children's residuals; the column maximum over the K rows is rounded to an
-// integer and moved into R
-template <int RPT, int U, bool MULTI, int CL>
+// integer and moved into R.  ACC = double for rows with many children (a leaf product over 98 pixels adds up to
+// -540, where one fp32 step is 6e-5: summed in fp32 the residuals -- and with them every flow ratio p_c / p_n below --
+// would be off by up to 1e-3); the rounded maximum is subtracted in that precision, the small residual is stored as fp32.
+template <typename ACC> struct Acc4 { ACC x, y, z, w; };
+template <int RPT, int U, bool MULTI, int CL, typename ACC>
 __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *__restrict__ R, const GroupSet gs,
                                                   int32_t K, int64_t Bs)
 {
@@ -419,11 +422,11 @@ __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *
     const int32_t *row_nbr = gr.nbr + (int64_t)r * gr.width;
     const int32_t cnt = gr.aux[r] >> 8;
     const int32_t id = gr.ids[r];
-    float4 s[RPT];
+    Acc4<ACC> s[RPT];
     float mx[4] = {PC_NEG_INF, PC_NEG_INF, PC_NEG_INF, PC_NEG_INF};
     float4 rsum = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-    for (int i = 0; i < RPT; ++i) s[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i = 0; i < RPT; ++i) s[i] = Acc4<ACC>{0, 0, 0, 0};
     if (in) {
         for (int j0 = 0; j0 < cnt; j0 += U) {
             int32_t ch[U];
@@ -446,7 +449,7 @@ __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *
             for (int u = 0; u < U; ++u) {
 #pragma unroll
                 for (int i = 0; i < RPT; ++i) {
-                    s[i].x += t[u][i].x; s[i].y += t[u][i].y; s[i].z += t[u][i].z; s[i].w += t[u][i].w;
+                    s[i].x += (ACC)t[u][i].x; s[i].y += (ACC)t[u][i].y; s[i].z += (ACC)t[u][i].z; s[i].w += (ACC)t[u][i].w;
                 }
                 rsum.x += tr[u].x; rsum.y += tr[u].y; rsum.z += tr[u].z; rsum.w += tr[u].w;
             }
@@ -454,8 +457,8 @@ __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *
 #pragma unroll
         for (int i = 0; i < RPT; ++i)
             if (rg + RG * i < K) {
-                mx[0] = fmaxf(mx[0], s[i].x); mx[1] = fmaxf(mx[1], s[i].y);
-                mx[2] = fmaxf(mx[2], s[i].z); mx[3] = fmaxf(mx[3], s[i].w);
+                mx[0] = fmaxf(mx[0], (float)s[i].x); mx[1] = fmaxf(mx[1], (float)s[i].y);
+                mx[2] = fmaxf(mx[2], (float)s[i].z); mx[3] = fmaxf(mx[3], (float)s[i].w);
             }
     }
     block_col_max<CL>(mx, red, wave, cl);
@@ -469,7 +472,9 @@ __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *
     for (int i = 0; i < RPT; ++i) {
         const int k = rg + RG * i;
         if (k < K)
-            *reinterpret_cast<float4 *>(l + (int64_t)(id + k) * Bs + b) = make_float4(s[i].x - sh[0], s[i].y - sh[1], s[i].z - sh[2], s[i].w - sh[3]);
+            *reinterpret_cast<float4 *>(l + (int64_t)(id + k) * Bs + b) =
+                make_float4((float)(s[i].x - (ACC)sh[0]), (float)(s[i].y - (ACC)sh[1]), (float)(s[i].z - (ACC)sh[2]),
+                            (float)(s[i].w - (ACC)sh[3]));
     }
 }
 
@@ -674,13 +679,14 @@ __global__ __launch_bounds__(256) void k_sum_bwd_param_generic(const float *__re
         const float *nrow = N + (int64_t)(ids[r] + i) * Bs;
         const float *lrow = l + (int64_t)(ns + jj) * Bs;
         const float *Rs = R + (int64_t)(ids[r] / K) * Bs, *Rc = R + (int64_t)(ns / K) * Bs;
+        const float lth = __logf(th);                                   // inside the exponent: every term is an edge flow <= 1
         float acc = 0.0f;
         for (int b = 0; b < B; ++b) {
             const float nf = nrow[b], lc = lrow[b];
-            if (nf > PC_NEG_INF && lc > PC_NEG_INF) acc += __expf(nf + lc + (Rc[b] - Rs[b]));
+            if (nf > PC_NEG_INF && lc > PC_NEG_INF) acc += __expf(nf + lc + (Rc[b] - Rs[b]) + lth);
         }
         float *dst = G + (int64_t)ps + (int64_t)i * K + jj;
-        if (atomic) atomicAdd(dst, th * acc); else *dst += th * acc;
+        if (atomic) atomicAdd(dst, acc); else *dst += acc;
     }
 }
 
@@ -691,16 +697,28 @@ __global__ __launch_bounds__(256) void k_sum_bwd_param_generic(const float *__re
 // exponentials that Sec. 4.1 describes.  The K x K weights have workgroup-uniform addresses and ride in scalar
 // registers.  Linear-space accumulators with a running maximum, as in the MFMA kernels.
 // ------------------------------------------------------------------------------------------
-// Two-factor split of a parameter-flow term exp(log_nf_s + l_c) around a = max_s log_nf_s of the sum block:
-//   first factor  exp(log_nf_s - a + PC_SPLIT_A)  <= e^31
-//   second factor exp(l_c + a - PC_SPLIT_B)       <= e^32.5   (theta p_c / p_s <= 1 and theta >= FLT_MIN bound l_c + a by 87.3)
-// The products carry the fixed scale e^-(PC_SPLIT_B - PC_SPLIT_A) = e^-24, taken out again when the flow is written:
-// a sum over up to 2^21 samples times a thousand tied instances of terms as large as 1 / FLT_MIN then still fits
-// fp32, and a product is lost to underflow only when the term is below e^-30.
-#define PC_SPLIT_A 31.0f
-#define PC_SPLIT_B 55.0f
+// Two-factor split of a parameter-flow term exp(log_nf_s + l_c + dR) of one sample (dR = R_child - R_sum, an exact
+// integer).  With a = max_s log_nf_s over the sum block and g = a + dR -- the children are product blocks, whose
+// largest residual lies within +-0.5 of 0, so e^g is the size of the sample's largest term in this block pair, and
+// theta p_c / p_s <= 1 with theta >= FLT_MIN bounds g by 87.3 --
+//   first factor  exp(log_nf_s - a + s_b)            <= e^s_b
+//   second factor exp(l_c + g - s_b - PC_SPLIT_SCALE) <= e^(s_b + 0.5)     with s_b = (g - PC_SPLIT_SCALE) / 2 <= 31.65
+// Any per-sample shift is valid (it only moves scale between the factors); this one gives both factors the same
+// head-room, so each keeps 87 + s_b nats below its largest value.  The products carry the fixed scale e^-PC_SPLIT_SCALE,
+// taken out again when the flow is written: a sum over up to 2^21 samples times a thousand tied instances of terms
+// as large as 1 / FLT_MIN then still fits fp32.  What is lost: a product below FLT_MIN, i.e. a term below
+// FLT_MIN * e^PC_SPLIT_SCALE = 3.2e-28, and -- only in a sample with g > 23.4, which takes a weight below e^-23 on an
+// edge that nevertheless carries the block's largest flow ratio -- a term below e^(g / 2 - 75) whose factor underflows
+// (at most e^-31.4).  (A fixed first shift of 31 lost every term of a sample with g < -32, the common case of a block
+// pair that carries little flow.)
+#define PC_SPLIT_SCALE 24.0f
 #define PC_SPLIT_CAP 32.5f
 #define PC_SPLIT_OUT 2.6489122e10f   /* e^24 */
+__device__ inline float pc_split_shift(float g) { return fminf(fmaxf(0.5f * (g - PC_SPLIT_SCALE), -40.0f), 31.5f); }
+// flow += theta * sum * e^24 without leaving the fp32 range on the way: theta may be FLT_MIN (theta * sum would be
+// subnormal) and the sum as large as e^85 (sum * e^24 would overflow); theta * 2^40 is a normal number below 2^41 and
+// (theta * 2^40) * sum = flow * 2^5.4
+__device__ inline float pc_flow_out(float th, float sum) { return ((th * 0x1p+40f) * sum) * (PC_SPLIT_OUT * 0x1p-40f); }
 template <int K>
 __global__ __launch_bounds__(256) void k_sum_fwd_small(const float *__restrict__ theta, float *__restrict__ l,
                                                        float *__restrict__ R, const int32_t *__restrict__ ids,
@@ -873,8 +891,9 @@ __global__ __launch_bounds__(256) void k_param_flow_small(const float *__restric
                 const float mx = nfmax[(int64_t)(ms / K) * Bs + b];
                 const float dR = R[(int64_t)(ns / K) * Bs + b] - R[(int64_t)(ms / K) * Bs + b];
                 const bool live = mx > PC_NEG_INF;                      // dead sample: both factors 0
-                const float qa = live ? PC_SPLIT_A - mx : PC_NEG_INF;
-                const float qb = live ? mx + dR - PC_SPLIT_B : PC_NEG_INF;
+                const float sb = pc_split_shift(mx + dR);
+                const float qa = live ? sb - mx : PC_NEG_INF;
+                const float qb = live ? mx + dR - sb - PC_SPLIT_SCALE : PC_NEG_INF;
                 float fa[IG], fb[K];
 #pragma unroll
                 for (int i = 0; i < IG; ++i) fa[i] = __expf(N[(int64_t)(ms + ig + i) * Bs + b] + qa);
@@ -916,7 +935,7 @@ __global__ __launch_bounds__(256) void k_param_flow_small(const float *__restric
                 const int a = idx + e;                                  // = i * K + jj inside this pass
                 const int64_t at = (int64_t)pb + (int64_t)ig * K + a;
                 const float th = theta[at];
-                if (th > 0.0f) G[at] += th * acc[e] * PC_SPLIT_OUT;
+                if (th > 0.0f) G[at] += pc_flow_out(th, acc[e]);
             }
         }
     }
@@ -1239,9 +1258,8 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
 // atomics and without the per-layer accumulation that closes Alg. 3.
 //
 // Each term exp(log_nf_s + l_c) is split into two fp32 factors around a per-sample shift (any shift is
-// valid: it only moves scale between the factors) -- the balanced split defined with PC_SPLIT_A / PC_SPLIT_B
-// above.  Alg. 3 shifts by the block maximum a alone, which can drop products of order one when a weight is as
-// small as FLT_MIN.
+// valid: it only moves scale between the factors) -- the balanced split defined with PC_SPLIT_SCALE above.  Alg. 3
+// shifts by the block maximum a alone, which can drop products of order one when a weight is as small as FLT_MIN.
 //
 // Per chunk of 32 samples a wave fetches its TMW rows of N and TNW rows of l with 16-byte loads along
 // the batch, applies the exponentials, and stages both tiles in wave-private LDS (row stride 36 floats)
@@ -1315,8 +1333,10 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restr
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const bool live = mx_next[e] > PC_NEG_INF;
-            qa[e] = live ? (PC_SPLIT_A - mx_next[e]) * PC_LOG2E : PC_NEG_INF;              // dead sample: both factors 0
-            qb[e] = live ? (mx_next[e] + (rc_next[e] - rs_next[e]) - PC_SPLIT_B) * PC_LOG2E : PC_NEG_INF;
+            const float g = mx_next[e] + (rc_next[e] - rs_next[e]);
+            const float sb = pc_split_shift(g);
+            qa[e] = live ? (sb - mx_next[e]) * PC_LOG2E : PC_NEG_INF;                      // dead sample: both factors 0
+            qb[e] = live ? (g - sb - PC_SPLIT_SCALE) * PC_LOG2E : PC_NEG_INF;
         }
 #pragma unroll
         for (int i = 0; i < NA4; ++i) {
@@ -1373,8 +1393,8 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restr
                 const int64_t at = (int64_t)pb + (int64_t)i * K + c0 + ct * 32 + l32;
                 const float th = theta[at];
                 if (th > 0.0f) {                                        // theta = 0: no flow (and never 0 * inf)
-                    if (n_split > 1) atomicAdd(G + at, th * acc[rt][ct][e] * PC_SPLIT_OUT);
-                    else G[at] += th * acc[rt][ct][e] * PC_SPLIT_OUT;
+                    if (n_split > 1) atomicAdd(G + at, pc_flow_out(th, acc[rt][ct][e]));
+                    else G[at] += pc_flow_out(th, acc[rt][ct][e]);
                 }
             }
 }
@@ -1462,8 +1482,10 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
         floatx4 qa, qb;                                                 /* per-sample shifts in log2 units */         \
         _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                               \
             const bool live = MX[e] > PC_NEG_INF;                                                                     \
-            qa[e] = live ? (PC_SPLIT_A - MX[e]) * PC_LOG2E : PC_NEG_INF; /* dead sample: both factors 0 */            \
-            qb[e] = live ? (MX[e] + (RC[e] - RS[e]) - PC_SPLIT_B) * PC_LOG2E : PC_NEG_INF;                            \
+            const float g_ = MX[e] + (RC[e] - RS[e]);                                                                 \
+            const float sb_ = pc_split_shift(g_);                                                                     \
+            qa[e] = live ? (sb_ - MX[e]) * PC_LOG2E : PC_NEG_INF;       /* dead sample: both factors 0 */             \
+            qb[e] = live ? (g_ - sb_ - PC_SPLIT_SCALE) * PC_LOG2E : PC_NEG_INF;                                       \
         }                                                                                                             \
         _Pragma("unroll") for (int i = 0; i < NL; ++i) {                                                              \
             floatx4 q, p;                                                                                             \
@@ -1548,7 +1570,7 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
             for (int e = 0; e < 16; ++e) {
                 const int i = r0 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
                 const int64_t at = (int64_t)pb + (int64_t)i * K + c0 + ct * 32 + l32;
-                const float inc = thv[e] > 0.0f ? thv[e] * acc[rt][ct][e] * PC_SPLIT_OUT : 0.0f;
+                const float inc = thv[e] > 0.0f ? pc_flow_out(thv[e], acc[rt][ct][e]) : 0.0f;
                 if (n_split > 1) { if (inc != 0.0f) atomicAdd(G + at, inc); }
                 else G[at] = gv[e] + inc;
             }
@@ -1917,19 +1939,22 @@ void launch_input_bwd(const float *F, const int32_t *xT, const GroupDev &g, int3
 #define PC_DISPATCH_PROD_M(KERNEL, MULTI, ...)                                                             \
     do {                                                                                                   \
         if (narrow) {                                /* 32 columns per workgroup: twice the workgroups, half the rows per thread */ \
-            if (K <= 32) hipLaunchKernelGGL((KERNEL<1, 8, MULTI, 8>), __VA_ARGS__);                        \
-            else if (K <= 64) hipLaunchKernelGGL((KERNEL<2, 4, MULTI, 8>), __VA_ARGS__);                   \
-            else hipLaunchKernelGGL((KERNEL<4, 4, MULTI, 8>), __VA_ARGS__);                                \
-        } else if (K <= 16) hipLaunchKernelGGL((KERNEL<1, 8, MULTI, 16>), __VA_ARGS__);                    \
-        else if (K <= 32) hipLaunchKernelGGL((KERNEL<2, 4, MULTI, 16>), __VA_ARGS__);                      \
-        else if (K <= 64) hipLaunchKernelGGL((KERNEL<4, 4, MULTI, 16>), __VA_ARGS__);                      \
-        else hipLaunchKernelGGL((KERNEL<8, 2, MULTI, 16>), __VA_ARGS__);                                   \
+            if (K <= 32) hipLaunchKernelGGL((KERNEL(1, 8, MULTI, 8)), __VA_ARGS__);                        \
+            else if (K <= 64) hipLaunchKernelGGL((KERNEL(2, 4, MULTI, 8)), __VA_ARGS__);                   \
+            else hipLaunchKernelGGL((KERNEL(4, 4, MULTI, 8)), __VA_ARGS__);                                \
+        } else if (K <= 16) hipLaunchKernelGGL((KERNEL(1, 8, MULTI, 16)), __VA_ARGS__);                    \
+        else if (K <= 32) hipLaunchKernelGGL((KERNEL(2, 4, MULTI, 16)), __VA_ARGS__);                      \
+        else if (K <= 64) hipLaunchKernelGGL((KERNEL(4, 4, MULTI, 16)), __VA_ARGS__);                      \
+        else hipLaunchKernelGGL((KERNEL(8, 2, MULTI, 16)), __VA_ARGS__);                                   \
     } while (0)
 #define PC_DISPATCH_PROD(KERNEL, ...)                                                                      \
     do {                                                                                                   \
         if (gs.n > 1) PC_DISPATCH_PROD_M(KERNEL, true, __VA_ARGS__);                                       \
         else PC_DISPATCH_PROD_M(KERNEL, false, __VA_ARGS__);                                               \
     } while (0)
+#define PC_PROD_FWD_F32(RPT, U, MULTI, CL) k_prod_fwd<RPT, U, MULTI, CL, float>
+#define PC_PROD_FWD_F64(RPT, U, MULTI, CL) k_prod_fwd<RPT, U, MULTI, CL, double>
+#define PC_PROD_BWD(RPT, U, MULTI, CL) k_prod_bwd<RPT, U, MULTI, CL>
 // small launches (the deep narrow circuits) use 32-column workgroups
 static inline bool prod_narrow(const GroupSet &gs, int64_t Bs) { return (int64_t)gs.first[gs.n] * ((Bs + 63) / 64) < 1024; }
 
@@ -1966,7 +1991,9 @@ void launch_prod_fwd(float *l, float *R, const std::vector<GroupSet> &sets, int3
         Timed timed(KC_PROD_FWD, s);
         const bool narrow = prod_narrow(gs, Bs);
         dim3 grid((unsigned)set_rows(gs), (unsigned)(narrow ? (Bs + 31) / 32 : (Bs + 63) / 64));
-        PC_DISPATCH_PROD(k_prod_fwd, grid, dim3(256), 0, s, l, R, gs, K, Bs);
+        // rows with more than eight children (leaf products over many variables) are summed in double
+        if (set_width(gs) > 8) PC_DISPATCH_PROD(PC_PROD_FWD_F64, grid, dim3(256), 0, s, l, R, gs, K, Bs);
+        else PC_DISPATCH_PROD(PC_PROD_FWD_F32, grid, dim3(256), 0, s, l, R, gs, K, Bs);
     }
 }
 
@@ -1977,7 +2004,7 @@ void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const std
         Timed timed(KC_PROD_BWD, s);
         const bool narrow = prod_narrow(gs, Bs);
         dim3 grid((unsigned)set_rows(gs), (unsigned)(narrow ? (Bs + 31) / 32 : (Bs + 63) / 64));
-        PC_DISPATCH_PROD(k_prod_bwd, grid, dim3(256), 0, s, l, F, N, nfmax, gs, K, Bs);
+        PC_DISPATCH_PROD(PC_PROD_BWD, grid, dim3(256), 0, s, l, F, N, nfmax, gs, K, Bs);
     }
 }
 

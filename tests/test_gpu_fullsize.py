@@ -2,8 +2,10 @@
 
 The oracle is too slow for whole batches here, so (a) the first few samples of the full-batch GPU run are
 compared with the oracle node by node (log-probabilities and node flows are per-sample quantities), (b) the
-batch-summed parameter flows are checked through properties that hold at any size (flow conservation), and
-(c) a second GPU run on exactly the oracle's sub-batch is compared flow by flow.
+batch-summed parameter flows of that run are checked through a property that holds at any size (per sum node, the
+edge flows add up to the node's flow, Def. 2), (c) a second full-batch GPU run -- the same launch configuration, the
+one bench.py times -- on the oracle's n samples repeated B / n times is compared with B / n times the oracle's
+parameter and table flows, element by element, and (d) a GPU run on exactly the oracle's sub-batch likewise.
 """
 import numpy as np
 import pytest
@@ -13,7 +15,8 @@ torch = pytest.importorskip("torch")
 from oracle import pc_oracle as orc
 from paper_2406_00766_amd import binding as pcb
 from paper_2406_00766_amd import workloads as W
-from tests.test_gpu_parity import assert_device_tables_match_oracle, assert_flow_close, assert_logprob_close
+from tests.test_gpu_parity import (assert_device_tables_match_oracle, assert_flow_close, assert_logprob_close,
+                                   flow_floors)
 
 pytestmark = pytest.mark.gpu
 
@@ -52,35 +55,46 @@ def test_full_size_config(label, make, n):
     print(f"  oracle on the first {n} samples", flush=True)
     wb = w.with_batch(w.x[:n])
     ref_ll, ref_lp, ref_flow, ref_tf, ref_gf = orc.backward(wb, w.theta, w.tables, wb.x)
+    floors = flow_floors(wb, w.theta, {"lp": ref_lp, "flow": ref_flow}, n)
     assert_logprob_close(ll[:n], ref_ll, "ll")
     assert_logprob_close(lp_gpu, ref_lp, "node log-probs")
-    assert_flow_close(flow_gpu, ref_flow, "node flows")
+    assert_flow_close(flow_gpu, ref_flow, "node flows", floors["flow"])
     assert np.all(np.isfinite(ll))
 
     # properties of the batch-summed flows at the full batch size
     assert np.all(np.isfinite(tf)) and np.all(np.isfinite(gf)) and tf.min() >= 0 and gf.min() >= 0
     assert np.isclose(gf.sum(), B * w.n_vars, rtol=1e-4)
-    Fsum = F[K:, :B].double().sum(dim=1).cpu().numpy()                 # per node, summed over the batch
-    if w.meta["kind"] == "hmm":
-        H, T = w.meta["H"], w.meta["T"]
-        nb = H // K
-        assert np.isclose(tf[1:1 + nb * nb].sum(), B * (T - 1), rtol=1e-4)
-        assert np.isclose(tf[1 + nb * nb:].sum(), B, rtol=1e-4)
-    else:
-        rng = np.random.default_rng(0)
-        sums = np.nonzero(w.type == W.SUM)[0]
-        for u in rng.choice(sums, size=min(200, len(sums)), replace=False):
-            row = np.zeros(K)
-            for e in range(w.child_ptr[u], w.child_ptr[u + 1]):
-                row += tf[w.param_blk[e] + 1].sum(axis=1)
-            want = Fsum[u * K:(u + 1) * K]
-            assert np.allclose(row, want, rtol=1e-3, atol=1e-6 * max(want.max(), 1e-30))
+    Fsum = F[K:, :B].double().sum(dim=1).cpu().numpy().reshape(w.n_blocks, K)     # per node, summed over the batch
+    # sum blocks that share their parameter blocks (tied: the layers of an HMM) share the rows of the flow blocks:
+    # per row, the flows over all children add up to the summed node flows of the blocks that use the row
+    by_list = {}
+    for u in np.nonzero(w.type == W.SUM)[0]:
+        by_list.setdefault(tuple(w.param_blk[w.child_ptr[u]:w.child_ptr[u + 1]]), []).append(u)
+    keys = list(by_list)
+    rng = np.random.default_rng(0)
+    for i in rng.choice(len(keys), size=min(200, len(keys)), replace=False):
+        row = tf[np.asarray(keys[i]) + 1].sum(axis=(0, 2))
+        want = Fsum[by_list[keys[i]]].sum(axis=0)
+        assert np.allclose(row, want, rtol=5e-4, atol=1e-30), f"edge flows of sum blocks {by_list[keys[i]][:3]}.. do not add up"
+
+    reps = B // n
+    print(f"  gpu at full batch on the oracle's samples repeated {reps} times", flush=True)
+    c.theta_flow.zero_(); c.table_flow.zero_()
+    c.set_batch(np.tile(wb.x, (reps, 1)))
+    ll_t = c.forward().double().cpu().numpy()
+    c.backward()
+    torch.cuda.synchronize()
+    assert_logprob_close(ll_t, np.tile(ref_ll, reps), "ll of the repeated samples")
+    assert_flow_close(c.theta_flow.double().cpu().numpy().reshape(w.theta.shape), reps * ref_tf, "theta flows, full batch",
+                      reps * floors["theta_flow"])
+    assert_flow_close(c.table_flow.double().cpu().numpy().reshape(w.tables.shape), reps * ref_gf, "table flows, full batch",
+                      reps * floors["table_flow"])
 
     print("  gpu on the oracle's sub-batch", flush=True)
     c.theta_flow.zero_(); c.table_flow.zero_()
     c.set_batch(wb.x)
     c.forward(); c.backward()
     torch.cuda.synchronize()
-    assert_flow_close(c.theta_flow.double().cpu().numpy().reshape(w.theta.shape), ref_tf, "theta flows")
-    assert_flow_close(c.table_flow.double().cpu().numpy().reshape(w.tables.shape), ref_gf, "table flows")
+    assert_flow_close(c.theta_flow.double().cpu().numpy().reshape(w.theta.shape), ref_tf, "theta flows", floors["theta_flow"])
+    assert_flow_close(c.table_flow.double().cpu().numpy().reshape(w.tables.shape), ref_gf, "table flows", floors["table_flow"])
     c.close()
