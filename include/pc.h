@@ -144,6 +144,18 @@ pc_status pc_forward(pc_circuit *c, const float *theta, const float *tables, con
                      const uint8_t *mask, int32_t B, void *workspace, size_t workspace_bytes,
                      float *ll, void *stream);
 
+/* pc_forward for callers that cannot allocate device memory or pass a workspace along: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and same result as
+ * pc_forward, but the workspace is a fixed array of PC_STATIC_SCRATCH_BYTES inside the library's device image (every
+ * GPU the library runs on holds its copy until the process ends).  The call allocates nothing and records no timing
+ * events; it only enqueues kernels on `stream`.  PC_ERR_WORKSPACE if pc_workspace_bytes(c, B) exceeds
+ * PC_STATIC_SCRATCH_BYTES.  All calls on one GPU share that array: calls that overlap in time on one GPU (two streams,
+ * two threads, two circuits) race; the array keeps the last call's contents, and every call writes what it reads.  It
+ * leaves no state for pc_backward (which returns PC_ERR_STATE after it). */
+#define PC_STATIC_SCRATCH_BYTES (64u << 20)
+pc_status pc_forward_static(pc_circuit *c, const float *theta, const float *tables, const int32_t *x,
+                            const uint8_t *mask, int32_t B, float *ll, void *stream);
+
 /* Backward pass, Def. 2: node flows with F_root = 1, then
  *   theta_flow[param(n,c)] += sum_b theta_{n,c} p_c / p_n F_n        (Alg. 3; tied edges add up, App. A.3)
  *   table_flow[t][x_b,v][k] += sum_b F_n                              for observed variables

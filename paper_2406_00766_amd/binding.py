@@ -62,7 +62,7 @@ class pc_profile(C.Structure):
 
 EXPORTS = ["pc_compile", "pc_compile_host", "pc_destroy", "pc_last_error", "pc_get_sizes", "pc_get_layer",
            "pc_get_group", "pc_copy_group", "pc_workspace_layout", "pc_workspace_bytes", "pc_forward",
-           "pc_backward", "pc_em_step", "pc_profile_enable", "pc_profile_read", "pc_kernel_class_name"]
+           "pc_forward_static", "pc_backward", "pc_em_step", "pc_profile_enable", "pc_profile_read", "pc_kernel_class_name"]
 
 _lib = None
 
@@ -88,6 +88,8 @@ def lib():
         L.pc_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_size_t)]
         L.pc_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                  C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        L.pc_forward_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                        C.c_void_p, C.c_void_p]
         L.pc_backward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                   C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
         L.pc_em_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -204,6 +206,14 @@ def pc_workspace_bytes(handle: int, B: int) -> int:
 def pc_forward(handle, theta, tables, x, mask, B, workspace, workspace_bytes, ll, stream=None):
     _check(lib().pc_forward(handle, _ptr(theta), _ptr(tables), _ptr(x), _ptr(mask), int(B), _ptr(workspace),
                             int(workspace_bytes), _ptr(ll), _stream(stream)))
+
+
+PC_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def pc_forward_static(handle, theta, tables, x, mask, B, ll, stream=None):
+    _check(lib().pc_forward_static(handle, _ptr(theta), _ptr(tables), _ptr(x), _ptr(mask), int(B), _ptr(ll),
+                                   _stream(stream)))
 
 
 def pc_backward(handle, theta, tables, x, mask, B, workspace, workspace_bytes, theta_flow, table_flow, stream=None):

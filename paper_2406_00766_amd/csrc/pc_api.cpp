@@ -3,6 +3,7 @@
 
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 
@@ -24,6 +25,30 @@ static pc_status hip_fail(hipError_t e, const char *what)
     } while (0)
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Workspace of pc_forward_static: a fixed array in every GPU's memory, there from the moment the library is loaded
+// until the process ends.  In host code the name `scratch` is only a handle for hipGetSymbolAddress -- each device
+// holds its own copy at its own address, looked up once per device by static_scratch() and used from then on.
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[PC_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices] = {nullptr};
+
+static pc_status static_scratch(void **out)
+{
+    int device = -1;
+    PC_HIP(hipGetDevice(&device));
+    if (device < 0 || device >= kMaxDevices) return fail(PC_ERR_ARG, "device ordinal out of range");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void *ptr = nullptr;
+        PC_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));     // the current device's copy
+        if (!ptr) return fail(PC_ERR_HIP, "hipGetSymbolAddress returned a null address for the static scratch");
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return PC_OK;
+}
 
 // One arena for every table: sizes first, then pointers.  Host copies are uploaded where they exist; tables built
 // on the device only get their space.
@@ -70,7 +95,7 @@ pc_status upload(pc_circuit *c, hipStream_t stream)
 }
 
 struct ProfScope {                                   // installs the circuit's profiler for the calling thread
-    explicit ProfScope(pc_circuit *c) { set_profiler((Profiler *)c->profiler); }
+    explicit ProfScope(pc_circuit *c) { set_profiler(c ? (Profiler *)c->profiler : nullptr); }
     ~ProfScope() { set_profiler(nullptr); }
 };
 
@@ -242,9 +267,9 @@ pc_status pc_workspace_bytes(const pc_circuit *c, int32_t B, size_t *bytes)
     return st;
 }
 
-pc_status pc_forward(pc_circuit *c, const float *theta, const float *tables, const int32_t *x,
-                     const uint8_t *mask, int32_t B, void *workspace, size_t workspace_bytes,
-                     float *ll, void *stream)
+// The forward pass proper: argument checks, then kernels only.  `profiled` installs the circuit's per-launch timer.
+static pc_status forward_on(pc_circuit *c, const float *theta, const float *tables, const int32_t *x, const uint8_t *mask,
+                            int32_t B, void *workspace, size_t workspace_bytes, float *ll, hipStream_t s, bool profiled)
 {
     if (!c || !theta || !tables || !x || !workspace || !ll) return fail(PC_ERR_ARG, "NULL argument");
     if (!c->on_device) return fail(PC_ERR_STATE, "circuit was compiled without a device");
@@ -254,8 +279,7 @@ pc_status pc_forward(pc_circuit *c, const float *theta, const float *tables, con
         return fail(PC_ERR_ARG, "theta, tables and workspace must be 16-byte aligned");
     const Ws w = ws_layout(c, B);
     if (workspace_bytes < w.total) return fail(PC_ERR_WORKSPACE, "workspace smaller than pc_workspace_bytes");
-    hipStream_t s = (hipStream_t)stream;
-    ProfScope prof(c);
+    ProfScope prof(profiled ? c : nullptr);
     char *base = (char *)workspace;
     float *l = (float *)(base + w.l_off), *R = (float *)(base + w.r_off);
     int32_t *xT = (int32_t *)(base + w.xt_off);
@@ -278,9 +302,36 @@ pc_status pc_forward(pc_circuit *c, const float *theta, const float *tables, con
     }
     launch_readout(l, R, (int64_t)(c->root_block + 1) * K, (int64_t)c->root_block + 1, w.Bs, B, ll, s);
     PC_HIP(hipGetLastError());
+    return PC_OK;
+}
+
+pc_status pc_forward(pc_circuit *c, const float *theta, const float *tables, const int32_t *x,
+                     const uint8_t *mask, int32_t B, void *workspace, size_t workspace_bytes,
+                     float *ll, void *stream)
+{
+    pc_status st = forward_on(c, theta, tables, x, mask, B, workspace, workspace_bytes, ll, (hipStream_t)stream, true);
+    if (st != PC_OK) return st;
     c->fw_workspace = workspace; c->fw_theta = theta; c->fw_tables = tables; c->fw_x = x; c->fw_mask = mask;
     c->fw_B = B;
     return PC_OK;
+}
+
+pc_status pc_forward_static(pc_circuit *c, const float *theta, const float *tables, const int32_t *x,
+                            const uint8_t *mask, int32_t B, float *ll, void *stream)
+{
+    if (!c) return fail(PC_ERR_ARG, "NULL argument");
+    if (B < 1) return fail(PC_ERR_ARG, "B must be positive");
+    if (B > PC_MAX_BATCH) return fail(PC_ERR_TOO_LARGE, "more than PC_MAX_BATCH samples in one call");
+    const Ws w = ws_layout(c, B);
+    if (w.total > (size_t)PC_STATIC_SCRATCH_BYTES)
+        return fail(PC_ERR_WORKSPACE, "this circuit and batch need " + std::to_string(w.total) +
+                                          " bytes of workspace, more than the PC_STATIC_SCRATCH_BYTES = " +
+                                          std::to_string((size_t)PC_STATIC_SCRATCH_BYTES) + " of pc_forward_static");
+    void *ws = nullptr;
+    pc_status st = static_scratch(&ws);
+    if (st != PC_OK) return st;
+    // no per-launch timing here: the timer creates events
+    return forward_on(c, theta, tables, x, mask, B, ws, (size_t)PC_STATIC_SCRATCH_BYTES, ll, (hipStream_t)stream, false);
 }
 
 pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, const int32_t *x,
