@@ -19,40 +19,100 @@ if ROOT not in sys.path:
 PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak: 256 CU x 256 flop/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 
-# HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, scale factor 1.00) from the rocprofv3 --pmc runs summarised in
-# profiles/cfg4_hmm_T32_H4096_B256_hbm_traffic.txt; counters cannot be read from inside this process.
-MEASURED_TRAFFIC = {
-    ("cfg4_hmm_T32_H4096_V50257_B256", "sum_bwd_child"): (51565.5 + 4096.0) * 1024,
-    ("cfg4_hmm_T32_H4096_V50257_B256", "sum_fwd"): (49346.5 + 4128.0) * 1024,
-    ("cfg4_hmm_T32_H4096_V50257_B256", "sum_bwd_param"): (957554.9 + 67584.0) * 1024,
-}
+def longest_path_depth(w):
+    """Depth of every block (inputs 0, else 1 + the deepest child): the layering of Sec. 3, recomputed here only to
+    count bytes per launch (one launch per product layer)."""
+    import numpy as np
+    n = w.n_blocks
+    depth = np.zeros(n, dtype=np.int64)
+    n_par = np.bincount(w.child, minlength=n)
+    parents_ptr = np.concatenate([[0], np.cumsum(n_par)])
+    fill = parents_ptr[:-1].copy()
+    parents = np.empty(len(w.child), dtype=np.int64)
+    src = np.repeat(np.arange(n), np.diff(w.child_ptr))
+    for e, c in enumerate(w.child):
+        parents[fill[c]] = src[e]
+        fill[c] += 1
+    pending = np.diff(w.child_ptr).astype(np.int64)
+    ready = [u for u in range(n) if pending[u] == 0]
+    while ready:
+        u = ready.pop()
+        for p in parents[parents_ptr[u]:parents_ptr[u + 1]]:
+            depth[p] = max(depth[p], depth[u] + 1)
+            pending[p] -= 1
+            if pending[p] == 0:
+                ready.append(p)
+    return depth, parents_ptr, parents
 
 
 def algorithmic_work(w):
-    """Per-step algorithmic flops / bytes per kernel class (ideal-IO model of Sec. 3: every child value
-    read once per consumer block, every output written once; padded and pruned blocks not counted)."""
+    """Per-step algorithmic work per kernel class.
+
+    Sum kernels: 2 E_s B flops each.  HBM-bound kernels: the COMPULSORY HBM bytes of the ideal-IO model of Sec. 3
+    applied per launch -- every distinct row a launch needs is read from HBM once (a row read by several workgroups of
+    one launch is served by L2 after the first), every output row is written once.  The second figure, `per_consumer`,
+    charges a row once per block that reads it (what the L2 <-> CU side moves)."""
     import numpy as np
     from paper_2406_00766_amd import workloads as W
     K, B = w.K, w.B
     deg = np.diff(w.child_ptr)
     is_in, is_prod, is_sum = (w.type == W.INPUT), (w.type == W.PRODUCT), (w.type == W.SUM)
     n_par = np.bincount(w.child, minlength=w.n_blocks)
-    prod_children = np.zeros(w.n_blocks, dtype=bool)
-    for u in np.nonzero(is_prod)[0]:
-        prod_children[w.child[w.child_ptr[u]:w.child_ptr[u + 1]]] = True
+    depth, pptr, parents = longest_path_depth(w)
     Es = w.n_sum_edges()
-    row = K * B * 4                                   # bytes of one block row-slab
+    row = K * B * 4                                   # bytes of one block's rows
+    # product layers: one launch per depth
+    prod_fwd = prod_bwd = 0.0
+    prod_children = np.zeros(w.n_blocks, dtype=bool)
+    for d in np.unique(depth[is_prod]):
+        prods = np.nonzero(is_prod & (depth == d))[0]
+        ch = np.unique(np.concatenate([w.child[w.child_ptr[u]:w.child_ptr[u + 1]] for u in prods]))
+        prod_children[ch] = True
+        prod_fwd += (len(ch) + len(prods)) * row      # distinct child rows in, product rows out
+        # backward: parent flows in, child flows out; a child fed before by a deeper layer is read first; where the
+        # flow of a sum child becomes final its log-probabilities are read and log F - l is written as well
+        pd = [depth[parents[pptr[c]:pptr[c + 1]]] for c in ch]
+        not_first = sum(1 for x in pd if x.max() > d)
+        final_sum = sum(1 for c, x in zip(ch, pd) if is_sum[c] and x.min() == d)
+        prod_bwd += (len(prods) + len(ch) + not_first + 2 * final_sum) * row
+    # input layer: distinct (table, category) rows of K floats
+    in_blocks = np.nonzero(is_in)[0]
+    vars_of_table, cats_of_var = {}, {}
+    for t, v in zip(w.in_table[in_blocks].tolist(), w.in_var[in_blocks].tolist()):
+        vars_of_table.setdefault(t, set()).add(v)
+    n_tab_rows = 0
+    for t, vs in vars_of_table.items():
+        cats = set()
+        for v in vs:
+            if v not in cats_of_var:
+                cats_of_var[v] = set(np.unique(w.x[:, v]).tolist())
+            cats |= cats_of_var[v]
+        n_tab_rows += len(cats)
+    tab_bytes = n_tab_rows * K * 4                    # a table is [n_cats][K]: K floats per category that occurs
+    n_in = float(is_in.sum())
     work = {
-        "sum_fwd": ("TFLOP/s", 2.0 * Es * B),
-        "sum_bwd_child": ("TFLOP/s", 2.0 * Es * B),
-        "sum_bwd_param": ("TFLOP/s", 2.0 * Es * B),
-        "input_fwd": ("GB/s", float(is_in.sum()) * row * 2),
-        "input_bwd": ("GB/s", float(is_in.sum()) * row * 3),
-        "prod_fwd": ("GB/s", float((deg[is_prod] + 1).sum()) * row),
-        "prod_bwd": ("GB/s", float((n_par[prod_children] + 2).sum()) * row),
-        "lognf": ("GB/s", float(is_sum.sum()) * row * 3),
+        "sum_fwd": ("TFLOP/s", 2.0 * Es * B, None),
+        "sum_bwd_child": ("TFLOP/s", 2.0 * Es * B, None),
+        "sum_bwd_param": ("TFLOP/s", 2.0 * Es * B, None),
+        "input_fwd": ("GB/s", n_in * row + tab_bytes, n_in * row * 2),
+        "input_bwd": ("GB/s", n_in * row + 2 * tab_bytes, n_in * row * 3),
+        "prod_fwd": ("GB/s", prod_fwd, float((deg[is_prod] + 1).sum()) * row),
+        "prod_bwd": ("GB/s", prod_bwd, float((n_par[prod_children] + 2).sum()) * row),
     }
     return work, Es
+
+
+def measured_traffic(w, kernel_class):
+    """HBM bytes per launch of a kernel class from the committed rocprofv3 counter summary of this workload
+    (FETCH_SIZE + WRITE_SIZE), or None when there is none for this workload and block size."""
+    from paper_2406_00766_amd import profile_summary as ps
+    path = os.path.join(ROOT, "profiles", f"{w.name}_K{w.K}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None, None
+    head, per = ps.read_counters(path)
+    if head.get("workload") != w.name or head.get("K") != str(w.K) or kernel_class not in per:
+        return None, None
+    return per[kernel_class].get("hbm_bytes_per_launch"), os.path.relpath(path, ROOT)
 
 
 def main():
@@ -65,8 +125,6 @@ def main():
     ap.add_argument("--K", type=int, default=None, help="node block size (default per config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-em", action="store_true", help="skip the secondary timing that adds pc_em_step")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 256 MiB device-to-device copy kernel (scale reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
@@ -81,14 +139,6 @@ def main():
     w = W.rat_config(K=args.K, B=args.batch) if args.config == "rat" else W.config(int(args.config), K=args.K, B=args.batch)
     gen_s = time.time() - t0
     work, Es = algorithmic_work(w)
-
-    if args.calibrate_copy:                            # reads 256 MiB, writes 256 MiB: what FETCH_SIZE / WRITE_SIZE are scaled by
-        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
 
     t0 = time.time()
     c = pcb.Circuit(w, "cuda:0")
@@ -125,20 +175,30 @@ def main():
         ent = {"launches_per_step": launches / args.steps, "ms_per_step": ms / args.steps,
                "avg_launch_us": 1e3 * ms / launches}
         if name in work:
-            unit, amount = work[name]
+            unit, amount, per_consumer = work[name]
             rate = amount * args.steps / (ms * 1e-3)
             if unit == "TFLOP/s":
                 ent.update(bound="mfma", achieved=rate / 1e12, peak=PEAK_FP32_MFMA_TFLOPS, unit=unit,
                            frac=rate / 1e12 / PEAK_FP32_MFMA_TFLOPS, work_per_launch=amount * args.steps / launches)
             else:
                 ent.update(bound="hbm", achieved=rate / 1e9, peak=PEAK_HBM_GBS, unit=unit,
-                           frac=rate / 1e9 / PEAK_HBM_GBS, work_per_launch=amount * args.steps / launches)
+                           frac=rate / 1e9 / PEAK_HBM_GBS, work_per_launch=amount * args.steps / launches,
+                           per_consumer_gbs=per_consumer * args.steps / (ms * 1e-3) / 1e9)
         kernels[name] = ent
     dom = max((k for k in kernels if "bound" in kernels[k]), key=lambda k: kernels[k]["ms_per_step"])
     d = kernels[dom]
+    traffic, traffic_file = measured_traffic(w, dom)
     roofline = {"kernel": dom, "bound": d["bound"], "achieved": d["achieved"], "peak": d["peak"], "unit": d["unit"],
-                "frac": d["frac"], "traffic": MEASURED_TRAFFIC.get((w.name, dom)), "avg_launch_us": d["avg_launch_us"],
+                "frac": d["frac"], "traffic": traffic, "traffic_source": traffic_file, "avg_launch_us": d["avg_launch_us"],
                 "work_per_launch": d["work_per_launch"]}
+
+    # achievable peaks of this device beside the published ones: a plain streaming copy and a register-only MFMA loop
+    buf = torch.empty(2 * 256 * 1024 * 1024, dtype=torch.uint8, device="cuda:0")
+    half = buf.numel() // 2
+    measured_peak = {"hbm_copy_gbs": pcb.pc_measure_copy(buf[:half], buf[half:], half, 10),
+                     "mfma_f32_tflops": pcb.pc_measure_mfma_f32(buf, buf.numel(), 5),
+                     "how": "256 MiB device-to-device copy kernel (bytes read + written); v_mfma_f32_32x32x2_f32 loop, 2 waves per SIMD"}
+    del buf
 
     em = None
     if not args.no_em:
@@ -171,7 +231,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "structure": w.meta["kind"], "K": w.K, "batch": B, "sum_edges": Es,
                    "n_blocks": w.n_blocks, "n_layers": c.sizes.n_layers},
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "with_em_step": em,
+        "roofline": roofline, "measured_peak": measured_peak, "cpu_baseline": cpu, "kernels": kernels, "with_em_step": em,
         "compile_s": compile_s, "generate_s": gen_s,
     }
     print(json.dumps(out))

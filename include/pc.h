@@ -191,6 +191,15 @@ pc_status pc_profile_enable(pc_circuit *c, int32_t on);
 pc_status pc_profile_read(pc_circuit *c, pc_profile *out);
 const char *pc_kernel_class_name(int32_t cls);
 
+/* Achievable peaks of the device the calling thread has current, for quoting beside the published ones (measurement
+ * protocol).  Both time `reps` launches of a plain kernel with HIP events on `stream` and wait for them.
+ *   pc_measure_copy      16-byte streaming copy of `bytes` from src to dst (device, 16-byte aligned, not overlapping);
+ *                        *gb_per_s = (bytes read + bytes written) / time
+ *   pc_measure_mfma_f32  register-only loop of v_mfma_f32_32x32x2_f32 on every SIMD; `out` is a device buffer of at
+ *                        least 2 MiB that receives the accumulators; *tflops = multiply-add flops / time */
+pc_status pc_measure_copy(const void *src, void *dst, size_t bytes, int32_t reps, void *stream, double *gb_per_s);
+pc_status pc_measure_mfma_f32(void *out, size_t out_bytes, int32_t reps, void *stream, double *tflops);
+
 #ifdef __cplusplus
 }
 #endif

@@ -62,7 +62,8 @@ class pc_profile(C.Structure):
 
 EXPORTS = ["pc_compile", "pc_compile_host", "pc_destroy", "pc_last_error", "pc_get_sizes", "pc_get_layer",
            "pc_get_group", "pc_copy_group", "pc_workspace_layout", "pc_workspace_bytes", "pc_forward",
-           "pc_forward_static", "pc_backward", "pc_em_step", "pc_profile_enable", "pc_profile_read", "pc_kernel_class_name"]
+           "pc_forward_static", "pc_backward", "pc_em_step", "pc_profile_enable", "pc_profile_read", "pc_kernel_class_name",
+           "pc_measure_copy", "pc_measure_mfma_f32"]
 
 _lib = None
 
@@ -98,6 +99,8 @@ def lib():
         L.pc_profile_read.argtypes = [C.c_void_p, C.POINTER(pc_profile)]
         L.pc_kernel_class_name.argtypes = [C.c_int32]
         L.pc_kernel_class_name.restype = C.c_char_p
+        L.pc_measure_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
+        L.pc_measure_mfma_f32.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
         _lib = L
     return _lib
 
@@ -235,6 +238,20 @@ def pc_profile_read(handle: int) -> dict:
     p = pc_profile()
     _check(lib().pc_profile_read(handle, C.byref(p)))
     return {lib().pc_kernel_class_name(i).decode(): (int(p.launches[i]), float(p.ms[i])) for i in range(p.n_classes)}
+
+
+def pc_measure_copy(src, dst, nbytes: int, reps: int = 5, stream=None) -> float:
+    """GB/s (read + written) of a plain streaming copy between two device buffers."""
+    out = C.c_double()
+    _check(lib().pc_measure_copy(_ptr(src), _ptr(dst), int(nbytes), int(reps), _stream(stream), C.byref(out)))
+    return float(out.value)
+
+
+def pc_measure_mfma_f32(out_buf, out_bytes: int, reps: int = 5, stream=None) -> float:
+    """TFLOP/s of a register-only fp32 MFMA loop; out_buf: device buffer of at least 2 MiB."""
+    out = C.c_double()
+    _check(lib().pc_measure_mfma_f32(_ptr(out_buf), int(out_bytes), int(reps), _stream(stream), C.byref(out)))
+    return float(out.value)
 
 
 def compiled_tables(handle: int) -> list[dict]:
