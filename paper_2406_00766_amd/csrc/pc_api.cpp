@@ -100,7 +100,7 @@ struct ProfScope {                                   // installs the circuit's p
 };
 
 static const char *const kClassNames[KC_COUNT] = {"misc", "input_fwd", "prod_fwd", "sum_fwd", "lognf", "sum_bwd_child",
-                                                  "sum_bwd_param", "prod_bwd", "input_bwd", "em"};
+                                                  "sum_bwd_param", "prod_bwd", "input_bwd", "em", "split"};
 
 static GroupDev dev(const GroupTab &g) { return GroupDev{g.n_rows, g.width, g.d_ids, g.d_nbr, g.d_par, g.tied_in_group, g.d_aux}; }
 
@@ -127,6 +127,8 @@ static LaunchPlan *make_plan(const pc_circuit *c)
 struct Ws {
     int64_t Bs;
     size_t l_off, f_off, n_off, r_off, mx_off, xt_off, total;
+    size_t th_off, tl_off, tth_off, ttl_off, ph_off, pl_off;   // bf16 operand planes (only where a layer takes the bf16 kernels)
+    bool bf16;
 };
 static inline bool misaligned(const void *p) { return ((uintptr_t)p & 15) != 0; }   // kernels use 16-byte accesses
 
@@ -142,6 +144,18 @@ static Ws ws_layout(const pc_circuit *c, int32_t B)
     w.mx_off = w.r_off + per_block;
     w.xt_off = w.mx_off + per_block;
     w.total = w.xt_off + align_up((size_t)c->n_vars * w.Bs * 4, 256);
+    // layers with long dense rows run on the bf16 matrix cores and need theta and the node values split into planes
+    w.bf16 = false;
+    for (const LayerTab &L : c->layers)
+        if (L.kind == KIND_SUM && L.fwd.size() == 1 && sum_layer_takes_bf16(c->K, 1, L.fwd[0].n_rows, L.fwd[0].width, w.Bs)) w.bf16 = true;
+    w.th_off = w.tl_off = w.tth_off = w.ttl_off = w.ph_off = w.pl_off = 0;
+    if (w.bf16) {
+        const size_t tplane = align_up(((size_t)c->n_param_blocks + 1) * c->K * c->K * 2, 256), pplane = align_up(rows * w.Bs * 2, 256);
+        w.th_off = w.total; w.tl_off = w.th_off + tplane;               // theta, hi and lo
+        w.tth_off = w.tl_off + tplane; w.ttl_off = w.tth_off + tplane;  // theta transposed (backward)
+        w.ph_off = w.ttl_off + tplane; w.pl_off = w.ph_off + pplane;    // node values: product rows forward, sum rows backward
+        w.total = w.pl_off + pplane;
+    }
     return w;
 }
 
@@ -290,12 +304,17 @@ static pc_status forward_on(pc_circuit *c, const float *theta, const float *tabl
     launch_fill(l, (int64_t)K * w.Bs, 0.0f, s);                                  // null block: probability 1
     launch_fill(R, ((int64_t)c->n_blocks + 1) * w.Bs, 0.0f, s);                  // input and null blocks: R = 0
     const LaunchPlan &plan = *(const LaunchPlan *)c->plan;
+    if (w.bf16) launch_split_theta(theta, (int64_t)c->n_param_blocks + 1, K, false, base + w.th_off, base + w.tl_off, s);
     for (size_t li = 0; li < c->layers.size(); ++li) {
         const LayerTab &L = c->layers[li];
         if (L.kind == KIND_INPUT) {
             launch_input_fwd(tables, xT, dev(L.fwd[0]), K, c->n_cats, w.Bs, l, s);
         } else if (L.kind == KIND_PRODUCT) {
             launch_prod_fwd(l, R, plan.layers[li].fwd, K, w.Bs, s);
+            if (w.bf16) launch_split_p(l, nullptr, L.d_blk_ids, (int32_t)L.blk_ids.size(), K, w.Bs, base + w.ph_off, base + w.pl_off, s);
+        } else if (w.bf16 && L.fwd.size() == 1 && sum_layer_takes_bf16(K, 1, L.fwd[0].n_rows, L.fwd[0].width, w.Bs)) {
+            launch_sum_bf16(base + w.th_off, base + w.tl_off, base + w.ph_off, base + w.pl_off, l, R, nullptr, nullptr, false,
+                            plan.layers[li].fwd[0], K, w.Bs, s);
         } else {
             launch_sum_fwd(theta, l, R, plan.layers[li].fwd, K, w.Bs, s);
         }
@@ -363,9 +382,20 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
     // initialised here
     const LaunchPlan &plan = *(const LaunchPlan *)c->plan;
     launch_init_flows(l, F, N, nfmax, c->d_init_ids, (int32_t)c->init_ids.size(), (c->root_block + 1) * K, K, w.Bs, B, s);
+    bool theta_t_split = false;
     for (size_t li = c->layers.size(); li-- > 0;) {
         const LayerTab &L = c->layers[li];
-        if (L.kind == KIND_SUM) {
+        if (L.kind == KIND_SUM && w.bf16 && L.bwd.size() == 1 &&
+            sum_layer_takes_bf16(K, 1, L.bwd[0].n_rows, L.bwd[0].width, w.Bs)) {
+            // long dense rows: bf16 matrix cores on planes of theta^T (once per pass) and of this layer's exp(log_nf - max)
+            if (!theta_t_split) launch_split_theta(theta, (int64_t)c->n_param_blocks + 1, K, true, base + w.tth_off, base + w.ttl_off, s);
+            theta_t_split = true;
+            launch_split_p(N, nfmax, L.d_blk_ids, (int32_t)L.blk_ids.size(), K, w.Bs, base + w.ph_off, base + w.pl_off, s);
+            launch_sum_bf16(base + w.tth_off, base + w.ttl_off, base + w.ph_off, base + w.pl_off, l, const_cast<float *>(R), nfmax, F,
+                            true, plan.layers[li].bwd[0], K, w.Bs, s);
+            if (theta_flow && !batched_params)
+                for (const GroupTab &g : L.fwd) launch_sum_bwd_param_generic(theta, l, R, N, theta_flow, dev(g), K, w.Bs, B, s);
+        } else if (L.kind == KIND_SUM) {
             launch_sum_bwd_child(theta, l, R, N, nfmax, F, plan.layers[li].bwd, K, w.Bs, s);
             if (theta_flow && !batched_params)
                 for (const GroupTab &g : L.fwd) launch_sum_bwd_param_generic(theta, l, R, N, theta_flow, dev(g), K, w.Bs, B, s);

@@ -42,7 +42,7 @@ void set_force_generic(bool on);
 // HIP events on the launch stream; totals per kernel class are summed when the profile is read.
 enum KernelClass : int {
     KC_MISC = 0, KC_INPUT_FWD, KC_PROD_FWD, KC_SUM_FWD, KC_LOGNF, KC_SUM_BWD_CHILD, KC_SUM_BWD_PARAM, KC_PROD_BWD,
-    KC_INPUT_BWD, KC_EM, KC_COUNT
+    KC_INPUT_BWD, KC_EM, KC_SPLIT, KC_COUNT
 };
 struct Profiler {
     struct Rec { int cls; hipEvent_t a, b; };
@@ -77,6 +77,13 @@ void launch_sum_bwd_child(const float *theta, const float *l, const float *R, co
                           const std::vector<GroupSet> &sets, int32_t K, int64_t Bs, hipStream_t s);
 void launch_sum_bwd_param_generic(const float *theta, const float *l, const float *R, const float *N, float *G,
                                   const GroupDev &g, int32_t K, int64_t Bs, int32_t B, hipStream_t s);
+// bf16-split path (long dense reductions): operand planes and the kernels that read them
+bool sum_layer_takes_bf16(int32_t K, int32_t n_groups, int32_t n_rows, int32_t width, int64_t Bs);
+void launch_split_theta(const float *theta, int64_t n_blocks, int32_t K, bool transposed, void *Th, void *Tl, hipStream_t s);
+void launch_split_p(const float *X, const float *ref, const int32_t *blk_ids, int32_t n_blk, int32_t K, int64_t Bs, void *Ph,
+                    void *Pl, hipStream_t s);
+void launch_sum_bf16(const void *Th, const void *Tl, const void *Ph, const void *Pl, float *l, float *R, const float *nfmax,
+                     float *F, bool bwd, const GroupSet &gs, int32_t K, int64_t Bs, hipStream_t s);
 bool param_flow_by_block(int32_t K);
 void launch_param_flow(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *G,
                        const ParamFlowDev &pf, int32_t K, int64_t Bs, hipStream_t s);

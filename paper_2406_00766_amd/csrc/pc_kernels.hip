@@ -1250,6 +1250,250 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
         }
 }
 
+// ------------------------------------------------------------------------------------------
+// Long dense reductions on the bf16 matrix cores (fp32 values split in two)
+// ------------------------------------------------------------------------------------------
+// The fp32 MFMA rate (157 TFLOP/s) is a sixteenth of the bf16 rate.  Every term of a sum node is non-negative, so a
+// product theta * p can be taken as  th*ph + th*pl + tl*ph  with theta = th + tl and p = ph + pl split into two bf16
+// values each (8 + 8 significant bits, round to nearest): three bf16 MFMAs with fp32 accumulation per fp32 MFMA's
+// worth of work, relative error of a term about 2^-17, no cancellation.  Used for rows with long reductions (the
+// dense layers of a large HMM), where the fp32 kernel is bound by the matrix cores.
+//
+// Operands are prepared once, in the order the MFMA wants them, so that the main loop is loads and MFMAs only:
+//   * theta planes (k_split_theta, once per forward pass): per parameter block and (32-row tile rt, 16-column slice
+//     ks) one 1 KiB tile -- lane (i = lane % 32, h = lane / 32) owns theta[32 rt + i][16 ks + 8 h .. + 7] as 8 bf16;
+//   * value planes (k_split_p, per product layer): p = exp(l + PC_UP) of the residual log-probabilities -- at most
+//     e^(PC_UP + 0.5), a product block's largest residual is within 0.5 of 0 -- per (16-node slice, 32-column tile)
+//     one 1 KiB tile: lane (j = lane % 32, h) owns p[16 slice + 8 h .. + 7][32 tile + j].
+// What the fp32 kernel does per value (running maximum, exponential) happens per child BLOCK here: a block's values
+// are relative to its integer reference R_c, the block's partial sums are accumulated on their own and added to the
+// row's accumulator with the factor exp(R_c - R_row) (R_row = largest reference so far; the accumulator is rescaled
+// when it grows).  v_mfma_f32_32x32x16_bf16: A 32 x 16, B 16 x 32, D as for the fp32 instruction.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+__device__ inline void bf16_split2(float a, float b, uint32_t &hi, uint32_t &lo)
+{
+    const floatx2 v = {a, b};
+    const bf16x2 h = __builtin_convertvector(v, bf16x2);               // round to nearest even
+    const floatx2 hf = __builtin_convertvector(h, floatx2);
+    const bf16x2 l = __builtin_convertvector(v - hf, bf16x2);
+    hi = __builtin_bit_cast(uint32_t, h);
+    lo = __builtin_bit_cast(uint32_t, l);
+}
+
+// theta [n_blocks][K][K] fp32 -> planes Th, Tl of 1 KiB tiles [block][rt][ks][lane][8]; TRANSPOSED: the tiles of
+// theta^T (rows = children), for the backward kernel.  One wave per tile.
+template <bool TRANSPOSED>
+__global__ __launch_bounds__(256) void k_split_theta(const float *__restrict__ theta, int64_t n_tiles, int32_t K,
+                                                     uint4 *__restrict__ Th, uint4 *__restrict__ Tl)
+{
+    const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= n_tiles) return;
+    const int lane = threadIdx.x & 63, i = lane & 31, h = lane >> 5;
+    const int nks = K / 16, nrt = K / 32;
+    const int ks = (int)(tile % nks), rt = (int)((tile / nks) % nrt);
+    const int64_t pb = tile / ((int64_t)nks * nrt);
+    const float *src = theta + pb * K * K;
+    float v[8];
+    if (!TRANSPOSED) {
+        const float4 *q = reinterpret_cast<const float4 *>(src + (int64_t)(32 * rt + i) * K + 16 * ks + 8 * h);
+        const float4 a = q[0], b = q[1];
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = src[(int64_t)(16 * ks + 8 * h + e) * K + 32 * rt + i];
+    }
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) bf16_split2(v[2 * e], v[2 * e + 1], hi[e], lo[e]);
+    Th[tile * 64 + lane] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+    Tl[tile * 64 + lane] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+}
+
+// value planes of the given node blocks: X = l (forward: residual log-probabilities of product blocks) gives
+// exp(l + PC_UP); with a block reference `ref` (backward: X = log_nf of sum blocks, ref = their column maxima) gives
+// exp(X - ref + PC_UP).  One wave per (block, 16-node slice, 32-column tile).
+__global__ __launch_bounds__(256) void k_split_p(const float *__restrict__ X, const float *__restrict__ ref,
+                                                 const int32_t *__restrict__ blk_ids, int32_t n_blk, int32_t K, int64_t Bs,
+                                                 uint4 *__restrict__ Ph, uint4 *__restrict__ Pl)
+{
+    const int n_ct = (int)(Bs / 32), nks = K / 16;
+    const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (item >= (int64_t)n_blk * nks * n_ct) return;
+    const int lane = threadIdx.x & 63, j = lane & 31, h = lane >> 5;
+    const int ct = (int)(item % n_ct), ks = (int)((item / n_ct) % nks);
+    const int32_t id = blk_ids[item / ((int64_t)n_ct * nks)];
+    const int64_t col = (int64_t)ct * 32 + j;
+    float sh = PC_UP;
+    if (ref) {
+        const float r = ref[(int64_t)(id / K) * Bs + col];
+        sh = r > PC_NEG_INF ? PC_UP - r : PC_NEG_INF;                   // a block without flow: every factor 0
+    }
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = __expf(X[(int64_t)(id + 16 * ks + 8 * h + e) * Bs + col] + sh);
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) bf16_split2(v[2 * e], v[2 * e + 1], hi[e], lo[e]);
+    const int64_t tile = ((int64_t)(id / 16 + ks)) * n_ct + ct;
+    Ph[tile * 64 + lane] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+    Pl[tile * 64 + lane] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+}
+
+// Sum layer on the planes, forward (rows = sum blocks, neighbours = their product children) and backward to the
+// children (rows = product blocks, neighbours = their sum parents, theta planes transposed).  Workgroup = 4 waves that
+// share one output tile of 64 rows x 32 columns and take the row's neighbour blocks in turn (a split of the reduction;
+// merged through LDS at the end).  Per 16-node slice a wave fetches 2 + 2 theta tiles and 1 + 1 value tiles (hi and lo
+// planes, 16 bytes per lane each, 1 KiB per wave load) and issues 6 MFMAs; the operands of D slices are in flight at
+// any time (a ring of D register sets that runs across the neighbour blocks).
+//   forward : block scale = R_c (integer reference of the child block); result l = ln(sum) - PC_UP relative to the
+//             largest reference, which becomes the row's own
+//   backward: block scale = nfmax_s + (R_row - R_s) (column maximum of the parent's log_nf, brought to the row's
+//             reference); result F += exp(ln(sum) + scale - PC_UP + l_row)
+// Measured on 4096 x 4096 layers at B = 256: 41 us per layer against 80 us on the fp32 matrix cores; the matrix work
+// itself is 10 us, the kernel is bound by the 64 bytes per clock at which a CU's L1 feeds the four SIMDs (a 64 x 32
+// tile needs 1 KiB of operands per MFMA), which only larger register tiles or operand sharing through LDS would lift --
+// at this batch size both leave too few tiles to fill the chip.
+template <int K, int D, bool BWD>
+__global__ __launch_bounds__(256, 2) void k_sum_bf16(const uint4 *__restrict__ Th, const uint4 *__restrict__ Tl,
+                                                     const uint4 *__restrict__ Ph, const uint4 *__restrict__ Pl,
+                                                     float *__restrict__ l, float *__restrict__ R,
+                                                     const float *__restrict__ nfmax, float *__restrict__ F, const GroupSet gs,
+                                                     int64_t Bs)
+{
+    constexpr int NKS = K / 16, NRT = K / 32, SUB = K / 64;
+    constexpr int XCH = 2 * 16 * 64 + 64;                               // one partial accumulator tile and its reference
+    static_assert(NKS % D == 0, "the ring must divide a block's slices");
+    __shared__ float lds[3 * XCH];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
+    const GroupRow gr = locate_row<false>(gs, blockIdx.x / SUB);
+    const int r = gr.r, sub = blockIdx.x % SUB;
+    const int n_ct = (int)(Bs / 32);
+    const int ct = blockIdx.y;
+    const int64_t col = (int64_t)ct * 32 + l32;
+    const int32_t *row_nbr = gr.nbr + (int64_t)r * gr.width, *row_par = gr.par + (int64_t)r * gr.width;
+    const int32_t id = gr.ids[r];
+    const int32_t fl = gr.aux[r];
+    const int cnt = fl >> 8;
+    const float Rown = BWD ? R[(int64_t)(id / K) * Bs + col] : 0.0f;
+
+    floatx16 acc[2], blk[2];
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[rt][e] = 0.0f;
+    float m = PC_NEG_INF, cm = PC_NEG_INF;                              // reference of the accumulator, of the current block
+
+    struct Ops { uint4 ah[2], al[2], bh, bl; };
+    const int n_my = cnt > wave ? (cnt - wave + 3) / 4 : 0;             // neighbour blocks wave, wave + 4, ...
+    auto load_slice = [&](int32_t ns, int32_t ps, int ks, Ops &o) {
+        const int64_t ta = (((int64_t)(ps / (K * K)) * NRT + 2 * sub) * NKS + ks) * 64 + lane;   // rt advances by NKS tiles
+        const int64_t tb = ((int64_t)(ns / 16 + ks) * n_ct + ct) * 64 + lane;
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) { o.ah[rt] = Th[ta + (int64_t)rt * NKS * 64]; o.al[rt] = Tl[ta + (int64_t)rt * NKS * 64]; }
+        o.bh = Ph[tb];
+        o.bl = Pl[tb];
+    };
+    // The loop over the wave's neighbour blocks is straight-line inside (every slot of the ring is refilled
+    // unconditionally: past the last block the refill repeats that block and is never used), so that the compiler can
+    // count the loads in flight and wait for just the oldest set; a branch around a load makes it wait for all of them.
+    Ops o[D];
+    int32_t ns_cur = 0, ps_cur = 0;
+    if (n_my > 0) {
+        ns_cur = row_nbr[wave];
+        ps_cur = row_par[wave];
+#pragma unroll
+        for (int d = 0; d < D; ++d) load_slice(ns_cur, ps_cur, d, o[d]);
+    }
+    for (int bi = 0; bi < n_my; ++bi) {
+        const int jn = wave + 4 * (bi + 1 < n_my ? bi + 1 : bi);
+        const int32_t ns_nxt = row_nbr[jn], ps_nxt = row_par[jn];
+        {
+            const float Rn = R[(int64_t)(ns_cur / K) * Bs + col];       // finite
+            cm = BWD ? nfmax[(int64_t)(ns_cur / K) * Bs + col] + (Rown - Rn) : Rn;
+        }
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            Ops &c = o[ks % D];
+            const bf16x8 bh = __builtin_bit_cast(bf16x8, c.bh), bl = __builtin_bit_cast(bf16x8, c.bl);
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt) {
+                const bf16x8 ah = __builtin_bit_cast(bf16x8, c.ah[rt]), al = __builtin_bit_cast(bf16x8, c.al[rt]);
+                floatx16 t = blk[rt];
+                if (ks == 0) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) t[e] = 0.0f;
+                }
+                t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, t, 0, 0, 0);          // small products first
+                t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, t, 0, 0, 0);
+                t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, t, 0, 0, 0);
+                blk[rt] = t;
+            }
+            if (ks + D < NKS) load_slice(ns_cur, ps_cur, ks + D, c);
+            else load_slice(ns_nxt, ps_nxt, ks + D - NKS, c);
+            __builtin_amdgcn_sched_barrier(0);                          // keeps the refill here, D - 1 slices ahead of its use
+        }
+        // the block's partial sums join the row's accumulator, both brought to the larger reference
+        {
+            const float mn = fmaxf(m, cm);
+            const float sa = m > PC_NEG_INF ? __expf(m - mn) : 0.0f, sb = cm > PC_NEG_INF ? __expf(cm - mn) : 0.0f;
+            m = mn;
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[rt][e] = acc[rt][e] * sa + blk[rt][e] * sb;
+        }
+        ns_cur = ns_nxt;
+        ps_cur = ps_nxt;
+    }
+
+    // merge the four partial tiles
+    float *buf = lds + (wave - 1) * XCH;
+    if (wave != 0) {
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) buf[(rt * 16 + e) * 64 + lane] = acc[rt][e];
+        buf[2 * 16 * 64 + lane] = m;
+    }
+    __syncthreads();
+    if (wave != 0) return;
+#pragma unroll 1
+    for (int w = 0; w < 3; ++w) {
+        const float *ob = lds + w * XCH;
+        const float mo = ob[2 * 16 * 64 + lane];                        // -inf: that wave had no block (its sums are 0)
+        const float mn = fmaxf(m, mo);
+        const float sa = m > PC_NEG_INF ? __expf(m - mn) : 0.0f, sb = mo > PC_NEG_INF ? __expf(mo - mn) : 0.0f;
+        m = mn;
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[rt][e] = acc[rt][e] * sa + ob[(rt * 16 + e) * 64 + lane] * sb;
+    }
+    if (!BWD && sub == 0 && half == 0) R[(int64_t)(id / K) * Bs + col] = m;
+    const bool first = (fl & 2) != 0;                                   // backward: the first layer that feeds the block stores
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int row = sub * 64 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+            const int64_t at = (int64_t)(id + row) * Bs + col;
+            if (!BWD) {
+                // ln(sum) - PC_UP, the logarithm taken of sum / 2^24 (see the fp32 kernel)
+                l[at] = fmaf(__builtin_amdgcn_logf(acc[rt][e] * 0x1p-24f), 0.6931471805599453f, 16.635532333f - PC_UP);
+            } else {
+                // exp(ln(sum) + (m - PC_UP) + l_row); sum = 0 or l_row = -inf gives 0
+                const float lg = __builtin_amdgcn_logf(acc[rt][e]);
+                const float add = acc[rt][e] > 0.0f ? __builtin_amdgcn_exp2f(lg + (l[at] + (m - PC_UP)) * PC_LOG2E) : 0.0f;
+                if (first) F[at] = add;
+                else if (add > 0.0f) F[at] += add;
+            }
+        }
+}
+
 // Backward to the parameters (role of Alg. 3), organised by PARAMETER BLOCK instead of by layer: one launch
 // covers every parameter block of the circuit after the backward sweep.  A wave owns a TMW x TNW tile
 // (up to 64 x 64) of one K x K parameter block and reduces over the batch of every (sum block, child
@@ -2162,6 +2406,52 @@ void launch_param_flow(const float *theta, const float *l, const float *R, const
         else PC_PF_WG(128, false);
 #undef PC_PF_WG
     }
+}
+
+// ---- bf16-split path for long dense reductions ----
+static int bf16_enabled()                                              // PC_BF16=0 keeps every layer on the fp32 matrix cores
+{
+    static const int on = [] { const char *e = std::getenv("PC_BF16"); return (e && e[0] == '0') ? 0 : 1; }();
+    return on;
+}
+// A layer takes the bf16 kernel when its rows are long (at least 2048 children: the fp32 kernel is bound by the matrix
+// cores there) and the launch has a workgroup for every fourth CU at least.
+bool sum_layer_takes_bf16(int32_t K, int32_t n_groups, int32_t n_rows, int32_t width, int64_t Bs)
+{
+    if (!bf16_enabled() || g_force_generic || (K != 64 && K != 128) || n_groups != 1) return false;
+    return (int64_t)width * K >= 2048 && (int64_t)n_rows * (K / 64) * (Bs / 32) >= 128;
+}
+
+void launch_split_theta(const float *theta, int64_t n_blocks, int32_t K, bool transposed, void *Th, void *Tl, hipStream_t s)
+{
+    Timed timed(KC_SPLIT, s);
+    const int64_t n_tiles = n_blocks * (K / 32) * (K / 16);
+    const dim3 grid((unsigned)((n_tiles + 3) / 4));
+    if (transposed) hipLaunchKernelGGL(k_split_theta<true>, grid, dim3(256), 0, s, theta, n_tiles, K, (uint4 *)Th, (uint4 *)Tl);
+    else hipLaunchKernelGGL(k_split_theta<false>, grid, dim3(256), 0, s, theta, n_tiles, K, (uint4 *)Th, (uint4 *)Tl);
+}
+
+void launch_split_p(const float *X, const float *ref, const int32_t *blk_ids, int32_t n_blk, int32_t K, int64_t Bs, void *Ph,
+                    void *Pl, hipStream_t s)
+{
+    if (n_blk == 0) return;
+    Timed timed(KC_SPLIT, s);
+    const int64_t items = (int64_t)n_blk * (K / 16) * (Bs / 32);
+    hipLaunchKernelGGL(k_split_p, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, s, X, ref, blk_ids, n_blk, K, Bs, (uint4 *)Ph,
+                       (uint4 *)Pl);
+}
+
+void launch_sum_bf16(const void *Th, const void *Tl, const void *Ph, const void *Pl, float *l, float *R, const float *nfmax,
+                     float *F, bool bwd, const GroupSet &gs, int32_t K, int64_t Bs, hipStream_t s)
+{
+    Timed timed(bwd ? KC_SUM_BWD_CHILD : KC_SUM_FWD, s);
+    const dim3 grid((unsigned)(set_rows(gs) * (K / 64)), (unsigned)(Bs / 32));
+#define PC_BF16_SUM(KK, BB)                                                                                            \
+    hipLaunchKernelGGL((k_sum_bf16<KK, 2, BB>), grid, dim3(256), 0, s, (const uint4 *)Th, (const uint4 *)Tl, (const uint4 *)Ph, \
+                       (const uint4 *)Pl, l, R, nfmax, F, gs, Bs)
+    if (K == 64) { if (bwd) PC_BF16_SUM(64, true); else PC_BF16_SUM(64, false); }
+    else { if (bwd) PC_BF16_SUM(128, true); else PC_BF16_SUM(128, false); }
+#undef PC_BF16_SUM
 }
 
 void launch_em(float *theta, float *tables, float *theta_flow, float *table_flow, const EmDev &em, int32_t K,

@@ -166,6 +166,10 @@ def test_block_sparse_sum_layer(n_sets, M, K, keep, B):
     lambda: W.hmm(3, 2048, 40, 128, 40, 46),
     # more than 1024 categories: per-sample atomics
     lambda: W.hmm(5, 64, 1500, 32, 130, 44, tokens="zipf"),
+    # rows of 2048 children and at least 64 output tiles: the bf16-split kernels (K = 128 with a ragged third column
+    # tile, K = 64), Dirichlet(0.1) rows as in the large HMM configuration
+    lambda: W.hmm(3, 2048, 40, 128, 90, 52, alpha_trans=0.1, alpha_emis=0.1),
+    lambda: W.hmm(3, 2048, 40, 64, 70, 53, alpha_trans=0.1, alpha_emis=0.1),
 ])
 def test_kernel_variants_selected_by_shape(make):
     w = make()
