@@ -1651,7 +1651,7 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma(const float *__restr
 // is double-buffered, so one barrier per chunk suffices, and the loads run two chunks ahead of the arithmetic -- a
 // chunk's matrix work (1.7 us) is shorter than a trip to HBM, which some of a chunk's loads always take; for short
 // reductions one tile and one register set, and many more waves per SIMD.
-template <int K, bool ONE>
+template <int K, bool ONE, bool BF>
 __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__restrict__ theta, const float *__restrict__ l,
                                                                const float *__restrict__ R, const float *__restrict__ N,
                                                                const float *__restrict__ nfmax, float *__restrict__ G,
@@ -1660,8 +1660,14 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
                                                                int32_t n_split, int64_t Bs)
 {
     constexpr int LD = 36;                                              // LDS row stride: 16-byte rows, b128 reads conflict-free
-    constexpr int TILE = 2 * K * LD;                                    // K rows of factors from N, K rows from l
+    // BF (long reductions): the factors are split into hi / lo bf16 values when they are staged -- four planes (Q hi, Q
+    // lo, P hi, P lo) of K rows x 32 samples, row stride 80 bytes (16-byte reads of 16 consecutive rows hit distinct
+    // banks) -- and a product is qh*ph + qh*pl + ql*ph on v_mfma_f32_32x32x16_bf16: 24 MFMAs of 32 cycles per chunk and
+    // wave instead of 64 of 64 cycles; all terms are non-negative, relative error about 2^-17.
+    constexpr int LDB = 20;                                             // bf16 planes: row stride in dwords
+    constexpr int TILE = BF ? 4 * K * LDB : 2 * K * LD;                 // K rows of factors from N, K rows from l
     constexpr int Q = K / 2, QT = Q / 32;                               // a wave's quarter: Q x Q, QT x QT MFMA tiles
+    static_assert(!(BF && ONE), "the bf16 form exists for long reductions only");
     constexpr int NL = K / 32;                                          // 16-byte loads per thread, chunk and array
     static_assert(K == 64 || K == 128, "workgroup-shared parameter-flow kernel");
     // ONE (short reductions -- a parameter block used by one pair, B / 32 chunks -- and many small workgroups): one LDS
@@ -1762,6 +1768,57 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
         }                                                                                                             \
     } while (0)
 
+    // the same with the factors split into bf16 planes (BF)
+#define PC_STAGE_BF(T, NF, LC, MX, RS, RC)                                                                            \
+    do {                                                                                                              \
+        uint32_t *Qh_ = reinterpret_cast<uint32_t *>(lds) + (T) * TILE, *Ql_ = Qh_ + K * LDB, *Ph_ = Ql_ + K * LDB,   \
+                 *Pl_ = Ph_ + K * LDB;                                                                                \
+        floatx4 qa, qb;                                                                                               \
+        _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                               \
+            const bool live = MX[e] > PC_NEG_INF;                                                                     \
+            const float g_ = MX[e] + (RC[e] - RS[e]);                                                                 \
+            const float sb_ = pc_split_shift(g_);                                                                     \
+            qa[e] = live ? (sb_ - MX[e]) * PC_LOG2E : PC_NEG_INF;                                                     \
+            qb[e] = live ? (g_ - sb_ - PC_SPLIT_SCALE) * PC_LOG2E : PC_NEG_INF;                                       \
+        }                                                                                                             \
+        _Pragma("unroll") for (int i = 0; i < NL; ++i) {                                                              \
+            floatx4 q, p;                                                                                             \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                           \
+                q[e] = __builtin_amdgcn_exp2f(fmaf(NF[i][e], PC_LOG2E, qa[e]));                                       \
+                p[e] = __builtin_amdgcn_exp2f(fminf(fmaf(LC[i][e], PC_LOG2E, qb[e]), PC_SPLIT_CAP * PC_LOG2E));      \
+            }                                                                                                         \
+            uint32_t h0, l0, h1, l1;                                                                                  \
+            const int at_ = (32 * i + srow) * LDB + (sc4 >> 1);                                                       \
+            bf16_split2(q[0], q[1], h0, l0); bf16_split2(q[2], q[3], h1, l1);                                         \
+            *reinterpret_cast<uint2 *>(Qh_ + at_) = make_uint2(h0, h1);                                               \
+            *reinterpret_cast<uint2 *>(Ql_ + at_) = make_uint2(l0, l1);                                               \
+            bf16_split2(p[0], p[1], h0, l0); bf16_split2(p[2], p[3], h1, l1);                                         \
+            *reinterpret_cast<uint2 *>(Ph_ + at_) = make_uint2(h0, h1);                                               \
+            *reinterpret_cast<uint2 *>(Pl_ + at_) = make_uint2(l0, l1);                                               \
+        }                                                                                                             \
+    } while (0)
+#define PC_MATH_BF(T)                                                                                                 \
+    do {                                                                                                              \
+        const uint32_t *Qh_ = reinterpret_cast<const uint32_t *>(lds) + (T) * TILE, *Ql_ = Qh_ + K * LDB,             \
+                       *Ph_ = Ql_ + K * LDB, *Pl_ = Ph_ + K * LDB;                                                    \
+        _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) {                                                            \
+            bf16x8 ah[QT], al[QT], bh[QT], bl[QT];                                                                    \
+            _Pragma("unroll") for (int rt = 0; rt < QT; ++rt) {                                                       \
+                const int ra_ = (r0 + rt * 32 + l32) * LDB + 8 * ks + 4 * half, rb_ = (c0 + rt * 32 + l32) * LDB + 8 * ks + 4 * half; \
+                ah[rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(Qh_ + ra_));                     \
+                al[rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(Ql_ + ra_));                     \
+                bh[rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(Ph_ + rb_));                     \
+                bl[rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(Pl_ + rb_));                     \
+            }                                                                                                         \
+            _Pragma("unroll") for (int rt = 0; rt < QT; ++rt)                                                         \
+                _Pragma("unroll") for (int ct = 0; ct < QT; ++ct) {                                                   \
+                    acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[rt], bh[ct], acc[rt][ct], 0, 0, 0);      \
+                    acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rt], bl[ct], acc[rt][ct], 0, 0, 0);      \
+                    acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rt], bh[ct], acc[rt][ct], 0, 0, 0);      \
+                }                                                                                                     \
+        }                                                                                                             \
+    } while (0)
+
     // n_chunks is the same for all four waves, so every wave reaches every barrier
     if (ONE) {
         if (n_chunks > 0) PC_ISSUE(0, nfA, lcA, mxA, rsA, rcA);
@@ -1777,24 +1834,26 @@ __global__ __launch_bounds__(256, 2) void k_param_flow_mfma_wg(const float *__re
     if (n_chunks > 1) PC_ISSUE(1, nfB, lcB, mxB, rsB, rcB);
     int c = 0;
     for (; c + 1 < n_chunks; c += 2) {                                  // pairs of chunks; a last single chunk follows
-        PC_STAGE(0, nfA, lcA, mxA, rsA, rcA);
+        if (BF) PC_STAGE_BF(0, nfA, lcA, mxA, rsA, rcA); else PC_STAGE(0, nfA, lcA, mxA, rsA, rcA);
         if (c + 2 < n_chunks) PC_ISSUE(c + 2, nfA, lcA, mxA, rsA, rcA);
         __syncthreads();
-        PC_MATH(0);
-        PC_STAGE(1, nfB, lcB, mxB, rsB, rcB);
+        if (BF) PC_MATH_BF(0); else PC_MATH(0);
+        if (BF) PC_STAGE_BF(1, nfB, lcB, mxB, rsB, rcB); else PC_STAGE(1, nfB, lcB, mxB, rsB, rcB);
         if (c + 3 < n_chunks) PC_ISSUE(c + 3, nfB, lcB, mxB, rsB, rcB);
         __syncthreads();
-        PC_MATH(1);
+        if (BF) PC_MATH_BF(1); else PC_MATH(1);
     }
     if (c < n_chunks) {
-        PC_STAGE(0, nfA, lcA, mxA, rsA, rcA);
+        if (BF) PC_STAGE_BF(0, nfA, lcA, mxA, rsA, rcA); else PC_STAGE(0, nfA, lcA, mxA, rsA, rcA);
         __syncthreads();
-        PC_MATH(0);
+        if (BF) PC_MATH_BF(0); else PC_MATH(0);
     }
     }
 #undef PC_ISSUE
 #undef PC_STAGE
 #undef PC_MATH
+#undef PC_STAGE_BF
+#undef PC_MATH_BF
 
     // flows out: all loads of a 32 x 32 tile first, then the arithmetic, then the stores (a load between two stores
     // would be waited for on its own); theta = 0: no flow (and never 0 * inf)
@@ -2363,6 +2422,12 @@ void launch_sum_bwd_param_generic(const float *theta, const float *l, const floa
                        g.par, g.n_rows, g.width, K, Bs, B, g.tied ? 1 : 0);
 }
 
+static int bf16_enabled()                                              // PC_BF16=0 keeps every layer on the fp32 matrix cores
+{
+    static const int on = [] { const char *e = std::getenv("PC_BF16"); return (e && e[0] == '0') ? 0 : 1; }();
+    return on;
+}
+
 bool param_flow_by_block(int32_t K) { return use_mfma(K) || use_small(K); }
 
 void launch_param_flow(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *G,
@@ -2397,23 +2462,22 @@ void launch_param_flow(const float *theta, const float *l, const float *R, const
         const int n_split = (int)std::max<int64_t>(1, std::min<int64_t>(pf.n_pairs / pf.n_pb, 256 / pf.n_pb));
         // short reductions (fewer than 64 chunks per workgroup on average): the single-tile form
         const bool one = (int64_t)pf.n_pairs * (Bs / 32) < 64 * (int64_t)pf.n_pb * n_split;
-#define PC_PF_WG(KK, ONE)                                                                                           \
-    hipLaunchKernelGGL((k_param_flow_mfma_wg<KK, ONE>), dim3((unsigned)pf.n_pb * n_split), dim3(256), 0, s, theta, l, R, N, \
+#define PC_PF_WG(KK, ONE, BF)                                                                                       \
+    hipLaunchKernelGGL((k_param_flow_mfma_wg<KK, ONE, BF>), dim3((unsigned)pf.n_pb * n_split), dim3(256), 0, s, theta, l, R, N, \
                        nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, n_split, Bs)
-        if (K == 64 && one) PC_PF_WG(64, true);
-        else if (K == 64) PC_PF_WG(64, false);
-        else if (one) PC_PF_WG(128, true);
-        else PC_PF_WG(128, false);
+        // long reductions (128 chunks per workgroup or more: tied blocks of a large model): bf16-split products
+        const bool bf = bf16_enabled() && (int64_t)pf.n_pairs * (Bs / 32) >= 128 * (int64_t)pf.n_pb * n_split;
+        if (K == 64 && one) PC_PF_WG(64, true, false);
+        else if (K == 64 && bf) PC_PF_WG(64, false, true);
+        else if (K == 64) PC_PF_WG(64, false, false);
+        else if (one) PC_PF_WG(128, true, false);
+        else if (bf) PC_PF_WG(128, false, true);
+        else PC_PF_WG(128, false, false);
 #undef PC_PF_WG
     }
 }
 
 // ---- bf16-split path for long dense reductions ----
-static int bf16_enabled()                                              // PC_BF16=0 keeps every layer on the fp32 matrix cores
-{
-    static const int on = [] { const char *e = std::getenv("PC_BF16"); return (e && e[0] == '0') ? 0 : 1; }();
-    return on;
-}
 // A layer takes the bf16 kernel when its rows are long (at least 2048 children: the fp32 kernel is bound by the matrix
 // cores there) and the launch has a workgroup for every fourth CU at least.
 bool sum_layer_takes_bf16(int32_t K, int32_t n_groups, int32_t n_rows, int32_t width, int64_t Bs)

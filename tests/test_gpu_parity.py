@@ -202,6 +202,9 @@ def check_repeated(w, reps, mask=None):
     (lambda: W.hclt(6, 256, 128, 128, 49, n_cats=16), 16),          # K = 128, untied: 64 chunks per block
     (lambda: W.hmm(40, 256, 60, 128, 128, 50), 16),                 # K = 128, tied, pairs dealt to 26 workgroups: 64 chunks each
     (lambda: W.hmm(12, 1024, 200, 128, 100, 51, alpha_trans=0.1, alpha_emis=0.1, tokens="zipf"), 8),   # K = 128, 72 blocks, 3 workgroups each
+    # from 128 chunks per workgroup the products are bf16-split (the form the large HMM configuration runs)
+    (lambda: W.hmm(12, 1024, 200, 128, 100, 54, alpha_trans=0.1, alpha_emis=0.1, tokens="zipf"), 13),  # K = 128: 135 chunks
+    (lambda: W.hmm(40, 128, 60, 64, 32, 55), 127),                                                    # K = 64: 128 chunks
 ])
 def test_two_tile_parameter_flow_kernels(make, reps):
     w = make()
