@@ -186,6 +186,7 @@ typedef struct {
     int32_t n_classes;
     int64_t launches[PC_MAX_KERNEL_CLASSES];
     double ms[PC_MAX_KERNEL_CLASSES];
+    int64_t bf16_launches[PC_MAX_KERNEL_CLASSES];   /* of those, launches whose contraction ran as bf16-split products */
 } pc_profile;
 pc_status pc_profile_enable(pc_circuit *c, int32_t on);
 pc_status pc_profile_read(pc_circuit *c, pc_profile *out);

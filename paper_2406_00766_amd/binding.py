@@ -57,7 +57,8 @@ class pc_ws_layout(C.Structure):
 
 
 class pc_profile(C.Structure):
-    _fields_ = [("n_classes", C.c_int32), ("launches", C.c_int64 * 16), ("ms", C.c_double * 16)]
+    _fields_ = [("n_classes", C.c_int32), ("launches", C.c_int64 * 16), ("ms", C.c_double * 16),
+                ("bf16_launches", C.c_int64 * 16)]
 
 
 EXPORTS = ["pc_compile", "pc_compile_host", "pc_destroy", "pc_last_error", "pc_get_sizes", "pc_get_layer",
@@ -233,10 +234,14 @@ def pc_profile_enable(handle: int, on: bool):
     _check(lib().pc_profile_enable(handle, 1 if on else 0))
 
 
-def pc_profile_read(handle: int) -> dict:
-    """{class name: (launches, total ms)} since pc_profile_enable."""
+def pc_profile_read(handle: int, with_bf16: bool = False) -> dict:
+    """{class name: (launches, total ms)} since pc_profile_enable; with_bf16 adds the launches that ran as bf16-split
+    products as a third element."""
     p = pc_profile()
     _check(lib().pc_profile_read(handle, C.byref(p)))
+    if with_bf16:
+        return {lib().pc_kernel_class_name(i).decode(): (int(p.launches[i]), float(p.ms[i]), int(p.bf16_launches[i]))
+                for i in range(p.n_classes)}
     return {lib().pc_kernel_class_name(i).decode(): (int(p.launches[i]), float(p.ms[i])) for i in range(p.n_classes)}
 
 

@@ -106,7 +106,7 @@ static GroupDev dev(const GroupTab &g) { return GroupDev{g.n_rows, g.width, g.d_
 
 // Group sets of every layer, built once after the tables are on the device.
 struct LaunchPlan {
-    struct Layer { std::vector<GroupSet> fwd, bwd; };
+    struct Layer { std::vector<GroupSet> fwd, bwd; bool orphan_sum = false; };   // orphan_sum: a sum block of the layer has no parent
     std::vector<Layer> layers;
 };
 static LaunchPlan *make_plan(const pc_circuit *c)
@@ -120,6 +120,9 @@ static LaunchPlan *make_plan(const pc_circuit *c)
         for (const GroupTab &g : c->layers[li].bwd) b.push_back(dev(g));
         p->layers[li].fwd = make_group_sets(f);
         p->layers[li].bwd = make_group_sets(b);
+        if (c->layers[li].kind == KIND_SUM)
+            for (int32_t id : c->layers[li].blk_ids)
+                for (int32_t e : c->init_ids) if (e == id) p->layers[li].orphan_sum = true;
     }
     return p;
 }
@@ -310,8 +313,7 @@ static pc_status forward_on(pc_circuit *c, const float *theta, const float *tabl
         if (L.kind == KIND_INPUT) {
             launch_input_fwd(tables, xT, dev(L.fwd[0]), K, c->n_cats, w.Bs, l, s);
         } else if (L.kind == KIND_PRODUCT) {
-            launch_prod_fwd(l, R, plan.layers[li].fwd, K, w.Bs, s);
-            if (w.bf16) launch_split_p(l, nullptr, L.d_blk_ids, (int32_t)L.blk_ids.size(), K, w.Bs, base + w.ph_off, base + w.pl_off, s);
+            launch_prod_fwd(l, R, plan.layers[li].fwd, K, w.Bs, w.bf16 ? base + w.ph_off : nullptr, w.bf16 ? base + w.pl_off : nullptr, s);
         } else if (w.bf16 && L.fwd.size() == 1 && sum_layer_takes_bf16(K, 1, L.fwd[0].n_rows, L.fwd[0].width, w.Bs)) {
             launch_sum_bf16(base + w.th_off, base + w.tl_off, base + w.ph_off, base + w.pl_off, l, R, nullptr, nullptr, false,
                             plan.layers[li].fwd[0], K, w.Bs, s);
@@ -390,7 +392,9 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
             // long dense rows: bf16 matrix cores on planes of theta^T (once per pass) and of this layer's exp(log_nf - max)
             if (!theta_t_split) launch_split_theta(theta, (int64_t)c->n_param_blocks + 1, K, true, base + w.tth_off, base + w.ttl_off, s);
             theta_t_split = true;
-            launch_split_p(N, nfmax, L.d_blk_ids, (int32_t)L.blk_ids.size(), K, w.Bs, base + w.ph_off, base + w.pl_off, s);
+            // the planes of exp(log_nf - max) were written by the product layers that finished these blocks' flows; a
+            // block without parents (initialised by k_init_flows) has none, so such a layer splits here
+            if (plan.layers[li].orphan_sum) launch_split_p(N, nfmax, L.d_blk_ids, (int32_t)L.blk_ids.size(), K, w.Bs, base + w.ph_off, base + w.pl_off, s);
             launch_sum_bf16(base + w.tth_off, base + w.ttl_off, base + w.ph_off, base + w.pl_off, l, const_cast<float *>(R), nfmax, F,
                             true, plan.layers[li].bwd[0], K, w.Bs, s);
             if (theta_flow && !batched_params)
@@ -400,7 +404,7 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
             if (theta_flow && !batched_params)
                 for (const GroupTab &g : L.fwd) launch_sum_bwd_param_generic(theta, l, R, N, theta_flow, dev(g), K, w.Bs, B, s);
         } else if (L.kind == KIND_PRODUCT) {
-            launch_prod_bwd(l, F, N, nfmax, plan.layers[li].bwd, K, w.Bs, s);
+            launch_prod_bwd(l, F, N, nfmax, plan.layers[li].bwd, K, w.Bs, w.bf16 ? base + w.ph_off : nullptr, w.bf16 ? base + w.pl_off : nullptr, s);
         } else if (table_flow) {
             launch_input_bwd(F, xT, dev(L.fwd[0]), K, c->n_cats, w.Bs, table_flow, s);
         }
@@ -448,6 +452,7 @@ pc_status pc_profile_read(pc_circuit *c, pc_profile *out)
     for (int k = 0; k < PC_MAX_KERNEL_CLASSES; ++k) {
         out->launches[k] = k < KC_COUNT ? c->prof_launches[k] : 0;
         out->ms[k] = k < KC_COUNT ? c->prof_ms[k] : 0.0;
+        out->bf16_launches[k] = (c->profiler && k < KC_COUNT) ? ((Profiler *)c->profiler)->bf16_launches[k] : 0;
     }
     PC_HIP(hipGetLastError());
     return PC_OK;

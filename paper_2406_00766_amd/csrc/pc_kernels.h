@@ -47,6 +47,7 @@ enum KernelClass : int {
 struct Profiler {
     struct Rec { int cls; hipEvent_t a, b; };
     std::vector<Rec> recs;
+    int64_t bf16_launches[16] = {0};                    // per class: launches that ran on the bf16 matrix cores
     std::vector<hipEvent_t> pool;
     hipEvent_t get();
     void collect(int64_t *launches, double *ms);      // waits for the recorded events, adds to the totals
@@ -68,9 +69,10 @@ void launch_input_bwd(const float *F, const int32_t *xT, const GroupDev &g, int3
 // The four layer launchers take all table groups of the layer, packed into sets by make_group_sets: the groups of a
 // layer are independent of one another, and one launch covers a whole set.
 std::vector<GroupSet> make_group_sets(const std::vector<GroupDev> &groups);
-void launch_prod_fwd(float *l, float *R, const std::vector<GroupSet> &sets, int32_t K, int64_t Bs, hipStream_t s);
+// Ph / Pl non-null: the kernel also writes the bf16 value planes of its rows (see launch_split_p)
+void launch_prod_fwd(float *l, float *R, const std::vector<GroupSet> &sets, int32_t K, int64_t Bs, void *Ph, void *Pl, hipStream_t s);
 void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const std::vector<GroupSet> &sets, int32_t K,
-                     int64_t Bs, hipStream_t s);
+                     int64_t Bs, void *Ph, void *Pl, hipStream_t s);
 void launch_sum_fwd(const float *theta, float *l, float *R, const std::vector<GroupSet> &sets, int32_t K, int64_t Bs,
                     hipStream_t s);
 void launch_sum_bwd_child(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *F,

@@ -371,6 +371,39 @@ __device__ inline GroupRow locate_row(const GroupSet &gs, int row)
     return GroupRow{row - gs.first[g], gs.width[g], gs.ids[g], gs.nbr[g], gs.par[g], gs.aux[g]};
 }
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+__device__ inline void bf16_split2(float a, float b, uint32_t &hi, uint32_t &lo)
+{
+    const floatx2 v = {a, b};
+    const bf16x2 h = __builtin_convertvector(v, bf16x2);               // round to nearest even
+    const floatx2 hf = __builtin_convertvector(h, floatx2);
+    const bf16x2 l = __builtin_convertvector(v - hf, bf16x2);
+    hi = __builtin_bit_cast(uint32_t, h);
+    lo = __builtin_bit_cast(uint32_t, l);
+}
+
+// One 1 KiB tile of the value planes read by the bf16 sum kernels (see there): exp(X + sh) of 16 node rows x 32 columns,
+// split into hi and lo bf16 values; lane (j = lane % 32, h = lane / 32) owns rows 8 h .. 8 h + 7 of column j.  `sh` is
+// the lane's shift (per column), -inf for a column without flow.  row0 = first node row of the slice.
+__device__ inline void split_value_tile(const float *__restrict__ X, float sh, int64_t row0, int ct, int n_ct, int64_t Bs,
+                                        uint4 *__restrict__ Ph, uint4 *__restrict__ Pl, int lane)
+{
+    const int j = lane & 31, h = lane >> 5;
+    const int64_t col = (int64_t)ct * 32 + j;
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = __expf(X[(row0 + 8 * h + e) * Bs + col] + sh);
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) bf16_split2(v[2 * e], v[2 * e + 1], hi[e], lo[e]);
+    const int64_t tile = (row0 / 16) * n_ct + ct;
+    Ph[tile * 64 + lane] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+    Pl[tile * 64 + lane] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+}
+
 // ------------------------------------------------------------------------------------------
 // product layers: forward adds child log-probs (Sec. 3); backward adds parent flows (Def. 2)
 // ------------------------------------------------------------------------------------------
@@ -408,9 +441,9 @@ __device__ inline void block_col_max(float (&mx)[4], float (*red)[64], int wave,
 // -540, where one fp32 step is 6e-5: summed in fp32 the residuals -- and with them every flow ratio p_c / p_n below --
 // would be off by up to 1e-3); the rounded maximum is subtracted in that precision, the small residual is stored as fp32.
 template <typename ACC> struct Acc4 { ACC x, y, z, w; };
-template <int RPT, int U, bool MULTI, int CL, typename ACC>
+template <int RPT, int U, bool MULTI, int CL, typename ACC, bool PLANES>
 __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *__restrict__ R, const GroupSet gs,
-                                                  int32_t K, int64_t Bs)
+                                                  int32_t K, int64_t Bs, uint4 *__restrict__ Ph, uint4 *__restrict__ Pl)
 {
     __shared__ float red[4][64];
     const GroupRow gr = locate_row<MULTI>(gs, blockIdx.x);
@@ -462,19 +495,33 @@ __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *
             }
     }
     block_col_max<CL>(mx, red, wave, cl);
-    if (!in) return;
-    float sh[4];
+    if (!PLANES && !in) return;
+    if (in) {
+        float sh[4];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) sh[v] = mx[v] > PC_NEG_INF ? rintf(mx[v]) : 0.0f;
-    if (rg == 0)
-        *reinterpret_cast<float4 *>(R + (int64_t)(id / K) * Bs + b) = make_float4(rsum.x + sh[0], rsum.y + sh[1], rsum.z + sh[2], rsum.w + sh[3]);
+        for (int v = 0; v < 4; ++v) sh[v] = mx[v] > PC_NEG_INF ? rintf(mx[v]) : 0.0f;
+        if (rg == 0)
+            *reinterpret_cast<float4 *>(R + (int64_t)(id / K) * Bs + b) = make_float4(rsum.x + sh[0], rsum.y + sh[1], rsum.z + sh[2], rsum.w + sh[3]);
 #pragma unroll
-    for (int i = 0; i < RPT; ++i) {
-        const int k = rg + RG * i;
-        if (k < K)
-            *reinterpret_cast<float4 *>(l + (int64_t)(id + k) * Bs + b) =
-                make_float4((float)(s[i].x - (ACC)sh[0]), (float)(s[i].y - (ACC)sh[1]), (float)(s[i].z - (ACC)sh[2]),
-                            (float)(s[i].w - (ACC)sh[3]));
+        for (int i = 0; i < RPT; ++i) {
+            const int k = rg + RG * i;
+            if (k < K)
+                *reinterpret_cast<float4 *>(l + (int64_t)(id + k) * Bs + b) =
+                    make_float4((float)(s[i].x - (ACC)sh[0]), (float)(s[i].y - (ACC)sh[1]), (float)(s[i].z - (ACC)sh[2]),
+                                (float)(s[i].w - (ACC)sh[3]));
+        }
+    }
+    if (PLANES) {
+        // the block's tile again as bf16 operand planes for a sum layer that runs on the bf16 matrix cores (this saves
+        // the launch of k_split_p): the rows just stored are read back through L2 once every store has landed
+        __threadfence_block();
+        __syncthreads();
+        const int n_ct = (int)(Bs / 32), lane = threadIdx.x & 63;
+        constexpr int CTW = CL / 8;                                     // 32-column tiles of the workgroup
+        for (int it = wave; it < (K / 16) * CTW; it += 4) {
+            const int ks = it / CTW, ct = (int)blockIdx.y * CTW + it % CTW;
+            if (ct < n_ct) split_value_tile(l, PC_UP, (int64_t)id + 16 * ks, ct, n_ct, Bs, Ph, Pl, lane);
+        }
     }
 }
 
@@ -482,9 +529,10 @@ __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *
 // F_child += sum of the parents' flows ('=' where this is the first layer that feeds the block, flag bit 1, so
 // the flow buffer is never cleared).  Where this layer is the last one that feeds a SUM block (flag bit 0) its
 // flow is final, so log_nf = log F - l (Alg. 3 / 4) and its column maximum per block are produced here.
-template <int RPT, int U, bool MULTI, int CL>
+template <int RPT, int U, bool MULTI, int CL, bool PLANES>
 __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, float *__restrict__ F, float *__restrict__ N,
-                                                  float *__restrict__ nfmax, const GroupSet gs, int32_t K, int64_t Bs)
+                                                  float *__restrict__ nfmax, const GroupSet gs, int32_t K, int64_t Bs,
+                                                  uint4 *__restrict__ Ph, uint4 *__restrict__ Pl)
 {
     __shared__ float red[4][64];
     const GroupRow gr = locate_row<MULTI>(gs, blockIdx.x);
@@ -556,6 +604,20 @@ __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, f
     }
     block_col_max<CL>(mx, red, wave, cl);
     if (in && rg == 0) *reinterpret_cast<float4 *>(nfmax + (int64_t)(id / K) * Bs + b) = make_float4(mx[0], mx[1], mx[2], mx[3]);
+    if (PLANES) {
+        // exp(log_nf - column maximum + PC_UP) of the block as bf16 operand planes for a sum layer whose backward pass
+        // runs on the bf16 matrix cores (saves the launch of k_split_p); read back through L2 once the stores have landed
+        __threadfence_block();
+        __syncthreads();
+        const int n_ct = (int)(Bs / 32), lane = threadIdx.x & 63;
+        constexpr int CTW = CL / 8;                                     // 32-column tiles of the workgroup
+        for (int it = wave; it < (K / 16) * CTW; it += 4) {
+            const int ks = it / CTW, ct = (int)blockIdx.y * CTW + it % CTW;
+            if (ct >= n_ct) continue;
+            const float top = nfmax[(int64_t)(id / K) * Bs + (int64_t)ct * 32 + (lane & 31)];
+            split_value_tile(N, top > PC_NEG_INF ? PC_UP - top : PC_NEG_INF, (int64_t)id + 16 * ks, ct, n_ct, Bs, Ph, Pl, lane);
+        }
+    }
 }
 
 // Blocks without parents, which no layer of the backward sweep writes.  An entry >= 0 is a sum block: the root
@@ -1269,19 +1331,6 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
 // are relative to its integer reference R_c, the block's partial sums are accumulated on their own and added to the
 // row's accumulator with the factor exp(R_c - R_row) (R_row = largest reference so far; the accumulator is rescaled
 // when it grows).  v_mfma_f32_32x32x16_bf16: A 32 x 16, B 16 x 32, D as for the fp32 instruction.
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
-
-__device__ inline void bf16_split2(float a, float b, uint32_t &hi, uint32_t &lo)
-{
-    const floatx2 v = {a, b};
-    const bf16x2 h = __builtin_convertvector(v, bf16x2);               // round to nearest even
-    const floatx2 hf = __builtin_convertvector(h, floatx2);
-    const bf16x2 l = __builtin_convertvector(v - hf, bf16x2);
-    hi = __builtin_bit_cast(uint32_t, h);
-    lo = __builtin_bit_cast(uint32_t, l);
-}
 
 // theta [n_blocks][K][K] fp32 -> planes Th, Tl of 1 KiB tiles [block][rt][ks][lane][8]; TRANSPOSED: the tiles of
 // theta^T (rows = children), for the backward kernel.  One wave per tile.
@@ -1322,24 +1371,15 @@ __global__ __launch_bounds__(256) void k_split_p(const float *__restrict__ X, co
     const int n_ct = (int)(Bs / 32), nks = K / 16;
     const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (item >= (int64_t)n_blk * nks * n_ct) return;
-    const int lane = threadIdx.x & 63, j = lane & 31, h = lane >> 5;
+    const int lane = threadIdx.x & 63;
     const int ct = (int)(item % n_ct), ks = (int)((item / n_ct) % nks);
     const int32_t id = blk_ids[item / ((int64_t)n_ct * nks)];
-    const int64_t col = (int64_t)ct * 32 + j;
     float sh = PC_UP;
     if (ref) {
-        const float r = ref[(int64_t)(id / K) * Bs + col];
+        const float r = ref[(int64_t)(id / K) * Bs + (int64_t)ct * 32 + (lane & 31)];
         sh = r > PC_NEG_INF ? PC_UP - r : PC_NEG_INF;                   // a block without flow: every factor 0
     }
-    float v[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = __expf(X[(int64_t)(id + 16 * ks + 8 * h + e) * Bs + col] + sh);
-    uint32_t hi[4], lo[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) bf16_split2(v[2 * e], v[2 * e + 1], hi[e], lo[e]);
-    const int64_t tile = ((int64_t)(id / 16 + ks)) * n_ct + ct;
-    Ph[tile * 64 + lane] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-    Pl[tile * 64 + lane] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    split_value_tile(X, sh, (int64_t)id + 16 * ks, ct, n_ct, Bs, Ph, Pl, lane);
 }
 
 // Sum layer on the planes, forward (rows = sum blocks, neighbours = their product children) and backward to the
@@ -2255,9 +2295,12 @@ void launch_input_bwd(const float *F, const int32_t *xT, const GroupDev &g, int3
         if (gs.n > 1) PC_DISPATCH_PROD_M(KERNEL, true, __VA_ARGS__);                                       \
         else PC_DISPATCH_PROD_M(KERNEL, false, __VA_ARGS__);                                               \
     } while (0)
-#define PC_PROD_FWD_F32(RPT, U, MULTI, CL) k_prod_fwd<RPT, U, MULTI, CL, float>
-#define PC_PROD_FWD_F64(RPT, U, MULTI, CL) k_prod_fwd<RPT, U, MULTI, CL, double>
-#define PC_PROD_BWD(RPT, U, MULTI, CL) k_prod_bwd<RPT, U, MULTI, CL>
+#define PC_PROD_FWD_F32(RPT, U, MULTI, CL) k_prod_fwd<RPT, U, MULTI, CL, float, false>
+#define PC_PROD_FWD_F64(RPT, U, MULTI, CL) k_prod_fwd<RPT, U, MULTI, CL, double, false>
+#define PC_PROD_FWD_F32_P(RPT, U, MULTI, CL) k_prod_fwd<RPT, U, MULTI, CL, float, true>
+#define PC_PROD_FWD_F64_P(RPT, U, MULTI, CL) k_prod_fwd<RPT, U, MULTI, CL, double, true>
+#define PC_PROD_BWD(RPT, U, MULTI, CL) k_prod_bwd<RPT, U, MULTI, CL, false>
+#define PC_PROD_BWD_P(RPT, U, MULTI, CL) k_prod_bwd<RPT, U, MULTI, CL, true>
 // small launches (the deep narrow circuits) use 32-column workgroups
 static inline bool prod_narrow(const GroupSet &gs, int64_t Bs) { return (int64_t)gs.first[gs.n] * ((Bs + 63) / 64) < 1024; }
 
@@ -2288,26 +2331,32 @@ static inline int32_t set_width(const GroupSet &gs)
     return w;
 }
 
-void launch_prod_fwd(float *l, float *R, const std::vector<GroupSet> &sets, int32_t K, int64_t Bs, hipStream_t s)
+void launch_prod_fwd(float *l, float *R, const std::vector<GroupSet> &sets, int32_t K, int64_t Bs, void *Ph, void *Pl, hipStream_t s)
 {
+    uint4 *ph = (uint4 *)Ph, *pl = (uint4 *)Pl;                          // non-null: also write the bf16 value planes
     for (const GroupSet &gs : sets) {
         Timed timed(KC_PROD_FWD, s);
         const bool narrow = prod_narrow(gs, Bs);
         dim3 grid((unsigned)set_rows(gs), (unsigned)(narrow ? (Bs + 31) / 32 : (Bs + 63) / 64));
         // rows with more than eight children (leaf products over many variables) are summed in double
-        if (set_width(gs) > 8) PC_DISPATCH_PROD(PC_PROD_FWD_F64, grid, dim3(256), 0, s, l, R, gs, K, Bs);
-        else PC_DISPATCH_PROD(PC_PROD_FWD_F32, grid, dim3(256), 0, s, l, R, gs, K, Bs);
+        if (ph && (K % 16) == 0) {
+            if (set_width(gs) > 8) PC_DISPATCH_PROD(PC_PROD_FWD_F64_P, grid, dim3(256), 0, s, l, R, gs, K, Bs, ph, pl);
+            else PC_DISPATCH_PROD(PC_PROD_FWD_F32_P, grid, dim3(256), 0, s, l, R, gs, K, Bs, ph, pl);
+        } else if (set_width(gs) > 8) PC_DISPATCH_PROD(PC_PROD_FWD_F64, grid, dim3(256), 0, s, l, R, gs, K, Bs, ph, pl);
+        else PC_DISPATCH_PROD(PC_PROD_FWD_F32, grid, dim3(256), 0, s, l, R, gs, K, Bs, ph, pl);
     }
 }
 
 void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const std::vector<GroupSet> &sets, int32_t K,
-                     int64_t Bs, hipStream_t s)
+                     int64_t Bs, void *Ph, void *Pl, hipStream_t s)
 {
+    uint4 *ph = (uint4 *)Ph, *pl = (uint4 *)Pl;                          // non-null: also write the bf16 planes of finished sum blocks
     for (const GroupSet &gs : sets) {
         Timed timed(KC_PROD_BWD, s);
         const bool narrow = prod_narrow(gs, Bs);
         dim3 grid((unsigned)set_rows(gs), (unsigned)(narrow ? (Bs + 31) / 32 : (Bs + 63) / 64));
-        PC_DISPATCH_PROD(PC_PROD_BWD, grid, dim3(256), 0, s, l, F, N, nfmax, gs, K, Bs);
+        if (ph && (K % 16) == 0) PC_DISPATCH_PROD(PC_PROD_BWD_P, grid, dim3(256), 0, s, l, F, N, nfmax, gs, K, Bs, ph, pl);
+        else PC_DISPATCH_PROD(PC_PROD_BWD, grid, dim3(256), 0, s, l, F, N, nfmax, gs, K, Bs, ph, pl);
     }
 }
 
@@ -2467,6 +2516,7 @@ void launch_param_flow(const float *theta, const float *l, const float *R, const
                        nfmax, G, pf.pb, pf.ptr, pf.sum, pf.child, n_split, Bs)
         // long reductions (128 chunks per workgroup or more: tied blocks of a large model): bf16-split products
         const bool bf = bf16_enabled() && (int64_t)pf.n_pairs * (Bs / 32) >= 128 * (int64_t)pf.n_pb * n_split;
+        if (bf && !one && g_prof) g_prof->bf16_launches[KC_SUM_BWD_PARAM] += 1;
         if (K == 64 && one) PC_PF_WG(64, true, false);
         else if (K == 64 && bf) PC_PF_WG(64, false, true);
         else if (K == 64) PC_PF_WG(64, false, false);
@@ -2509,6 +2559,7 @@ void launch_sum_bf16(const void *Th, const void *Tl, const void *Ph, const void 
                      float *F, bool bwd, const GroupSet &gs, int32_t K, int64_t Bs, hipStream_t s)
 {
     Timed timed(bwd ? KC_SUM_BWD_CHILD : KC_SUM_FWD, s);
+    if (g_prof) g_prof->bf16_launches[bwd ? KC_SUM_BWD_CHILD : KC_SUM_FWD] += 1;
     const dim3 grid((unsigned)(set_rows(gs) * (K / 64)), (unsigned)(Bs / 32));
 #define PC_BF16_SUM(KK, BB)                                                                                            \
     hipLaunchKernelGGL((k_sum_bf16<KK, 2, BB>), grid, dim3(256), 0, s, (const uint4 *)Th, (const uint4 *)Tl, (const uint4 *)Ph, \
