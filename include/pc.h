@@ -84,6 +84,27 @@ pc_status pc_compile_host(const pc_dag *dag, pc_circuit **out);
 void pc_destroy(pc_circuit *c);
 const char *pc_last_error(void);
 
+/* Collapse of consecutive sum / sum and product / product blocks (footnote to Def. 2): pc_compile accepts only DAGs
+ * in which sum blocks have product children and product blocks have sum or input children (PC_ERR_NOT_ALTERNATING
+ * otherwise); this optional pre-pass rewrites any other DAG of sum, product and input blocks into that form.  A
+ * product block takes over the children of its product children; a sum block takes over the children of its sum
+ * children with the K x K weight blocks multiplied (sum_j A[i][j] sum_k B[j][k] c_k = sum_k (A B)[i][k] c_k), several
+ * paths to one child add up.  The circuit computes the same function; its parameters are those of the collapsed
+ * circuit.  Host only; `theta` is a host array [n_param_blocks + 1][K][K].  Canonical form of the result:
+ *   - edges keep the order of the original edges, a replaced edge expanding in place into its child's edges; a child
+ *     reached twice keeps its first position (product blocks: PC_ERR_NOT_BLOCK_SPARSE);
+ *   - blocks no longer reachable from the root are dropped, the others keep their order (block_map: old id -> new id, -1);
+ *   - a sum block none of whose edges changed keeps its parameter blocks (and its ties), a changed one gets fresh
+ *     blocks for all its edges; parameter blocks are renumbered in order of first use.
+ * A sum block with an input child remains an error of pc_compile.  The handle owns every array it hands out
+ * (pc_collapsed_dag: ready for pc_compile; max_groups, tol_permille, n_vars, n_cats, n_tables are copied). */
+typedef struct pc_collapsed pc_collapsed;
+pc_status pc_collapse(const pc_dag *dag, const float *theta, pc_collapsed **out);
+const pc_dag *pc_collapsed_dag(const pc_collapsed *r);
+const float *pc_collapsed_theta(const pc_collapsed *r, int64_t *len);   /* [n_param_blocks + 1][K][K], block 0 zero */
+const int32_t *pc_collapsed_block_map(const pc_collapsed *r);            /* [n_blocks of the input DAG]            */
+void pc_collapsed_destroy(pc_collapsed *r);
+
 typedef struct {
     int32_t K, n_blocks, n_layers;
     int64_t n_rows;            /* (n_blocks+1)*K rows of the node buffers                        */

@@ -207,3 +207,105 @@ def compile_tables(w) -> dict:
                 "fwd": _grouped_tables(fwd_rows, w.max_groups, w.tol_permille),
                 "bwd": _grouped_tables(bwd_rows, w.max_groups, w.tol_permille)})
     return {"K": K, "n_rows": (w.n_blocks + 1) * K, "layers": layers}
+
+
+# ------------------------------------------------------------------------------------------------
+# Collapse of consecutive sum / sum and product / product blocks (footnote to Def. 2)
+# ------------------------------------------------------------------------------------------------
+def collapse(w, theta):
+    """Rewrite a block DAG so that it alternates: a product block takes over the children of its product children
+    (a product of products is one product), a sum block takes over the children of its sum children with the weight
+    blocks multiplied (sum_j A[i,j] sum_k B[j,k] c_k = sum_k (A B)[i,k] c_k); several paths to one child add up.
+
+    Canonical form of the result (the library follows the same written rules):
+      * edges keep the order of the original edges, a replaced edge expanding in place into its child's edges; a
+        child reached twice keeps its first position (sum blocks: the weight blocks add; product blocks: an error);
+      * blocks no longer reachable from the root are dropped, the others keep their order and are renumbered 0, 1, ...;
+      * a sum block none of whose edges changed keeps its parameter blocks (and its ties); a changed one gets fresh
+        blocks for all its edges; parameter blocks are renumbered in order of first use (blocks ascending, edges in order).
+    Returns a namespace with the DAG fields of a workload, `theta` (float32) and `block_map` (old id -> new id or -1)."""
+    from types import SimpleNamespace
+    K, n = int(w.K), int(w.n_blocks)
+    typ = np.asarray(w.type)
+    th = np.asarray(theta, dtype=np.float64)
+    prod_list: dict[int, list[int]] = {}
+    sum_list: dict[int, tuple[list[int], list, bool]] = {}
+
+    def flat_product(u):
+        if u not in prod_list:
+            out = []
+            for e in range(int(w.child_ptr[u]), int(w.child_ptr[u + 1])):
+                c = int(w.child[e])
+                out.extend(flat_product(c) if typ[c] == PRODUCT else [c])
+            if len(set(out)) != len(out):
+                raise CompileError(f"product block {u} reaches a child twice")
+            prod_list[u] = out
+        return prod_list[u]
+
+    def flat_sum(u):
+        """(children, per child: original parameter block id or matrix, changed)"""
+        if u not in sum_list:
+            order, entry, changed = [], {}, False
+            for e in range(int(w.child_ptr[u]), int(w.child_ptr[u + 1])):
+                c, pb = int(w.child[e]), int(w.param_blk[e])
+                if typ[c] == SUM:
+                    changed = True
+                    cc, ce, _ = flat_sum(c)
+                    parts = [(k2, th[pb + 1] @ (th[m + 1] if isinstance(m, int) else m)) for k2, m in zip(cc, ce)]
+                else:
+                    parts = [(c, pb)]
+                for k2, m in parts:
+                    if k2 in entry:
+                        changed = True
+                        old = entry[k2]
+                        entry[k2] = (th[old + 1] if isinstance(old, int) else old) + (th[m + 1] if isinstance(m, int) else m)
+                    else:
+                        entry[k2] = m
+                        order.append(k2)
+            sum_list[u] = (order, [entry[k2] for k2 in order], changed)
+        return sum_list[u]
+
+    import sys
+    sys.setrecursionlimit(max(10000, 4 * n))
+    new_children: dict[int, list[int]] = {}
+    reach, stack = set(), [int(w.root_block)]
+    while stack:
+        u = stack.pop()
+        if u in reach:
+            continue
+        reach.add(u)
+        new_children[u] = flat_product(u) if typ[u] == PRODUCT else flat_sum(u)[0] if typ[u] == SUM else []
+        stack.extend(new_children[u])
+    keep = sorted(reach)
+    block_map = np.full(n, -1, dtype=np.int32)
+    block_map[keep] = np.arange(len(keep), dtype=np.int32)
+    child_ptr, child, param, mats, pb_new = [0], [], [], [], {}
+    for u in keep:
+        if typ[u] == SUM:
+            order, ent, changed = flat_sum(u)
+            for c, m in zip(order, ent):
+                if not changed and isinstance(m, int):
+                    if m not in pb_new:
+                        pb_new[m] = len(mats)
+                        mats.append(th[m + 1])
+                    param.append(pb_new[m])
+                else:
+                    param.append(len(mats))
+                    mats.append(th[m + 1] if isinstance(m, int) else m)
+                child.append(int(block_map[c]))
+        else:
+            for c in new_children[u]:
+                child.append(int(block_map[c]))
+                param.append(-1)
+        child_ptr.append(len(child))
+    theta_new = np.zeros((len(mats) + 1, K, K), dtype=np.float32)
+    for p, M in enumerate(mats):
+        theta_new[p + 1] = M.astype(np.float32)
+    keep = np.asarray(keep, dtype=np.int64)
+    return SimpleNamespace(
+        K=K, n_blocks=len(keep), root_block=int(block_map[int(w.root_block)]), type=typ[keep].astype(np.uint8),
+        n_real=np.asarray(w.n_real)[keep].astype(np.int32), child_ptr=np.asarray(child_ptr, dtype=np.int64),
+        child=np.asarray(child, dtype=np.int32), param_blk=np.asarray(param, dtype=np.int32), n_param_blocks=len(mats),
+        in_var=np.asarray(w.in_var)[keep].astype(np.int32), in_table=np.asarray(w.in_table)[keep].astype(np.int32),
+        n_vars=int(w.n_vars), n_cats=int(w.n_cats), n_tables=int(w.n_tables), max_groups=int(w.max_groups),
+        tol_permille=int(w.tol_permille), theta=theta_new, block_map=block_map)

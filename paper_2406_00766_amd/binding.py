@@ -64,7 +64,8 @@ class pc_profile(C.Structure):
 EXPORTS = ["pc_compile", "pc_compile_host", "pc_destroy", "pc_last_error", "pc_get_sizes", "pc_get_layer",
            "pc_get_group", "pc_copy_group", "pc_workspace_layout", "pc_workspace_bytes", "pc_forward",
            "pc_forward_static", "pc_backward", "pc_em_step", "pc_profile_enable", "pc_profile_read", "pc_kernel_class_name",
-           "pc_measure_copy", "pc_measure_mfma_f32"]
+           "pc_measure_copy", "pc_measure_mfma_f32", "pc_collapse", "pc_collapsed_dag", "pc_collapsed_theta",
+           "pc_collapsed_block_map", "pc_collapsed_destroy"]
 
 _lib = None
 
@@ -102,6 +103,15 @@ def lib():
         L.pc_kernel_class_name.restype = C.c_char_p
         L.pc_measure_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
         L.pc_measure_mfma_f32.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
+        L.pc_collapse.argtypes = [C.POINTER(pc_dag), C.c_void_p, C.POINTER(C.c_void_p)]
+        L.pc_collapsed_dag.argtypes = [C.c_void_p]
+        L.pc_collapsed_dag.restype = C.POINTER(pc_dag)
+        L.pc_collapsed_theta.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
+        L.pc_collapsed_theta.restype = C.POINTER(C.c_float)
+        L.pc_collapsed_block_map.argtypes = [C.c_void_p]
+        L.pc_collapsed_block_map.restype = C.POINTER(C.c_int32)
+        L.pc_collapsed_destroy.argtypes = [C.c_void_p]
+        L.pc_collapsed_destroy.restype = None
         _lib = L
     return _lib
 
@@ -161,6 +171,36 @@ def pc_compile(w, stream=None, host_only: bool = False) -> int:
         _check(lib().pc_compile(C.byref(d), _stream(stream), C.byref(out)))
     del keep
     return out.value
+
+
+def pc_collapse(w):
+    """Footnote to Def. 2: the alternating form of a DAG with consecutive sum / sum or product / product blocks.
+    Returns a copy of the workload-like object `w` with the rewritten DAG arrays, `theta` and `block_map`."""
+    import copy
+    d, keep = make_dag(w)
+    theta = np.ascontiguousarray(w.theta, dtype=np.float32)
+    out = C.c_void_p()
+    _check(lib().pc_collapse(C.byref(d), theta.ctypes.data, C.byref(out)))
+    try:
+        nd = lib().pc_collapsed_dag(out).contents
+        n, ne = int(nd.n_blocks), int(nd.child_ptr[nd.n_blocks])
+        r = copy.copy(w)
+        r.n_blocks, r.root_block, r.n_param_blocks = n, int(nd.root_block), int(nd.n_param_blocks)
+        r.type = np.ctypeslib.as_array(nd.type, (n,)).copy()
+        r.n_real = np.ctypeslib.as_array(nd.n_real, (n,)).copy()
+        r.child_ptr = np.ctypeslib.as_array(nd.child_ptr, (n + 1,)).copy()
+        r.child = np.ctypeslib.as_array(nd.child, (max(ne, 1),))[:ne].copy()
+        r.param_blk = np.ctypeslib.as_array(nd.param_blk, (max(ne, 1),))[:ne].copy()
+        r.in_var = np.ctypeslib.as_array(nd.in_var, (n,)).copy()
+        r.in_table = np.ctypeslib.as_array(nd.in_table, (n,)).copy()
+        ln = C.c_int64()
+        tp = lib().pc_collapsed_theta(out, C.byref(ln))
+        r.theta = np.ctypeslib.as_array(tp, (int(ln.value),)).copy().reshape(-1, w.K, w.K)
+        r.block_map = np.ctypeslib.as_array(lib().pc_collapsed_block_map(out), (int(w.n_blocks),)).copy()
+    finally:
+        lib().pc_collapsed_destroy(out)
+    del keep
+    return r
 
 
 def pc_destroy(handle: int):

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpc.so")
-SOURCES = ["pc_compile.cpp", "pc_api.cpp", "pc_kernels.hip", "pc_compile_gpu.hip", "pc_measure.hip"]
+SOURCES = ["pc_compile.cpp", "pc_collapse.cpp", "pc_api.cpp", "pc_kernels.hip", "pc_compile_gpu.hip", "pc_measure.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 code generation
          "-Wall", "-Wno-unused-result", "-I", os.path.join(ROOT, "include"), "-I", CSRC]

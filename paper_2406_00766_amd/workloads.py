@@ -714,6 +714,71 @@ def random_circuit(n_vars: int, n_levels: int, width: int, K: int, B: int, seed:
                  width, theta, tables, x, {"kind": "random"})
 
 
+def non_alternating(n_vars: int, n_levels: int, width: int, K: int, B: int, seed: int, *, n_cats=4, p_insert=0.5,
+                    alpha=0.5) -> Workload:
+    """non_alternating_from a random_circuit without tying (not normalised in general: plain arithmetic on a DAG)."""
+    base = random_circuit(n_vars, n_levels, width, K, B, seed, n_cats=n_cats, tie_prob=0.0, alpha=alpha)
+    return non_alternating_from(base, seed, p_insert=p_insert, alpha=alpha)
+
+
+def non_alternating_from(base: Workload, seed: int, *, p_insert=0.5, alpha=0.5) -> Workload:
+    """A DAG with consecutive sum / sum and product / product blocks (the case the footnote to Def. 2 collapses).
+
+    Rewrites a random share of the edges of `base` (an alternating circuit without tied parameters): a sum edge S -> P becomes
+    S -> T -> P with a new sum block T (S keeps its row sums: the old K x K weights are replaced by rows of the same
+    mass, T gets Dirichlet rows over P and sometimes a second product child), a product edge P -> c becomes
+    P -> Q -> c with a new single-child product block Q; chains of two inserted blocks occur as well.  The result is
+    normalised whenever the base circuit is smooth, decomposable and normalised (an inserted sum block only mixes
+    product blocks of the scope of the edge it replaces when `base` is a tree-shaped circuit such as an HCLT)."""
+    K = base.K
+    rng = np.random.Generator(np.random.PCG64(seed + 7919))
+    bld = _Builder(K)
+    for u in range(base.n_blocks):
+        bld.add(int(base.type[u]), n_real=int(base.n_real[u]), var=int(base.in_var[u]), table=int(base.in_table[u]))
+    mats: list[np.ndarray] = [base.theta[p + 1].astype(np.float64) for p in range(base.n_param_blocks)]
+    products = [u for u in range(base.n_blocks) if base.type[u] == PRODUCT]
+    mix = base.meta.get("kind") == "random"            # a second, unrelated child keeps a random DAG valid but not a smooth one
+
+    def new_param(M) -> int:
+        mats.append(M)
+        return len(mats) - 1
+
+    def inserted_sum(child: int, depth: int) -> int:
+        """new sum block over `child` (a product block), with probability 1/3 over another inserted sum block"""
+        t = bld.add(SUM)
+        second = [q for q in products if q < child] if mix else []
+        chs = [child] + ([second[int(rng.integers(0, len(second)))]] if second and rng.random() < 0.5 else [])
+        Wt = _dirichlet_rows(rng, alpha, (K, len(chs) * K))
+        for j, c in enumerate(chs):
+            tgt = inserted_sum(c, depth + 1) if depth < 1 and rng.random() < 0.33 else c
+            bld.link(t, tgt, new_param(Wt[:, j * K:(j + 1) * K]))
+        return t
+
+    for u in range(base.n_blocks):
+        for e in range(base.child_ptr[u], base.child_ptr[u + 1]):
+            c, pb = int(base.child[e]), int(base.param_blk[e])
+            if base.type[u] == SUM and rng.random() < p_insert:
+                M = mats[pb]
+                A = _dirichlet_rows(rng, alpha, (K, K)) * M.sum(axis=1, keepdims=True)      # same row mass as before
+                bld.link(u, inserted_sum(c, 0), new_param(A))
+            elif base.type[u] == PRODUCT and rng.random() < p_insert:
+                q = bld.add(PRODUCT, n_real=int(base.n_real[c]))
+                if rng.random() < 0.33:                                                     # a chain of two
+                    q2 = bld.add(PRODUCT, n_real=int(base.n_real[c]))
+                    bld.link(q2, c)
+                    bld.link(q, q2)
+                else:
+                    bld.link(q, c)
+                bld.link(u, q)
+            else:
+                bld.link(u, c, pb)
+    theta = np.zeros((len(mats) + 1, K, K), dtype=np.float32)
+    for p, M in enumerate(mats):
+        theta[p + 1] = np.where(M > 0, np.maximum(M, FLT_MIN), 0.0).astype(np.float32)
+    return _make(f"nonalt_{base.name}_s{seed}", bld, base.root_block, len(mats), base.n_vars, base.n_cats, base.n_tables, theta,
+                 base.tables, base.x, {"kind": "non_alternating"})
+
+
 # --------------------------------------------------------------------------------------------
 # The five benchmark configurations and their reduced twins
 # --------------------------------------------------------------------------------------------

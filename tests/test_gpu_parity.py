@@ -291,6 +291,31 @@ def test_block_references_and_block_maxima_are_what_they_claim():
     c.close()
 
 
+@pytest.mark.parametrize("make", [
+    lambda: W.non_alternating(5, 5, 5, 32, 40, 913),
+    lambda: W.non_alternating(4, 4, 4, 4, 33, 900),
+    lambda: W.non_alternating_from(W.reduced(2), 6),          # HCLT, K = 32: every edge of the tree may be doubled
+    lambda: W.non_alternating_from(W.reduced(5), 7),          # pruned PD
+    lambda: W.non_alternating_from(W.reduced(3, B=40), 8),    # K = 64
+])
+def test_collapsed_non_alternating_dag(make):
+    """Footnote to Def. 2: pc_compile refuses consecutive sum / sum and product / product blocks; pc_collapse rewrites
+    them.  The GPU runs the library's collapsed DAG; the oracle runs (a) the same collapsed DAG, flows and all, and
+    (b) the ORIGINAL DAG node by node, whose log-likelihoods the collapsed circuit must reproduce."""
+    w = make()
+    print(f"case collapse {w.name}", flush=True)
+    with pytest.raises(pcb.PcError) as e:
+        pcb.pc_compile(w)
+    assert e.value.status_name == "PC_ERR_NOT_ALTERNATING"
+    wc = pcb.pc_collapse(w)
+    ref = co.collapse(w, w.theta)
+    for k in ("type", "child_ptr", "child", "param_blk"):
+        assert np.array_equal(getattr(wc, k), getattr(ref, k)), k
+    got, _ = check_all(wc)
+    assert_device_tables_match_oracle(got["circuit"].handle, wc)
+    assert_logprob_close(got["ll"], orc.forward(w, w.theta, w.tables, w.x)[1], "ll against the original DAG")
+
+
 def test_config1_full_size():
     w = W.config(1)
     print("case cfg1 full", flush=True)
