@@ -69,6 +69,10 @@ typedef struct {
     int32_t n_vars, n_cats, n_tables;
     int32_t max_groups;        /* G of Alg. 2 (App. A.1)                                         */
     int32_t tol_permille;      /* tol of Alg. 2 in 1/1000                                        */
+    int32_t product_scratch;   /* 0: every node's log-probability is kept for the backward pass.
+                                  1: the memory-saving mode of Sec. 5 -- the log-probabilities of product blocks live in one
+                                  scratch sized for the largest product layer and are recomputed in the backward pass just
+                                  before the sum layer that reads them.  Needs the block order of pc_order_for_scratch. */
 } pc_dag;
 
 /* Compile once, reuse for every batch (Sec. 6.1).  Layers by longest-path depth (Sec. 3), groups by
@@ -100,6 +104,12 @@ const char *pc_last_error(void);
  * (pc_collapsed_dag: ready for pc_compile; max_groups, tol_permille, n_vars, n_cats, n_tables are copied). */
 typedef struct pc_collapsed pc_collapsed;
 pc_status pc_collapse(const pc_dag *dag, const float *theta, pc_collapsed **out);
+/* Block order for product_scratch = 1 (Sec. 5, product values recomputed): the same DAG with its blocks renumbered --
+ * input and sum blocks first (relative order kept), then the product blocks grouped by the depth of the sum blocks
+ * that read them, so that the product blocks a sum layer reads are one contiguous range of ids.  PC_ERR_ARG if a
+ * product block is read by sum blocks of different depths (the mode does not apply).  Parameter block ids do not
+ * change; the result (pc_collapsed_dag, pc_collapsed_block_map; product_scratch already set) is owned by the handle. */
+pc_status pc_order_for_scratch(const pc_dag *dag, pc_collapsed **out);
 const pc_dag *pc_collapsed_dag(const pc_collapsed *r);
 const float *pc_collapsed_theta(const pc_collapsed *r, int64_t *len);   /* [n_param_blocks + 1][K][K], block 0 zero */
 const int32_t *pc_collapsed_block_map(const pc_collapsed *r);            /* [n_blocks of the input DAG]            */
@@ -151,6 +161,8 @@ typedef struct {
     int64_t stride;            /* floats between consecutive rows                               */
     size_t l_offset, f_offset, n_offset, r_offset;   /* byte offsets into the workspace         */
     size_t total_bytes;
+    int64_t l_rows;            /* rows of l: n_rows, or with product_scratch the null, input and sum blocks followed by
+                                  the window of the largest product layer (product rows are not kept)   */
 } pc_ws_layout;
 pc_status pc_workspace_layout(const pc_circuit *c, int32_t B, pc_ws_layout *out);
 pc_status pc_workspace_bytes(const pc_circuit *c, int32_t B, size_t *bytes);

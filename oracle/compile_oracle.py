@@ -172,6 +172,22 @@ def compile_tables(w) -> dict:
     depth = block_depths(w)
     if w.type[w.root_block] != SUM:
         raise CompileError("root must be a sum block")
+    if int(getattr(w, "product_scratch", 0)):
+        # Sec. 5, product values recomputed: a product block is evaluated as late as possible, in the layer right before
+        # the sum blocks that read it (all of one depth d: the block moves to depth d, and product layers come before
+        # sum layers inside a depth); product blocks nobody reads form a last layer of their own
+        readers: dict[int, set] = {}
+        for u in range(w.n_blocks):
+            if w.type[u] == SUM:
+                for e in range(int(w.child_ptr[u]), int(w.child_ptr[u + 1])):
+                    readers.setdefault(int(w.child[e]), set()).add(int(depth[u]))
+        last = int(depth.max()) + 1
+        for u in range(w.n_blocks):
+            if w.type[u] == PRODUCT:
+                ds = readers.get(u, {last})
+                if len(ds) != 1:
+                    raise CompileError("product block read by sum blocks of different depths")
+                depth[u] = next(iter(ds))
     node_off = lambda u: (int(u) + 1) * K
     par_off = lambda p: (int(p) + 1) * K * K
     layers = []

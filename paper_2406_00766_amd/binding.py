@@ -33,7 +33,7 @@ class pc_dag(C.Structure):
                 ("param_blk", C.POINTER(C.c_int32)), ("n_param_blocks", C.c_int32),
                 ("in_var", C.POINTER(C.c_int32)), ("in_table", C.POINTER(C.c_int32)),
                 ("n_vars", C.c_int32), ("n_cats", C.c_int32), ("n_tables", C.c_int32),
-                ("max_groups", C.c_int32), ("tol_permille", C.c_int32)]
+                ("max_groups", C.c_int32), ("tol_permille", C.c_int32), ("product_scratch", C.c_int32)]
 
 
 class pc_sizes(C.Structure):
@@ -53,7 +53,7 @@ class pc_group_desc(C.Structure):
 
 class pc_ws_layout(C.Structure):
     _fields_ = [("stride", C.c_int64), ("l_offset", C.c_size_t), ("f_offset", C.c_size_t),
-                ("n_offset", C.c_size_t), ("r_offset", C.c_size_t), ("total_bytes", C.c_size_t)]
+                ("n_offset", C.c_size_t), ("r_offset", C.c_size_t), ("total_bytes", C.c_size_t), ("l_rows", C.c_int64)]
 
 
 class pc_profile(C.Structure):
@@ -65,7 +65,7 @@ EXPORTS = ["pc_compile", "pc_compile_host", "pc_destroy", "pc_last_error", "pc_g
            "pc_get_group", "pc_copy_group", "pc_workspace_layout", "pc_workspace_bytes", "pc_forward",
            "pc_forward_static", "pc_backward", "pc_em_step", "pc_profile_enable", "pc_profile_read", "pc_kernel_class_name",
            "pc_measure_copy", "pc_measure_mfma_f32", "pc_collapse", "pc_collapsed_dag", "pc_collapsed_theta",
-           "pc_collapsed_block_map", "pc_collapsed_destroy"]
+           "pc_collapsed_block_map", "pc_collapsed_destroy", "pc_order_for_scratch"]
 
 _lib = None
 
@@ -104,6 +104,7 @@ def lib():
         L.pc_measure_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
         L.pc_measure_mfma_f32.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
         L.pc_collapse.argtypes = [C.POINTER(pc_dag), C.c_void_p, C.POINTER(C.c_void_p)]
+        L.pc_order_for_scratch.argtypes = [C.POINTER(pc_dag), C.POINTER(C.c_void_p)]
         L.pc_collapsed_dag.argtypes = [C.c_void_p]
         L.pc_collapsed_dag.restype = C.POINTER(pc_dag)
         L.pc_collapsed_theta.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
@@ -158,6 +159,7 @@ def make_dag(w):
     d.in_table = arrs["in_table"].ctypes.data_as(C.POINTER(C.c_int32))
     d.n_vars, d.n_cats, d.n_tables = int(w.n_vars), int(w.n_cats), int(w.n_tables)
     d.max_groups, d.tol_permille = int(w.max_groups), int(w.tol_permille)
+    d.product_scratch = int(getattr(w, "product_scratch", 0))
     return d, arrs
 
 
@@ -176,11 +178,24 @@ def pc_compile(w, stream=None, host_only: bool = False) -> int:
 def pc_collapse(w):
     """Footnote to Def. 2: the alternating form of a DAG with consecutive sum / sum or product / product blocks.
     Returns a copy of the workload-like object `w` with the rewritten DAG arrays, `theta` and `block_map`."""
+    return _rewritten(w, collapse=True)
+
+
+def pc_order_for_scratch(w):
+    """Sec. 5, product-scratch mode: a copy of `w` with its blocks renumbered (input and sum blocks first, product
+    blocks grouped by the sum layer that reads them), `product_scratch` set and `block_map` (old id -> new id)."""
+    return _rewritten(w, collapse=False)
+
+
+def _rewritten(w, collapse: bool):
     import copy
     d, keep = make_dag(w)
     theta = np.ascontiguousarray(w.theta, dtype=np.float32)
     out = C.c_void_p()
-    _check(lib().pc_collapse(C.byref(d), theta.ctypes.data, C.byref(out)))
+    if collapse:
+        _check(lib().pc_collapse(C.byref(d), theta.ctypes.data, C.byref(out)))
+    else:
+        _check(lib().pc_order_for_scratch(C.byref(d), C.byref(out)))
     try:
         nd = lib().pc_collapsed_dag(out).contents
         n, ne = int(nd.n_blocks), int(nd.child_ptr[nd.n_blocks])
@@ -193,9 +208,12 @@ def pc_collapse(w):
         r.param_blk = np.ctypeslib.as_array(nd.param_blk, (max(ne, 1),))[:ne].copy()
         r.in_var = np.ctypeslib.as_array(nd.in_var, (n,)).copy()
         r.in_table = np.ctypeslib.as_array(nd.in_table, (n,)).copy()
-        ln = C.c_int64()
-        tp = lib().pc_collapsed_theta(out, C.byref(ln))
-        r.theta = np.ctypeslib.as_array(tp, (int(ln.value),)).copy().reshape(-1, w.K, w.K)
+        if collapse:
+            ln = C.c_int64()
+            tp = lib().pc_collapsed_theta(out, C.byref(ln))
+            r.theta = np.ctypeslib.as_array(tp, (int(ln.value),)).copy().reshape(-1, w.K, w.K)
+        else:
+            r.product_scratch = 1
         r.block_map = np.ctypeslib.as_array(lib().pc_collapsed_block_map(out), (int(w.n_blocks),)).copy()
     finally:
         lib().pc_collapsed_destroy(out)
@@ -370,7 +388,7 @@ class Circuit:
         n = self.sizes.n_rows * lay.stride
         nb = (self.sizes.n_blocks + 1) * lay.stride
         f32 = self.torch.float32
-        l = self._ws[lay.l_offset:lay.l_offset + 4 * n].view(f32).view(self.sizes.n_rows, lay.stride)
+        l = self._ws[lay.l_offset:lay.l_offset + 4 * lay.l_rows * lay.stride].view(f32).view(lay.l_rows, lay.stride)
         F = self._ws[lay.f_offset:lay.f_offset + 4 * n].view(f32).view(self.sizes.n_rows, lay.stride)
         R = self._ws[lay.r_offset:lay.r_offset + 4 * nb].view(f32).view(self.sizes.n_blocks + 1, lay.stride)
         return l, F, R

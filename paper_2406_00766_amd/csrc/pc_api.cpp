@@ -73,6 +73,10 @@ pc_status upload(pc_circuit *c, hipStream_t stream)
                 add_sized(&g.d_par, g.par, (size_t)g.n_rows * g.width);
                 add(&g.d_aux, g.aux);
             }
+        if (!layer.pf_pb.empty()) {
+            add(&layer.d_pf_pb, layer.pf_pb); add(&layer.d_pf_ptr, layer.pf_ptr);
+            add(&layer.d_pf_sum, layer.pf_sum); add(&layer.d_pf_child, layer.pf_child);
+        }
     }
     add(&c->d_pb_group, c->pb_group); add(&c->d_pb_rows, c->pb_rows); add(&c->d_pb_cols, c->pb_cols);
     add(&c->d_group_nch, c->group_nch);
@@ -132,7 +136,15 @@ struct Ws {
     size_t l_off, f_off, n_off, r_off, mx_off, xt_off, total;
     size_t th_off, tl_off, tth_off, ttl_off, ph_off, pl_off;   // bf16 operand planes (only where a layer takes the bf16 kernels)
     bool bf16;
+    int64_t l_rows;                                   // rows of l: all of them, or the persistent ones and the product window
 };
+// Product-scratch mode: base pointer through which the rows of product layer L (a contiguous range of block ids) land
+// in the window behind the persistent rows of l; node offsets stay what they are.
+static inline float *window_base(const pc_circuit *c, const LayerTab &L, float *l, int64_t Bs)
+{
+    return l + ((int64_t)c->n_persistent_blocks - L.scr_first_block) * c->K * Bs;
+}
+
 static inline bool misaligned(const void *p) { return ((uintptr_t)p & 15) != 0; }   // kernels use 16-byte accesses
 
 static Ws ws_layout(const pc_circuit *c, int32_t B)
@@ -141,16 +153,19 @@ static Ws ws_layout(const pc_circuit *c, int32_t B)
     w.Bs = ((int64_t)B + 31) / 32 * 32;
     const size_t rows = ((size_t)c->n_blocks + 1) * c->K;
     const size_t node = align_up(rows * w.Bs * 4, 256);
-    w.l_off = 0; w.f_off = node; w.n_off = 2 * node;
+    // product-scratch mode: l holds the null block, the input and sum blocks and one window for the largest product layer
+    w.l_rows = c->product_scratch ? ((int64_t)c->n_persistent_blocks + 1 + c->max_window_blocks) * c->K : (int64_t)rows;
+    const size_t lnode = align_up((size_t)w.l_rows * w.Bs * 4, 256);
+    w.l_off = 0; w.f_off = lnode; w.n_off = lnode + node;
     const size_t per_block = align_up(((size_t)c->n_blocks + 1) * w.Bs * 4, 256);
-    w.r_off = 3 * node;
+    w.r_off = lnode + 2 * node;
     w.mx_off = w.r_off + per_block;
     w.xt_off = w.mx_off + per_block;
     w.total = w.xt_off + align_up((size_t)c->n_vars * w.Bs * 4, 256);
     // layers with long dense rows run on the bf16 matrix cores and need theta and the node values split into planes
     w.bf16 = false;
     for (const LayerTab &L : c->layers)
-        if (L.kind == KIND_SUM && L.fwd.size() == 1 && sum_layer_takes_bf16(c->K, 1, L.fwd[0].n_rows, L.fwd[0].width, w.Bs)) w.bf16 = true;
+        if (!c->product_scratch && L.kind == KIND_SUM && L.fwd.size() == 1 && sum_layer_takes_bf16(c->K, 1, L.fwd[0].n_rows, L.fwd[0].width, w.Bs)) w.bf16 = true;
     w.th_off = w.tl_off = w.tth_off = w.ttl_off = w.ph_off = w.pl_off = 0;
     if (w.bf16) {
         const size_t tplane = align_up(((size_t)c->n_param_blocks + 1) * c->K * c->K * 2, 256), pplane = align_up(rows * w.Bs * 2, 256);
@@ -272,6 +287,7 @@ pc_status pc_workspace_layout(const pc_circuit *c, int32_t B, pc_ws_layout *out)
     out->stride = w.Bs; out->l_offset = w.l_off; out->f_offset = w.f_off; out->n_offset = w.n_off;
     out->r_offset = w.r_off;
     out->total_bytes = w.total;
+    out->l_rows = w.l_rows;
     return PC_OK;
 }
 
@@ -313,12 +329,15 @@ static pc_status forward_on(pc_circuit *c, const float *theta, const float *tabl
         if (L.kind == KIND_INPUT) {
             launch_input_fwd(tables, xT, dev(L.fwd[0]), K, c->n_cats, w.Bs, l, s);
         } else if (L.kind == KIND_PRODUCT) {
-            launch_prod_fwd(l, R, plan.layers[li].fwd, K, w.Bs, w.bf16 ? base + w.ph_off : nullptr, w.bf16 ? base + w.pl_off : nullptr, s);
+            launch_prod_fwd(l, c->product_scratch ? window_base(c, L, l, w.Bs) : l, R, plan.layers[li].fwd, K, w.Bs,
+                            w.bf16 ? base + w.ph_off : nullptr, w.bf16 ? base + w.pl_off : nullptr, s);
         } else if (w.bf16 && L.fwd.size() == 1 && sum_layer_takes_bf16(K, 1, L.fwd[0].n_rows, L.fwd[0].width, w.Bs)) {
             launch_sum_bf16(base + w.th_off, base + w.tl_off, base + w.ph_off, base + w.pl_off, l, R, nullptr, nullptr, false,
                             plan.layers[li].fwd[0], K, w.Bs, s);
         } else {
-            launch_sum_fwd(theta, l, R, plan.layers[li].fwd, K, w.Bs, s);
+            // product-scratch mode: the children are the product layer just before, in the window
+            launch_sum_fwd(theta, c->product_scratch ? window_base(c, c->layers[li - 1], l, w.Bs) : l, l, R, plan.layers[li].fwd, K,
+                           w.Bs, s);
         }
     }
     launch_readout(l, R, (int64_t)(c->root_block + 1) * K, (int64_t)c->root_block + 1, w.Bs, B, ll, s);
@@ -399,6 +418,19 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
                             true, plan.layers[li].bwd[0], K, w.Bs, s);
             if (theta_flow && !batched_params)
                 for (const GroupTab &g : L.fwd) launch_sum_bwd_param_generic(theta, l, R, N, theta_flow, dev(g), K, w.Bs, B, s);
+        } else if (L.kind == KIND_SUM && c->product_scratch) {
+            // Sec. 5: the product layer this sum layer reads is evaluated again into the scratch window, then the flows
+            // to the children and this layer's parameter flows are taken while its values are there
+            const LayerTab &P = c->layers[li - 1];
+            float *lp = window_base(c, P, l, w.Bs);
+            launch_prod_fwd(l, lp, const_cast<float *>(R), plan.layers[li - 1].fwd, K, w.Bs, nullptr, nullptr, s);
+            launch_sum_bwd_child(theta, lp, R, N, nfmax, F, plan.layers[li].bwd, K, w.Bs, s);
+            if (theta_flow && batched_params) {
+                ParamFlowDev pf{(int32_t)L.pf_pb.size(), L.d_pf_pb, L.d_pf_ptr, L.d_pf_sum, L.d_pf_child, (int64_t)L.pf_sum.size()};
+                launch_param_flow(theta, lp, R, N, nfmax, theta_flow, pf, K, w.Bs, s);
+            } else if (theta_flow) {
+                for (const GroupTab &g : L.fwd) launch_sum_bwd_param_generic(theta, lp, R, N, theta_flow, dev(g), K, w.Bs, B, s);
+            }
         } else if (L.kind == KIND_SUM) {
             launch_sum_bwd_child(theta, l, R, N, nfmax, F, plan.layers[li].bwd, K, w.Bs, s);
             if (theta_flow && !batched_params)
@@ -409,7 +441,7 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
             launch_input_bwd(F, xT, dev(L.fwd[0]), K, c->n_cats, w.Bs, table_flow, s);
         }
     }
-    if (theta_flow && batched_params) {
+    if (theta_flow && batched_params && !c->product_scratch) {
         ParamFlowDev pf{(int32_t)c->pf_pb.size(), c->d_pf_pb, c->d_pf_ptr, c->d_pf_sum, c->d_pf_child, (int64_t)c->pf_sum.size()};
         launch_param_flow(theta, l, R, N, nfmax, theta_flow, pf, K, w.Bs, s);
     }

@@ -213,6 +213,71 @@ pc_status pc_collapse(const pc_dag *dag, const float *theta, pc_collapsed **out)
     return PC_OK;
 }
 
+// Block order for the product-scratch mode of pc_compile: input and sum blocks first (their relative order kept), then
+// the product blocks grouped by the depth of the sum blocks that read them (groups ascending, order kept inside).
+pc_status pc_order_for_scratch(const pc_dag *dag, pc_collapsed **out)
+{
+    if (!dag || !out) return fail(PC_ERR_ARG, "NULL argument");
+    const int32_t n = dag->n_blocks;
+    if (dag->K < 1 || n < 1 || !dag->type || !dag->n_real || !dag->child_ptr || !dag->in_var || !dag->in_table ||
+        (dag->child_ptr[n] > 0 && (!dag->child || !dag->param_blk)))
+        return fail(PC_ERR_ARG, "invalid DAG description");
+    for (int64_t e = 0; e < dag->child_ptr[n]; ++e)
+        if (dag->child[e] < 0 || dag->child[e] >= n) return fail(PC_ERR_ARG, "child id out of range");
+    // longest-path depth, children before parents
+    std::vector<int32_t> depth((size_t)n, 0), pending((size_t)n, 0), order;
+    std::vector<std::vector<int32_t>> parents((size_t)n);
+    for (int32_t u = 0; u < n; ++u) {
+        pending[u] = (int32_t)(dag->child_ptr[u + 1] - dag->child_ptr[u]);
+        for (int64_t e = dag->child_ptr[u]; e < dag->child_ptr[u + 1]; ++e) parents[dag->child[e]].push_back(u);
+        if (pending[u] == 0) order.push_back(u);
+    }
+    for (size_t i = 0; i < order.size(); ++i) {
+        const int32_t u = order[i];
+        for (int32_t p : parents[u]) {
+            depth[p] = std::max(depth[p], depth[u] + 1);
+            if (--pending[p] == 0) order.push_back(p);
+        }
+    }
+    if ((int32_t)order.size() != n) return fail(PC_ERR_CYCLE, "the block graph has a cycle");
+    // product blocks: key = depth of their readers (all of one depth, else the mode does not apply); unread ones last
+    std::vector<std::pair<int64_t, int32_t>> keyed;                     // (group key, old id)
+    for (int32_t u = 0; u < n; ++u) {
+        if (dag->type[u] != KIND_PRODUCT) { keyed.emplace_back(-1, u); continue; }
+        int64_t key = (int64_t)1 << 40;
+        for (int32_t p : parents[u]) {
+            if (key != ((int64_t)1 << 40) && key != depth[p])
+                return fail(PC_ERR_ARG, "product block " + std::to_string(u) + " is read by sum blocks of different depths");
+            key = depth[p];
+        }
+        keyed.emplace_back(key, u);
+    }
+    std::stable_sort(keyed.begin(), keyed.end(), [](const std::pair<int64_t, int32_t> &a, const std::pair<int64_t, int32_t> &b) { return a.first < b.first; });
+    pc_collapsed *r = new (std::nothrow) pc_collapsed();
+    if (!r) return fail(PC_ERR_ARG, "out of host memory");
+    r->block_map.assign((size_t)n, -1);
+    for (int32_t i = 0; i < n; ++i) r->block_map[keyed[i].second] = i;
+    r->child_ptr.push_back(0);
+    for (int32_t i = 0; i < n; ++i) {
+        const int32_t u = keyed[i].second;
+        r->type.push_back(dag->type[u]); r->n_real.push_back(dag->n_real[u]);
+        r->in_var.push_back(dag->in_var[u]); r->in_table.push_back(dag->in_table[u]);
+        for (int64_t e = dag->child_ptr[u]; e < dag->child_ptr[u + 1]; ++e) {
+            r->child.push_back(r->block_map[dag->child[e]]);
+            r->param_blk.push_back(dag->param_blk[e]);
+        }
+        r->child_ptr.push_back((int64_t)r->child.size());
+    }
+    r->dag = *dag;
+    r->dag.root_block = r->block_map[dag->root_block];
+    r->dag.type = r->type.data(); r->dag.n_real = r->n_real.data();
+    r->dag.child_ptr = r->child_ptr.data(); r->dag.child = r->child.data(); r->dag.param_blk = r->param_blk.data();
+    r->dag.in_var = r->in_var.data(); r->dag.in_table = r->in_table.data();
+    r->dag.product_scratch = 1;
+    *out = r;
+    return PC_OK;
+}
+
 const pc_dag *pc_collapsed_dag(const pc_collapsed *r) { return r ? &r->dag : nullptr; }
 
 const float *pc_collapsed_theta(const pc_collapsed *r, int64_t *len)

@@ -207,6 +207,26 @@ pc_status compile_host(const pc_dag *d, pc_circuit *c, bool tables_on_host)
     if (done != n) return fail(PC_ERR_CYCLE, "the block graph has a cycle");
 
     if (par_ptr[d->root_block + 1] != par_ptr[d->root_block]) return fail(PC_ERR_ARG, "the root block must not have parents");
+    // Product-scratch mode (Sec. 5): a product block is evaluated as late as possible -- in the layer right before the
+    // sum blocks that read it (all of one depth) -- so that a product layer is read by the next sum layer only and its
+    // values can share one scratch.  Product blocks nobody reads form a last layer of their own.
+    c->product_scratch = d->product_scratch != 0;
+    if (c->product_scratch) {
+        bool orphan = false;
+        for (int32_t u = 0; u < n; ++u) {
+            if (d->type[u] != KIND_PRODUCT) continue;
+            if (par_ptr[u] == par_ptr[u + 1]) { orphan = true; continue; }
+            const int32_t ds = depth[par_of[par_ptr[u]]];
+            for (int32_t k = par_ptr[u]; k < par_ptr[u + 1]; ++k)
+                if (depth[par_of[k]] != ds) return fail(PC_ERR_ARG, "product_scratch: a product block is read by sum blocks of different depths");
+            depth[u] = ds;
+        }
+        if (orphan) {
+            for (int32_t u = 0; u < n; ++u)
+                if (d->type[u] == KIND_PRODUCT && par_ptr[u] == par_ptr[u + 1]) depth[u] = max_depth + 1;
+            max_depth += 1;
+        }
+    }
     // per block: the smallest and the largest depth among its parents (the last and the first layer of the
     // backward sweep that feed it; all parents of a block are of one kind, so a depth names one layer)
     std::vector<int32_t> last_parent_depth(n, -1), first_parent_depth(n, -1);
@@ -231,7 +251,7 @@ pc_status compile_host(const pc_dag *d, pc_circuit *c, bool tables_on_host)
     c->an_first_parent_depth = first_parent_depth;
 
     // bucket blocks: layer key = 2*depth + (sum ? 1 : 0); inputs are layer 0
-    std::vector<std::vector<int32_t>> bucket(2 * (size_t)max_depth + 2);
+    std::vector<std::vector<int32_t>> bucket(2 * (size_t)max_depth + 2);      // max_depth includes the layer of unread products
     for (int32_t u = 0; u < n; ++u) {
         const size_t key = d->type[u] == KIND_INPUT ? 0 : 2 * (size_t)depth[u] + (d->type[u] == KIND_SUM ? 1 : 0);
         bucket[key].push_back(u);
@@ -285,7 +305,42 @@ pc_status compile_host(const pc_dag *d, pc_circuit *c, bool tables_on_host)
                                                first_parent_depth[ch]);
                 }
         }
+        if (c->product_scratch && layer.kind == KIND_PRODUCT) {
+            layer.scr_first_block = blocks.front();
+            if (blocks.back() - blocks.front() + 1 != (int32_t)blocks.size())
+                return fail(PC_ERR_ARG, "product_scratch: the product blocks of a layer must have consecutive ids (pc_order_for_scratch)");
+            c->max_window_blocks = std::max(c->max_window_blocks, (int32_t)blocks.size());
+        }
         c->layers.push_back(std::move(layer));
+    }
+    if (c->product_scratch) {
+        // input and sum blocks first, product blocks behind them; every sum layer reads the product layer before it
+        c->n_persistent_blocks = 0;
+        for (int32_t u = 0; u < n; ++u) if (d->type[u] != KIND_PRODUCT) ++c->n_persistent_blocks;
+        for (int32_t u = 0; u < n; ++u)
+            if ((d->type[u] == KIND_PRODUCT) != (u >= c->n_persistent_blocks))
+                return fail(PC_ERR_ARG, "product_scratch: input and sum blocks must come before the product blocks (pc_order_for_scratch)");
+        std::vector<int32_t> layer_of(n, 0);
+        for (size_t li = 0; li < c->layers.size(); ++li)
+            for (int32_t id : c->layers[li].blk_ids) layer_of[id / K - 1] = (int32_t)li;
+        for (size_t li = 0; li < c->layers.size(); ++li) {
+            LayerTab &L = c->layers[li];
+            if (L.kind != KIND_SUM) continue;
+            std::map<int32_t, std::vector<std::pair<int32_t, int32_t>>> users;        // parameter block -> pairs of this layer
+            for (int32_t id : L.blk_ids) {
+                const int32_t u = id / K - 1;
+                for (int64_t e = d->child_ptr[u]; e < d->child_ptr[u + 1]; ++e) {
+                    if (layer_of[d->child[e]] != (int32_t)li - 1) return fail(PC_ERR_ARG, "product_scratch: a sum layer must read the product layer before it");
+                    users[d->param_blk[e]].emplace_back(id, (d->child[e] + 1) * K);
+                }
+            }
+            L.pf_ptr.assign(1, 0);
+            for (auto &kv : users) {
+                L.pf_pb.push_back((kv.first + 1) * K * K);
+                for (auto &sc : kv.second) { L.pf_sum.push_back(sc.first); L.pf_child.push_back(sc.second); }
+                L.pf_ptr.push_back((int32_t)L.pf_sum.size());
+            }
+        }
     }
 
     // EM normalisation map.  A sum node's weights span all parameter blocks of its block's edges;

@@ -41,6 +41,11 @@ struct LayerTab {
     std::vector<GroupTab> fwd, bwd;
     std::vector<int32_t> blk_ids;                     // node offsets of all blocks of the layer, ascending
     int32_t *d_blk_ids = nullptr;
+    // product-scratch mode (Sec. 5): a product layer's blocks are one contiguous id range that lives in the scratch
+    // window; a sum layer has its own parameter-flow table (its products are gone when the sweep moves on)
+    int32_t scr_first_block = -1;                     // product layers: id of the first block of the layer
+    std::vector<int32_t> pf_pb, pf_ptr, pf_sum, pf_child;
+    int32_t *d_pf_pb = nullptr, *d_pf_ptr = nullptr, *d_pf_sum = nullptr, *d_pf_child = nullptr;
 };
 
 }  // namespace pc
@@ -65,6 +70,11 @@ struct pc_circuit {
     // node offsets; other blocks and the null block as ~offset
     std::vector<int32_t> init_ids;
     int32_t *d_init_ids = nullptr;
+
+    // product-scratch mode: product log-probabilities live in a window of max_window_blocks blocks behind the
+    // n_persistent_blocks input and sum blocks
+    bool product_scratch = false;
+    int32_t n_persistent_blocks = 0, max_window_blocks = 0;
 
     void *d_arena = nullptr;                          // one device allocation behind every d_* above
     size_t arena_bytes = 0;

@@ -70,11 +70,14 @@ void launch_input_bwd(const float *F, const int32_t *xT, const GroupDev &g, int3
 // layer are independent of one another, and one launch covers a whole set.
 std::vector<GroupSet> make_group_sets(const std::vector<GroupDev> &groups);
 // Ph / Pl non-null: the kernel also writes the bf16 value planes of its rows (see launch_split_p)
-void launch_prod_fwd(float *l, float *R, const std::vector<GroupSet> &sets, int32_t K, int64_t Bs, void *Ph, void *Pl, hipStream_t s);
+// l: base the children are read from, lout: base the products are written to (the same, except in the product-scratch mode)
+void launch_prod_fwd(const float *l, float *lout, float *R, const std::vector<GroupSet> &sets, int32_t K, int64_t Bs, void *Ph, void *Pl,
+                     hipStream_t s);
 void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const std::vector<GroupSet> &sets, int32_t K,
                      int64_t Bs, void *Ph, void *Pl, hipStream_t s);
-void launch_sum_fwd(const float *theta, float *l, float *R, const std::vector<GroupSet> &sets, int32_t K, int64_t Bs,
-                    hipStream_t s);
+// lch: base the product children are read from; l: base of the sum rows written
+void launch_sum_fwd(const float *theta, const float *lch, float *l, float *R, const std::vector<GroupSet> &sets, int32_t K,
+                    int64_t Bs, hipStream_t s);
 void launch_sum_bwd_child(const float *theta, const float *l, const float *R, const float *N, const float *nfmax, float *F,
                           const std::vector<GroupSet> &sets, int32_t K, int64_t Bs, hipStream_t s);
 void launch_sum_bwd_param_generic(const float *theta, const float *l, const float *R, const float *N, float *G,

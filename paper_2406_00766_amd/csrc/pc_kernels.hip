@@ -441,9 +441,12 @@ __device__ inline void block_col_max(float (&mx)[4], float (*red)[64], int wave,
 // -540, where one fp32 step is 6e-5: summed in fp32 the residuals -- and with them every flow ratio p_c / p_n below --
 // would be off by up to 1e-3); the rounded maximum is subtracted in that precision, the small residual is stored as fp32.
 template <typename ACC> struct Acc4 { ACC x, y, z, w; };
+// `l` is the base the children are read from, `lout` the base the block's own rows are written to: the same buffer,
+// except in the product-scratch mode (Sec. 5), where product rows live in a window that every product layer reuses.
 template <int RPT, int U, bool MULTI, int CL, typename ACC, bool PLANES>
-__global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *__restrict__ R, const GroupSet gs,
-                                                  int32_t K, int64_t Bs, uint4 *__restrict__ Ph, uint4 *__restrict__ Pl)
+__global__ __launch_bounds__(256) void k_prod_fwd(const float *__restrict__ l, float *__restrict__ lout, float *__restrict__ R,
+                                                  const GroupSet gs, int32_t K, int64_t Bs, uint4 *__restrict__ Ph,
+                                                  uint4 *__restrict__ Pl)
 {
     __shared__ float red[4][64];
     const GroupRow gr = locate_row<MULTI>(gs, blockIdx.x);
@@ -506,7 +509,7 @@ __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *
         for (int i = 0; i < RPT; ++i) {
             const int k = rg + RG * i;
             if (k < K)
-                *reinterpret_cast<float4 *>(l + (int64_t)(id + k) * Bs + b) =
+                *reinterpret_cast<float4 *>(lout + (int64_t)(id + k) * Bs + b) =
                     make_float4((float)(s[i].x - (ACC)sh[0]), (float)(s[i].y - (ACC)sh[1]), (float)(s[i].z - (ACC)sh[2]),
                                 (float)(s[i].w - (ACC)sh[3]));
         }
@@ -520,7 +523,7 @@ __global__ __launch_bounds__(256) void k_prod_fwd(float *__restrict__ l, float *
         constexpr int CTW = CL / 8;                                     // 32-column tiles of the workgroup
         for (int it = wave; it < (K / 16) * CTW; it += 4) {
             const int ks = it / CTW, ct = (int)blockIdx.y * CTW + it % CTW;
-            if (ct < n_ct) split_value_tile(l, PC_UP, (int64_t)id + 16 * ks, ct, n_ct, Bs, Ph, Pl, lane);
+            if (ct < n_ct) split_value_tile(lout, PC_UP, (int64_t)id + 16 * ks, ct, n_ct, Bs, Ph, Pl, lane);
         }
     }
 }
@@ -661,8 +664,8 @@ __device__ inline void lse_push(float &m, float &s, float t)
     else s += __expf(t - m);
 }
 
-__global__ __launch_bounds__(256) void k_sum_fwd_generic(const float *__restrict__ theta, float *__restrict__ l,
-                                                         float *__restrict__ R, const int32_t *__restrict__ ids,
+__global__ __launch_bounds__(256) void k_sum_fwd_generic(const float *__restrict__ theta, const float *__restrict__ lch,
+                                                         float *__restrict__ l, float *__restrict__ R, const int32_t *__restrict__ ids,
                                                          const int32_t *__restrict__ nbr, const int32_t *__restrict__ par,
                                                          int32_t n_rows, int32_t width, int32_t K, int64_t Bs)
 {
@@ -680,7 +683,7 @@ __global__ __launch_bounds__(256) void k_sum_fwd_generic(const float *__restrict
             const float d = R[(int64_t)(ns / K) * Bs + b] - Rn;
             for (int jj = 0; jj < K; ++jj) {
                 const float th = theta[(int64_t)ps + (int64_t)i * K + jj];
-                const float v = l[(int64_t)(ns + jj) * Bs + b] + d;
+                const float v = lch[(int64_t)(ns + jj) * Bs + b] + d;
                 if (th > 0.0f && v > PC_NEG_INF) lse_push(m, s, __logf(th) + v);
             }
         }
@@ -782,8 +785,8 @@ __device__ inline float pc_split_shift(float g) { return fminf(fmaxf(0.5f * (g -
 // (theta * 2^40) * sum = flow * 2^5.4
 __device__ inline float pc_flow_out(float th, float sum) { return ((th * 0x1p+40f) * sum) * (PC_SPLIT_OUT * 0x1p-40f); }
 template <int K>
-__global__ __launch_bounds__(256) void k_sum_fwd_small(const float *__restrict__ theta, float *__restrict__ l,
-                                                       float *__restrict__ R, const int32_t *__restrict__ ids,
+__global__ __launch_bounds__(256) void k_sum_fwd_small(const float *__restrict__ theta, const float *__restrict__ lch,
+                                                       float *__restrict__ l, float *__restrict__ R, const int32_t *__restrict__ ids,
                                                        const int32_t *__restrict__ nbr, const int32_t *__restrict__ par,
                                                        const int32_t *__restrict__ flags, int32_t width, int64_t Bs)
 {
@@ -811,7 +814,7 @@ __global__ __launch_bounds__(256) void k_sum_fwd_small(const float *__restrict__
 #pragma unroll
         for (int u = 0; u < U; ++u) {
 #pragma unroll
-            for (int jj = 0; jj < K; ++jj) vv[u][jj] = l[(int64_t)(nsv[u] + jj) * Bs + b];
+            for (int jj = 0; jj < K; ++jj) vv[u][jj] = lch[(int64_t)(nsv[u] + jj) * Bs + b];
             RBv[u] = R[(int64_t)(nsv[u] / K) * Bs + b];
         }
 #pragma unroll
@@ -1116,7 +1119,7 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
         float ar[NQ][RT], v[NQ];
         float rb, bm;
     };
-    const float *vsrc = BWD ? N : l;
+    const float *vsrc = N;                                              // forward: the children's log-probabilities (passed as N)
     int voff[4];                                                        // neighbour values: rows 0-3 of a group of 8 rows
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) voff[rr] = (int)(((int64_t)(4 * half + rr) * Bs + col) * 4);
@@ -2331,7 +2334,8 @@ static inline int32_t set_width(const GroupSet &gs)
     return w;
 }
 
-void launch_prod_fwd(float *l, float *R, const std::vector<GroupSet> &sets, int32_t K, int64_t Bs, void *Ph, void *Pl, hipStream_t s)
+void launch_prod_fwd(const float *l, float *lout, float *R, const std::vector<GroupSet> &sets, int32_t K, int64_t Bs, void *Ph, void *Pl,
+                     hipStream_t s)
 {
     uint4 *ph = (uint4 *)Ph, *pl = (uint4 *)Pl;                          // non-null: also write the bf16 value planes
     for (const GroupSet &gs : sets) {
@@ -2340,10 +2344,10 @@ void launch_prod_fwd(float *l, float *R, const std::vector<GroupSet> &sets, int3
         dim3 grid((unsigned)set_rows(gs), (unsigned)(narrow ? (Bs + 31) / 32 : (Bs + 63) / 64));
         // rows with more than eight children (leaf products over many variables) are summed in double
         if (ph && (K % 16) == 0) {
-            if (set_width(gs) > 8) PC_DISPATCH_PROD(PC_PROD_FWD_F64_P, grid, dim3(256), 0, s, l, R, gs, K, Bs, ph, pl);
-            else PC_DISPATCH_PROD(PC_PROD_FWD_F32_P, grid, dim3(256), 0, s, l, R, gs, K, Bs, ph, pl);
-        } else if (set_width(gs) > 8) PC_DISPATCH_PROD(PC_PROD_FWD_F64, grid, dim3(256), 0, s, l, R, gs, K, Bs, ph, pl);
-        else PC_DISPATCH_PROD(PC_PROD_FWD_F32, grid, dim3(256), 0, s, l, R, gs, K, Bs, ph, pl);
+            if (set_width(gs) > 8) PC_DISPATCH_PROD(PC_PROD_FWD_F64_P, grid, dim3(256), 0, s, l, lout, R, gs, K, Bs, ph, pl);
+            else PC_DISPATCH_PROD(PC_PROD_FWD_F32_P, grid, dim3(256), 0, s, l, lout, R, gs, K, Bs, ph, pl);
+        } else if (set_width(gs) > 8) PC_DISPATCH_PROD(PC_PROD_FWD_F64, grid, dim3(256), 0, s, l, lout, R, gs, K, Bs, ph, pl);
+        else PC_DISPATCH_PROD(PC_PROD_FWD_F32, grid, dim3(256), 0, s, l, lout, R, gs, K, Bs, ph, pl);
     }
 }
 
@@ -2392,8 +2396,8 @@ static void pick_sum_shape(int32_t K, int32_t n_rows, int32_t width, int64_t Bs,
     while (split < 4 && tiles * split < want && (int64_t)width * (K / 32) >= 2 * split) split <<= 1;
 }
 
-void launch_sum_fwd(const float *theta, float *l, float *R, const std::vector<GroupSet> &sets, int32_t K, int64_t Bs,
-                    hipStream_t s)
+void launch_sum_fwd(const float *theta, const float *lch, float *l, float *R, const std::vector<GroupSet> &sets, int32_t K,
+                    int64_t Bs, hipStream_t s)
 {
     if (use_mfma(K)) {
         for (const GroupSet &gs : sets) {
@@ -2406,7 +2410,7 @@ void launch_sum_fwd(const float *theta, float *l, float *R, const std::vector<Gr
             // long reductions at two waves per SIMD or fewer: see WAIT_ALL in the kernel
             const bool wait_all = (int64_t)set_width(gs) * (K / 32) >= 16 * split && (int64_t)grid.x * grid.y * 4 <= 2048;
             (void)wait_all;
-            PC_DISPATCH_SUM(false, grid, dim3(256), 0, s, theta, l, R, (const float *)nullptr, (const float *)nullptr,
+            PC_DISPATCH_SUM(false, grid, dim3(256), 0, s, theta, l, R, lch, (const float *)nullptr,
                             (float *)nullptr, gs, Bs);
         }
         return;
@@ -2417,10 +2421,10 @@ void launch_sum_fwd(const float *theta, float *l, float *R, const std::vector<Gr
         Timed timed(KC_SUM_FWD, s);
         if (use_small(K)) {
             dim3 grid((unsigned)g.n_rows, (unsigned)((Bs + 255) / 256));
-            PC_DISPATCH_SMALL(k_sum_fwd_small, grid, dim3(256), 0, s, theta, l, R, g.ids, g.nbr, g.par, g.aux, g.width, Bs);
+            PC_DISPATCH_SMALL(k_sum_fwd_small, grid, dim3(256), 0, s, theta, lch, l, R, g.ids, g.nbr, g.par, g.aux, g.width, Bs);
         } else {
             const int64_t items = (int64_t)g.n_rows * K * Bs;
-            hipLaunchKernelGGL(k_sum_fwd_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, l, R, g.ids, g.nbr, g.par,
+            hipLaunchKernelGGL(k_sum_fwd_generic, dim3(grid_for(items)), dim3(256), 0, s, theta, lch, l, R, g.ids, g.nbr, g.par,
                                g.n_rows, g.width, K, Bs);
         }
     }

@@ -59,6 +59,7 @@ class Workload:
     max_groups: int = 8
     tol_permille: int = 250
     meta: dict = field(default_factory=dict)
+    product_scratch: int = 0   # 1: compile in the memory-saving mode of Sec. 5 (needs the block order of pc_order_for_scratch)
 
     @property
     def B(self) -> int:

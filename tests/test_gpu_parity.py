@@ -316,6 +316,49 @@ def test_collapsed_non_alternating_dag(make):
     assert_logprob_close(got["ll"], orc.forward(w, w.theta, w.tables, w.x)[1], "ll against the original DAG")
 
 
+@pytest.mark.parametrize("make", [
+    lambda: W.reduced(5),                                  # pruned PD: product blocks of several depths feed one sum layer
+    lambda: W.reduced(2, B=70),                            # HCLT
+    lambda: W.reduced(4, K=32),                            # tied HMM: parameter flows accumulate layer by layer
+    lambda: W.reduced(6),                                  # RAT-SPN
+    lambda: W.hclt(9, 16, 4, 90, 14, n_cats=7),            # K = 4: vector-ALU kernels
+    lambda: W.hmm(4, 6, 5, 3, 7, 7),                       # K = 3: generic kernels
+])
+def test_product_scratch_mode(make):
+    """Sec. 5: product log-probabilities live in one scratch window and are recomputed in the backward pass.  Same
+    results as the oracle on the reordered circuit; the workspace is smaller; compiled tables bit-exact."""
+    w0 = make()
+    w = pcb.pc_order_for_scratch(w0)
+    assert w.product_scratch == 1
+    print(f"case product scratch {w.name}", flush=True)
+    ref = oracle_run(w)
+    c = pcb.Circuit(w)
+    assert_device_tables_match_oracle(c.handle, w)
+    c0 = pcb.Circuit(w0)
+    assert pcb.pc_workspace_bytes(c.handle, w.B) < pcb.pc_workspace_bytes(c0.handle, w.B)
+    c0.close()
+    c.set_batch(w.x)
+    c._ws.fill_(255)
+    ll = c.forward().double().cpu().numpy()
+    c.backward()
+    torch.cuda.synchronize()
+    assert_logprob_close(ll, ref["ll"], "ll")
+    K, B = w.K, w.B
+    l, F, R = c.node_buffers()
+    keep = np.repeat(w.type != W.PRODUCT, K)               # product rows of l are not kept in this mode
+    n_keep = int((w.type != W.PRODUCT).sum())
+    lp = (l[K:(n_keep + 1) * K, :B].double() + R[1:n_keep + 1, :B].double().repeat_interleave(K, dim=0)).cpu().numpy().T
+    assert_logprob_close(lp, ref["lp"][:, keep], "log-probabilities of input and sum nodes")
+    fl = flow_floors(w, w.theta, ref, B)
+    assert_flow_close(to_user_rows(F, K, B), ref["flow"], "node flows", fl["flow"])
+    assert_flow_close(c.theta_flow.double().cpu().numpy().reshape(w.theta.shape), ref["theta_flow"], "theta flows", fl["theta_flow"])
+    assert_flow_close(c.table_flow.double().cpu().numpy().reshape(w.tables.shape), ref["table_flow"], "table flows", fl["table_flow"])
+    # the same results as the circuit in its original block order, block by block
+    ref0 = oracle_run(w0)
+    assert np.array_equal(ref["ll"], ref0["ll"])
+    c.close()
+
+
 def test_config1_full_size():
     w = W.config(1)
     print("case cfg1 full", flush=True)
