@@ -124,6 +124,8 @@ def main():
     ap.add_argument("--config", default="4", help="1..5, the configurations of BASELINE.json; 'rat' = the RAT-SPN stand-in")
     ap.add_argument("--batch", type=int, default=None, help="batch size (default per configuration)")
     ap.add_argument("--K", type=int, default=None, help="node block size (default per config)")
+    ap.add_argument("--product-scratch", action="store_true",
+                    help="compile in the memory-saving mode of Sec. 5 (product values in one scratch window, recomputed in the backward pass)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-em", action="store_true", help="skip the secondary timing that adds pc_em_step")
     args = ap.parse_args()
@@ -138,6 +140,8 @@ def main():
 
     t0 = time.time()
     w = W.rat_config(K=args.K, B=args.batch) if args.config == "rat" else W.config(int(args.config), K=args.K, B=args.batch)
+    if args.product_scratch:
+        w = pcb.pc_order_for_scratch(w)
     gen_s = time.time() - t0
     work, Es = algorithmic_work(w)
 
@@ -244,7 +248,8 @@ def main():
         "dtype": "bf16x3->f32 (fp32 operands split into two bf16 values, three bf16 MFMAs per product, fp32 accumulation)" if any_bf16 else "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "structure": w.meta["kind"], "K": w.K, "batch": B, "sum_edges": Es,
-                   "n_blocks": w.n_blocks, "n_layers": c.sizes.n_layers},
+                   "n_blocks": w.n_blocks, "n_layers": c.sizes.n_layers, "product_scratch": bool(args.product_scratch),
+                   "workspace_bytes": pcb.pc_workspace_bytes(c.handle, B)},
         "roofline": roofline, "measured_peak": measured_peak, "cpu_baseline": cpu, "kernels": kernels, "with_em_step": em,
         "compile_s": compile_s, "generate_s": gen_s,
     }

@@ -106,9 +106,11 @@ typedef struct pc_collapsed pc_collapsed;
 pc_status pc_collapse(const pc_dag *dag, const float *theta, pc_collapsed **out);
 /* Block order for product_scratch = 1 (Sec. 5, product values recomputed): the same DAG with its blocks renumbered --
  * input and sum blocks first (relative order kept), then the product blocks grouped by the depth of the sum blocks
- * that read them, so that the product blocks a sum layer reads are one contiguous range of ids.  PC_ERR_ARG if a
- * product block is read by sum blocks of different depths (the mode does not apply).  Parameter block ids do not
- * change; the result (pc_collapsed_dag, pc_collapsed_block_map; product_scratch already set) is owned by the handle. */
+ * that read them, so that the product blocks a sum layer reads are one contiguous range of ids.  A product block read
+ * by sum blocks of several depths is copied, one copy per depth (it is then evaluated once for each of them; product
+ * blocks carry no parameters, so log-likelihoods and parameter flows are those of the original circuit).  Parameter
+ * block ids do not change; the result (pc_collapsed_dag; pc_collapsed_block_map: old id -> new id, for a copied block
+ * its first copy; product_scratch already set) is owned by the handle. */
 pc_status pc_order_for_scratch(const pc_dag *dag, pc_collapsed **out);
 const pc_dag *pc_collapsed_dag(const pc_collapsed *r);
 const float *pc_collapsed_theta(const pc_collapsed *r, int64_t *len);   /* [n_param_blocks + 1][K][K], block 0 zero */
@@ -161,8 +163,9 @@ typedef struct {
     int64_t stride;            /* floats between consecutive rows                               */
     size_t l_offset, f_offset, n_offset, r_offset;   /* byte offsets into the workspace         */
     size_t total_bytes;
-    int64_t l_rows;            /* rows of l: n_rows, or with product_scratch the null, input and sum blocks followed by
-                                  the window of the largest product layer (product rows are not kept)   */
+    int64_t l_rows;            /* rows of l and F: n_rows, or with product_scratch the null, input and sum blocks followed by
+                                  the window of the largest product layer (product rows are not kept; N then has the
+                                  null, input and sum rows only)                                           */
 } pc_ws_layout;
 pc_status pc_workspace_layout(const pc_circuit *c, int32_t B, pc_ws_layout *out);
 pc_status pc_workspace_bytes(const pc_circuit *c, int32_t B, size_t *bytes);

@@ -183,7 +183,8 @@ def pc_collapse(w):
 
 def pc_order_for_scratch(w):
     """Sec. 5, product-scratch mode: a copy of `w` with its blocks renumbered (input and sum blocks first, product
-    blocks grouped by the sum layer that reads them), `product_scratch` set and `block_map` (old id -> new id)."""
+    blocks grouped by the sum layer that reads them, copied where sum layers of several depths read them),
+    `product_scratch` set and `block_map` (old id -> new id)."""
     return _rewritten(w, collapse=False)
 
 
@@ -389,6 +390,6 @@ class Circuit:
         nb = (self.sizes.n_blocks + 1) * lay.stride
         f32 = self.torch.float32
         l = self._ws[lay.l_offset:lay.l_offset + 4 * lay.l_rows * lay.stride].view(f32).view(lay.l_rows, lay.stride)
-        F = self._ws[lay.f_offset:lay.f_offset + 4 * n].view(f32).view(self.sizes.n_rows, lay.stride)
+        F = self._ws[lay.f_offset:lay.f_offset + 4 * lay.l_rows * lay.stride].view(f32).view(lay.l_rows, lay.stride)
         R = self._ws[lay.r_offset:lay.r_offset + 4 * nb].view(f32).view(self.sizes.n_blocks + 1, lay.stride)
         return l, F, R

@@ -156,9 +156,13 @@ static Ws ws_layout(const pc_circuit *c, int32_t B)
     // product-scratch mode: l holds the null block, the input and sum blocks and one window for the largest product layer
     w.l_rows = c->product_scratch ? ((int64_t)c->n_persistent_blocks + 1 + c->max_window_blocks) * c->K : (int64_t)rows;
     const size_t lnode = align_up((size_t)w.l_rows * w.Bs * 4, 256);
-    w.l_off = 0; w.f_off = lnode; w.n_off = lnode + node;
+    // ... and so does F (a product layer's flows are written by the sum layer above it and read by the layer itself right
+    // after); log_nf exists for sum rows only, which are among the persistent ones
+    const size_t fnode = c->product_scratch ? lnode : node;
+    const size_t nnode = c->product_scratch ? align_up(((size_t)c->n_persistent_blocks + 1) * c->K * w.Bs * 4, 256) : node;
+    w.l_off = 0; w.f_off = lnode; w.n_off = lnode + fnode;
     const size_t per_block = align_up(((size_t)c->n_blocks + 1) * w.Bs * 4, 256);
-    w.r_off = lnode + 2 * node;
+    w.r_off = lnode + fnode + nnode;
     w.mx_off = w.r_off + per_block;
     w.xt_off = w.mx_off + per_block;
     w.total = w.xt_off + align_up((size_t)c->n_vars * w.Bs * 4, 256);
@@ -424,7 +428,7 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
             const LayerTab &P = c->layers[li - 1];
             float *lp = window_base(c, P, l, w.Bs);
             launch_prod_fwd(l, lp, const_cast<float *>(R), plan.layers[li - 1].fwd, K, w.Bs, nullptr, nullptr, s);
-            launch_sum_bwd_child(theta, lp, R, N, nfmax, F, plan.layers[li].bwd, K, w.Bs, s);
+            launch_sum_bwd_child(theta, lp, R, N, nfmax, window_base(c, P, F, w.Bs), plan.layers[li].bwd, K, w.Bs, s);
             if (theta_flow && batched_params) {
                 ParamFlowDev pf{(int32_t)L.pf_pb.size(), L.d_pf_pb, L.d_pf_ptr, L.d_pf_sum, L.d_pf_child, (int64_t)L.pf_sum.size()};
                 launch_param_flow(theta, lp, R, N, nfmax, theta_flow, pf, K, w.Bs, s);
@@ -435,8 +439,14 @@ pc_status pc_backward(pc_circuit *c, const float *theta, const float *tables, co
             launch_sum_bwd_child(theta, l, R, N, nfmax, F, plan.layers[li].bwd, K, w.Bs, s);
             if (theta_flow && !batched_params)
                 for (const GroupTab &g : L.fwd) launch_sum_bwd_param_generic(theta, l, R, N, theta_flow, dev(g), K, w.Bs, B, s);
+        } else if (L.kind == KIND_PRODUCT && c->product_scratch) {
+            float *Fw = window_base(c, L, F, w.Bs);
+            // the layer of product blocks nobody reads (the last one) has flow 0
+            if (li + 1 == c->layers.size())
+                launch_fill(Fw + (int64_t)(L.scr_first_block + 1) * K * w.Bs, (int64_t)L.blk_ids.size() * K * w.Bs, 0.0f, s);
+            launch_prod_bwd(l, F, Fw, N, nfmax, plan.layers[li].bwd, K, w.Bs, nullptr, nullptr, s);
         } else if (L.kind == KIND_PRODUCT) {
-            launch_prod_bwd(l, F, N, nfmax, plan.layers[li].bwd, K, w.Bs, w.bf16 ? base + w.ph_off : nullptr, w.bf16 ? base + w.pl_off : nullptr, s);
+            launch_prod_bwd(l, F, F, N, nfmax, plan.layers[li].bwd, K, w.Bs, w.bf16 ? base + w.ph_off : nullptr, w.bf16 ? base + w.pl_off : nullptr, s);
         } else if (table_flow) {
             launch_input_bwd(F, xT, dev(L.fwd[0]), K, c->n_cats, w.Bs, table_flow, s);
         }

@@ -240,35 +240,44 @@ pc_status pc_order_for_scratch(const pc_dag *dag, pc_collapsed **out)
         }
     }
     if ((int32_t)order.size() != n) return fail(PC_ERR_CYCLE, "the block graph has a cycle");
-    // product blocks: key = depth of their readers (all of one depth, else the mode does not apply); unread ones last
+    // product blocks: one copy per depth of the sum blocks that read them (a copy is read by sum blocks of one depth only
+    // and can be evaluated right before them); key = that depth, unread blocks last
+    const int64_t kUnread = (int64_t)1 << 40;
     std::vector<std::pair<int64_t, int32_t>> keyed;                     // (group key, old id)
     for (int32_t u = 0; u < n; ++u) {
         if (dag->type[u] != KIND_PRODUCT) { keyed.emplace_back(-1, u); continue; }
-        int64_t key = (int64_t)1 << 40;
-        for (int32_t p : parents[u]) {
-            if (key != ((int64_t)1 << 40) && key != depth[p])
-                return fail(PC_ERR_ARG, "product block " + std::to_string(u) + " is read by sum blocks of different depths");
-            key = depth[p];
-        }
-        keyed.emplace_back(key, u);
+        std::vector<int32_t> ds;
+        for (int32_t p : parents[u]) ds.push_back(depth[p]);
+        std::sort(ds.begin(), ds.end());
+        ds.erase(std::unique(ds.begin(), ds.end()), ds.end());
+        if (ds.empty()) keyed.emplace_back(kUnread, u);
+        for (int32_t dd : ds) keyed.emplace_back(dd, u);
     }
     std::stable_sort(keyed.begin(), keyed.end(), [](const std::pair<int64_t, int32_t> &a, const std::pair<int64_t, int32_t> &b) { return a.first < b.first; });
+    const int32_t n_new = (int32_t)keyed.size();
     pc_collapsed *r = new (std::nothrow) pc_collapsed();
     if (!r) return fail(PC_ERR_ARG, "out of host memory");
     r->block_map.assign((size_t)n, -1);
-    for (int32_t i = 0; i < n; ++i) r->block_map[keyed[i].second] = i;
+    std::map<std::pair<int32_t, int64_t>, int32_t> copy_of;             // (old product id, reader depth) -> new id
+    for (int32_t i = 0; i < n_new; ++i) {
+        if (r->block_map[keyed[i].second] < 0) r->block_map[keyed[i].second] = i;     // a product block: its first copy
+        copy_of[{keyed[i].second, keyed[i].first}] = i;
+    }
     r->child_ptr.push_back(0);
-    for (int32_t i = 0; i < n; ++i) {
+    for (int32_t i = 0; i < n_new; ++i) {
         const int32_t u = keyed[i].second;
         r->type.push_back(dag->type[u]); r->n_real.push_back(dag->n_real[u]);
         r->in_var.push_back(dag->in_var[u]); r->in_table.push_back(dag->in_table[u]);
         for (int64_t e = dag->child_ptr[u]; e < dag->child_ptr[u + 1]; ++e) {
-            r->child.push_back(r->block_map[dag->child[e]]);
+            const int32_t ch = dag->child[e];
+            // a sum block reads the copy made for its depth; everything else keeps its one image
+            r->child.push_back(dag->type[u] == KIND_SUM && dag->type[ch] == KIND_PRODUCT ? copy_of[{ch, (int64_t)depth[u]}] : r->block_map[ch]);
             r->param_blk.push_back(dag->param_blk[e]);
         }
         r->child_ptr.push_back((int64_t)r->child.size());
     }
     r->dag = *dag;
+    r->dag.n_blocks = n_new;
     r->dag.root_block = r->block_map[dag->root_block];
     r->dag.type = r->type.data(); r->dag.n_real = r->n_real.data();
     r->dag.child_ptr = r->child_ptr.data(); r->dag.child = r->child.data(); r->dag.param_blk = r->param_blk.data();

@@ -240,8 +240,11 @@ pc_status compile_host(const pc_dag *d, pc_circuit *c, bool tables_on_host)
     // other blocks and the null block as ~offset (flow zeroed only)
     c->init_ids.clear();
     c->init_ids.push_back(~0);
+    // (product-scratch mode: product blocks nobody reads are the last layer; their window is cleared when the backward
+    // sweep reaches it, and their rows do not exist in the flow buffer)
     for (int32_t u = 0; u < n; ++u)
-        if (last_parent_depth[u] < 0) c->init_ids.push_back(d->type[u] == KIND_SUM ? (u + 1) * K : ~((u + 1) * K));
+        if (last_parent_depth[u] < 0 && !(c->product_scratch && d->type[u] == KIND_PRODUCT))
+            c->init_ids.push_back(d->type[u] == KIND_SUM ? (u + 1) * K : ~((u + 1) * K));
 
     c->K = K; c->n_blocks = n; c->root_block = d->root_block; c->n_param_blocks = d->n_param_blocks;
     c->n_vars = d->n_vars; c->n_cats = d->n_cats; c->n_tables = d->n_tables;

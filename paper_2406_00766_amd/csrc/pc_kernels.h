@@ -73,7 +73,8 @@ std::vector<GroupSet> make_group_sets(const std::vector<GroupDev> &groups);
 // l: base the children are read from, lout: base the products are written to (the same, except in the product-scratch mode)
 void launch_prod_fwd(const float *l, float *lout, float *R, const std::vector<GroupSet> &sets, int32_t K, int64_t Bs, void *Ph, void *Pl,
                      hipStream_t s);
-void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const std::vector<GroupSet> &sets, int32_t K,
+// Fpar: base the parents' flows are read from (= F, except in the product-scratch mode)
+void launch_prod_bwd(const float *l, float *F, const float *Fpar, float *N, float *nfmax, const std::vector<GroupSet> &sets, int32_t K,
                      int64_t Bs, void *Ph, void *Pl, hipStream_t s);
 // lch: base the product children are read from; l: base of the sum rows written
 void launch_sum_fwd(const float *theta, const float *lch, float *l, float *R, const std::vector<GroupSet> &sets, int32_t K,

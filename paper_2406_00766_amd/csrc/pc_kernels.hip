@@ -532,10 +532,12 @@ __global__ __launch_bounds__(256) void k_prod_fwd(const float *__restrict__ l, f
 // F_child += sum of the parents' flows ('=' where this is the first layer that feeds the block, flag bit 1, so
 // the flow buffer is never cleared).  Where this layer is the last one that feeds a SUM block (flag bit 0) its
 // flow is final, so log_nf = log F - l (Alg. 3 / 4) and its column maximum per block are produced here.
+// `Fpar` is the base the parents' (product blocks') flows are read from, `F` the base of the rows' own flows: the same
+// buffer, except in the product-scratch mode, where product rows live in a window.
 template <int RPT, int U, bool MULTI, int CL, bool PLANES>
-__global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, float *__restrict__ F, float *__restrict__ N,
-                                                  float *__restrict__ nfmax, const GroupSet gs, int32_t K, int64_t Bs,
-                                                  uint4 *__restrict__ Ph, uint4 *__restrict__ Pl)
+__global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, float *__restrict__ F, const float *__restrict__ Fpar,
+                                                  float *__restrict__ N, float *__restrict__ nfmax, const GroupSet gs, int32_t K,
+                                                  int64_t Bs, uint4 *__restrict__ Ph, uint4 *__restrict__ Pl)
 {
     __shared__ float red[4][64];
     const GroupRow gr = locate_row<MULTI>(gs, blockIdx.x);
@@ -571,7 +573,7 @@ __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, f
 #pragma unroll
                 for (int i = 0; i < RPT; ++i) {
                     const int k = rg + RG * i;
-                    t[u][i] = (on && k < K) ? *reinterpret_cast<const float4 *>(F + (int64_t)(pa[u] + k) * Bs + b)
+                    t[u][i] = (on && k < K) ? *reinterpret_cast<const float4 *>(Fpar + (int64_t)(pa[u] + k) * Bs + b)
                                             : make_float4(0.f, 0.f, 0.f, 0.f);
                 }
             }
@@ -2351,7 +2353,7 @@ void launch_prod_fwd(const float *l, float *lout, float *R, const std::vector<Gr
     }
 }
 
-void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const std::vector<GroupSet> &sets, int32_t K,
+void launch_prod_bwd(const float *l, float *F, const float *Fpar, float *N, float *nfmax, const std::vector<GroupSet> &sets, int32_t K,
                      int64_t Bs, void *Ph, void *Pl, hipStream_t s)
 {
     uint4 *ph = (uint4 *)Ph, *pl = (uint4 *)Pl;                          // non-null: also write the bf16 planes of finished sum blocks
@@ -2359,8 +2361,8 @@ void launch_prod_bwd(const float *l, float *F, float *N, float *nfmax, const std
         Timed timed(KC_PROD_BWD, s);
         const bool narrow = prod_narrow(gs, Bs);
         dim3 grid((unsigned)set_rows(gs), (unsigned)(narrow ? (Bs + 31) / 32 : (Bs + 63) / 64));
-        if (ph && (K % 16) == 0) PC_DISPATCH_PROD(PC_PROD_BWD_P, grid, dim3(256), 0, s, l, F, N, nfmax, gs, K, Bs, ph, pl);
-        else PC_DISPATCH_PROD(PC_PROD_BWD, grid, dim3(256), 0, s, l, F, N, nfmax, gs, K, Bs, ph, pl);
+        if (ph && (K % 16) == 0) PC_DISPATCH_PROD(PC_PROD_BWD_P, grid, dim3(256), 0, s, l, F, Fpar, N, nfmax, gs, K, Bs, ph, pl);
+        else PC_DISPATCH_PROD(PC_PROD_BWD, grid, dim3(256), 0, s, l, F, Fpar, N, nfmax, gs, K, Bs, ph, pl);
     }
 }
 

@@ -98,3 +98,47 @@ def test_full_size_config(label, make, n):
     assert_flow_close(c.theta_flow.double().cpu().numpy().reshape(w.theta.shape), ref_tf, "theta flows", floors["theta_flow"])
     assert_flow_close(c.table_flow.double().cpu().numpy().reshape(w.tables.shape), ref_gf, "table flows", floors["table_flow"])
     c.close()
+
+
+def test_config5_in_product_scratch_mode():
+    """Sec. 5 at full size: config 5 compiled with product_scratch = 1 (block order of pc_order_for_scratch).  The
+    workspace shrinks; log-likelihoods, the flows of input and sum nodes and -- on the oracle's samples repeated over
+    the whole batch -- every parameter and table flow match the oracle."""
+    print("case full-size config 5, product scratch: generating", flush=True)
+    w0 = W.config(5)
+    w = pcb.pc_order_for_scratch(w0)
+    K, B, n = w.K, w.B, 4
+    c = pcb.Circuit(w)
+    assert_device_tables_match_oracle(c.handle, w)
+    h0 = pcb.pc_compile(w0, host_only=True)
+    full, small = pcb.pc_workspace_bytes(h0, B), pcb.pc_workspace_bytes(c.handle, B)
+    pcb.pc_destroy(h0)
+    print(f"  workspace {small / 2**30:.2f} GiB against {full / 2**30:.2f} GiB", flush=True)
+    assert small < 0.6 * full
+    wb = w.with_batch(w.x[:n])
+    ref_ll, ref_lp, ref_flow, ref_tf, ref_gf = orc.backward(wb, w.theta, w.tables, wb.x)
+    floors = flow_floors(wb, w.theta, {"lp": ref_lp, "flow": ref_flow}, n)
+    c.set_batch(w.x)
+    c._ws.fill_(255)
+    ll = c.forward().double().cpu().numpy()
+    c.backward()
+    torch.cuda.synchronize()
+    assert np.all(np.isfinite(ll))
+    assert_logprob_close(ll[:n], ref_ll, "ll")
+    l, F, R = c.node_buffers()
+    keep = np.repeat(w.type != W.PRODUCT, K)
+    n_keep = int((w.type != W.PRODUCT).sum())
+    lp = (l[K:(n_keep + 1) * K, :n].double() + R[1:n_keep + 1, :n].double().repeat_interleave(K, dim=0)).cpu().numpy().T
+    assert_logprob_close(lp, ref_lp[:, keep], "log-probabilities of input and sum nodes")
+    assert_flow_close(F[K:(n_keep + 1) * K, :n].double().cpu().numpy().T.copy(), ref_flow[:, keep], "flows of input and sum nodes",
+                      floors["flow"])
+    reps = B // n
+    c.theta_flow.zero_(); c.table_flow.zero_()
+    c.set_batch(np.tile(wb.x, (reps, 1)))
+    c.forward(); c.backward()
+    torch.cuda.synchronize()
+    assert_flow_close(c.theta_flow.double().cpu().numpy().reshape(w.theta.shape), reps * ref_tf, "theta flows, full batch",
+                      reps * floors["theta_flow"])
+    assert_flow_close(c.table_flow.double().cpu().numpy().reshape(w.tables.shape), reps * ref_gf, "table flows, full batch",
+                      reps * floors["table_flow"])
+    c.close()
