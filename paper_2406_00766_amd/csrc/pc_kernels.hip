@@ -1289,6 +1289,18 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
     const __amdgpu_buffer_rsrc_t ro =
         __builtin_amdgcn_make_buffer_rsrc((void *)(out + (int64_t)(id + sub * TM) * Bs), 0, PC_BUF_RANGE, PC_BUF_FLAGS);
     const float mb = (m - PC_UP) * PC_LOG2E;
+    // backward, a block that earlier layers of the sweep have fed already: its flows so far are all requested before the
+    // first is used (a load inside the per-element branch is waited for on its own, once per element)
+    floatx16 fold[BWD ? RT : 1];
+    if (BWD && !first) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int so = __builtin_amdgcn_readfirstlane((int)((int64_t)(rt * 32 + 8 * (e / 4) + (e % 4)) * Bs * 4));
+                fold[rt][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ro, ooff, so, 0));
+            }
+    }
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
@@ -1300,12 +1312,8 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
                 const float lc = lown[rt][e];
                 // exp(ln a + (m - PC_UP) + lc); a = 0 or lc = -inf gives exp2(-inf) = 0
                 const float add = __builtin_amdgcn_exp2f(lg + fmaf(lc, PC_LOG2E, mb));
-                if (first) {
-                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, add), ro, ooff, so, 0);
-                } else if (add > 0.0f) {
-                    const float old = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ro, ooff, so, 0));
-                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, old + add), ro, ooff, so, 0);
-                }
+                const float out_v = first ? add : fold[rt][e] + add;
+                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, out_v), ro, ooff, so, 0);
             } else {
                 // ln a + (m - PC_UP), with the logarithm taken of a / 2^24: the accumulator of a live column is around
                 // e^PC_UP, and a base-2 logarithm near 0 is far more accurate in absolute terms than one near 29 --
@@ -1520,6 +1528,19 @@ __global__ __launch_bounds__(256, 2) void k_sum_bf16(const uint4 *__restrict__ T
     }
     if (!BWD && sub == 0 && half == 0) R[(int64_t)(id / K) * Bs + col] = m;
     const bool first = (fl & 2) != 0;                                   // backward: the first layer that feeds the block stores
+    // backward: the rows' own log-probabilities (and, where this layer accumulates, the flows so far) are all requested
+    // before the first of them is used -- a load inside the per-element branch would be waited for on its own, 32 times
+    floatx16 lown[2], fold[2];
+    if (BWD) {
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int64_t at = (int64_t)(id + sub * 64 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4)) * Bs + col;
+                lown[rt][e] = l[at];
+                fold[rt][e] = first ? 0.0f : F[at];
+            }
+    }
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
@@ -1530,11 +1551,10 @@ __global__ __launch_bounds__(256, 2) void k_sum_bf16(const uint4 *__restrict__ T
                 // ln(sum) - PC_UP, the logarithm taken of sum / 2^24 (see the fp32 kernel)
                 l[at] = fmaf(__builtin_amdgcn_logf(acc[rt][e] * 0x1p-24f), 0.6931471805599453f, 16.635532333f - PC_UP);
             } else {
-                // exp(ln(sum) + (m - PC_UP) + l_row); sum = 0 or l_row = -inf gives 0
+                // exp(ln(sum) + (m - PC_UP) + l_row); sum = 0 or l_row = -inf gives exp2(-inf) = 0
                 const float lg = __builtin_amdgcn_logf(acc[rt][e]);
-                const float add = acc[rt][e] > 0.0f ? __builtin_amdgcn_exp2f(lg + (l[at] + (m - PC_UP)) * PC_LOG2E) : 0.0f;
-                if (first) F[at] = add;
-                else if (add > 0.0f) F[at] += add;
+                const float add = __builtin_amdgcn_exp2f(lg + (lown[rt][e] + (m - PC_UP)) * PC_LOG2E);
+                F[at] = fold[rt][e] + (m > PC_NEG_INF ? add : 0.0f);
             }
         }
 }

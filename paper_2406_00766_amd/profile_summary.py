@@ -22,7 +22,10 @@ def kernel_class(name: str) -> str:
     m = re.match(r"k_sum_mfma<\s*\d+,\s*\d+,\s*\d+,\s*(true|false)", n)
     if m:
         return "sum_bwd_child" if m.group(1) == "true" else "sum_fwd"
-    for prefix, cls in (("k_sum_fwd", "sum_fwd"), ("k_sum_bwd_child", "sum_bwd_child"), ("k_sum_bwd_small", "sum_bwd_child"),
+    m = re.match(r"k_sum_bf16<\s*\d+,\s*\d+,\s*(true|false)", n)
+    if m:
+        return "sum_bwd_child" if m.group(1) == "true" else "sum_fwd"
+    for prefix, cls in (("k_split_", "split"), ("k_sum_fwd", "sum_fwd"), ("k_sum_bwd_child", "sum_bwd_child"), ("k_sum_bwd_small", "sum_bwd_child"),
                         ("k_sum_bwd_param", "sum_bwd_param"), ("k_param_flow", "sum_bwd_param"), ("k_prod_fwd", "prod_fwd"),
                         ("k_prod_bwd", "prod_bwd"), ("k_input_fwd", "input_fwd"), ("k_input_bwd", "input_bwd"), ("k_em_", "em"),
                         ("k_measure_copy", "measure_copy"), ("k_measure_mfma", "measure_mfma")):
