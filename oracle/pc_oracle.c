@@ -19,7 +19,10 @@
  * Node (u, k) = node k of block u has index u*K + k.  Sum edge e = (u -> c) with parameter
  * block p: weight of (u,i) -> (c,j) is theta[(p+1)*K*K + i*K + j] (block 0 of theta is unused
  * padding).  Product block u: node (u,k) has children (c,k) for every child block c.
- * Input block u on variable v with table t: f(x) = tables[(t*n_cats + x_v)*K + k].
+ * Input block u on variable v with table t: f(x) = tables[(t*n_cats + x_v)*K + k]; a value x_v
+ * outside 0..n_cats-1 has f(x) = 0, so the sample's likelihood is 0 and (every node on a path
+ * from the root has that variable in its scope, hence probability 0, and a sum node of
+ * probability 0 passes no flow on) the sample adds nothing to any accumulated flow.
  *
  * Parallelism: OpenMP over samples (forward, node flows) or over the row index inside a
  * block (parameter flows), so no two threads ever add into the same accumulator.
@@ -113,7 +116,10 @@ int orc_forward(int32_t K, int32_t n_blocks, int32_t root_block, const uint8_t *
                             v = 0.0;                                   /* marginalised: p = 1 */
                         } else {
                             const int32_t xv = x[(int64_t)b * n_vars + var];
-                            v = log((double)tables[((int64_t)in_table[u] * n_cats + xv) * K + k]);
+                            /* a value outside 0..n_cats-1 is outside the support of the categorical
+                             * distribution: f(x) = 0 (Def. 1 with f_n a probability mass function) */
+                            v = (xv < 0 || xv >= n_cats) ? -INFINITY
+                                : log((double)tables[((int64_t)in_table[u] * n_cats + xv) * K + k]);
                         }
                     } else if (type[u] == T_PRODUCT) {
                         v = 0.0;
@@ -202,6 +208,7 @@ int orc_param_flows(int32_t K, int32_t n_blocks, const uint8_t *type,
                     const int32_t var = in_var[u];
                     if (mask && mask[(int64_t)b * n_vars + var]) continue;
                     const int32_t xv = x[(int64_t)b * n_vars + var];
+                    if (xv < 0 || xv >= n_cats) continue;               /* p(x) = 0: no table entry to credit */
                     table_flow[((int64_t)in_table[u] * n_cats + xv) * K + k] += Fn;
                 } else if (type[u] == T_SUM) {
                     const double Ln = L[(int64_t)u * K + k];

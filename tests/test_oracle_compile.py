@@ -170,6 +170,35 @@ def test_table_invariants(make):
     assert comp["n_rows"] == (w.n_blocks + 1) * K
 
 
+@pytest.mark.parametrize("make", [lambda: W.reduced(i) for i in range(1, 7)] +
+                         [lambda: W.random_circuit(5, 4, 3, 2, 3, 311), lambda: W.random_circuit(6, 6, 4, 4, 3, 312),
+                          lambda: W.config(2, draw=False)])
+def test_depth_is_the_longest_path_and_children_run_in_earlier_layers(make):
+    """Sec. 3 layering: a block can be evaluated once all its children have been, so every child must sit in a layer
+    that runs earlier.  The depth itself is pinned against a brute-force longest path to an input block (memoised
+    recursion over the children lists, written independently of the oracle's pass)."""
+    import functools
+    import sys
+    w = make()
+    depth = co.block_depths(w)
+    sys.setrecursionlimit(max(sys.getrecursionlimit(), 4 * w.n_blocks + 1000))
+
+    @functools.lru_cache(maxsize=None)
+    def longest(u):
+        ch = w.child[w.child_ptr[u]:w.child_ptr[u + 1]]
+        return 0 if len(ch) == 0 else 1 + max(longest(int(c)) for c in ch)
+
+    assert [longest(u) for u in range(w.n_blocks)] == [int(d) for d in depth]
+    comp = co.compile_tables(w)
+    position = {(l["kind"], l["depth"]): i for i, l in enumerate(comp["layers"])}
+    for u in range(w.n_blocks):
+        mine = position[(int(w.type[u]), int(depth[u]) if w.type[u] != W.INPUT else comp["layers"][0]["depth"])]
+        for c in w.child[w.child_ptr[u]:w.child_ptr[u + 1]]:
+            kind_c = int(w.type[c])
+            theirs = position[(kind_c, int(depth[c]) if kind_c != W.INPUT else comp["layers"][0]["depth"])]
+            assert depth[c] < depth[u] and theirs < mine
+
+
 def test_validation_errors():
     w = W.hmm(3, 2, 3, 2, 1, 52)
     bad = w.with_batch(w.x)

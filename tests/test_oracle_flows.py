@@ -240,3 +240,56 @@ def test_em_step_size_and_pseudocount():
     assert np.allclose(uni[1:-2], 1.0 / 4, rtol=1e-5)
     assert np.allclose(tab, 1.0 / 4, rtol=1e-5)
     assert np.all(uni[-2:, 1:, :] == 0.0) and np.all(uni[0] == 0.0)
+
+
+def two_component_mixture():
+    """One sum node over two input nodes on the same variable (K = 1): p(x) = 0.25 f_0(x) + 0.75 f_1(x)."""
+    i32 = lambda a: np.asarray(a, dtype=np.int32)
+    theta = np.zeros((3, 1, 1), dtype=np.float32); theta[1] = 0.25; theta[2] = 0.75
+    tables = np.array([[[0.5], [0.25], [0.25]], [[0.125], [0.125], [0.75]]], dtype=np.float32)
+    return W.Workload(name="mixture2", K=1, n_blocks=3, root_block=2, type=np.asarray([W.INPUT, W.INPUT, W.SUM], dtype=np.uint8),
+                      n_real=i32([1, 1, 1]), child_ptr=np.asarray([0, 0, 0, 2], dtype=np.int64), child=i32([0, 1]),
+                      param_blk=i32([0, 1]), n_param_blocks=2, in_var=i32([0, 0, -1]), in_table=i32([0, 1, -1]),
+                      n_vars=1, n_cats=3, n_tables=2, theta=theta, tables=tables, x=i32([[0], [2], [2], [1]]))
+
+
+def test_em_pseudocount_is_one_total_mass_split_evenly_hand_computed():
+    """The paper prints no formula for the smoothed update ("parity unpinned" by the paper); the reading pinned here is
+    Laplace smoothing with a total mass `pseudocount` per sum node / table column, split evenly over the node's edges:
+    theta_new = (flow + pc / n_edges) / (sum of flows + pc).  Values below are worked by hand; adding `pc` to every
+    edge instead would give (5/8, 3/8) and (4/17, 5/17, 8/17)."""
+    w = two_component_mixture()
+    tf = np.zeros((3, 1, 1)); tf[1] = 3.0; tf[2] = 1.0
+    gf = np.zeros((2, 3, 1)); gf[0, :, 0] = (1.0, 2.0, 5.0); gf[1, :, 0] = (0.0, 0.0, 4.0)
+    th, tb = orc.em_step(w, w.theta, w.tables, tf, gf, step=1.0, pseudocount=2.0)
+    assert np.allclose(th[1:, 0, 0], [(3 + 1) / 6, (1 + 1) / 6], rtol=1e-6)
+    assert np.allclose(tb[0, :, 0], [(1 + 2 / 3) / 10, (2 + 2 / 3) / 10, (5 + 2 / 3) / 10], rtol=1e-6)
+    assert np.allclose(tb[1, :, 0], [(2 / 3) / 6, (2 / 3) / 6, (4 + 2 / 3) / 6], rtol=1e-6)
+    # the full loop on the same circuit: posterior responsibilities by hand (Def. 2 on a two-component mixture)
+    _, _, _, tf, gf = orc.backward(w, w.theta, w.tables, w.x)
+    f = w.tables.astype(np.float64)[:, w.x[:, 0], 0]                     # [component, sample]
+    post = np.array([[0.25], [0.75]]) * f
+    post /= post.sum(axis=0, keepdims=True)
+    assert np.allclose(tf[1:, 0, 0], post.sum(axis=1), rtol=1e-12)
+    th, _ = orc.em_step(w, w.theta, w.tables, tf, gf, step=0.5, pseudocount=1.0)
+    want = 0.5 * np.array([0.25, 0.75]) + 0.5 * (post.sum(axis=1) + 0.5) / (4 + 1.0)
+    assert np.allclose(th[1:, 0, 0], want, rtol=1e-6)
+
+
+def test_category_outside_the_table_is_outside_the_support():
+    """A value outside 0..n_cats-1 has probability 0 under a categorical distribution.  Pinned two ways: against the
+    same circuit with its tables widened by zero-probability categories (where the value is in range), and against
+    the batch without the offending samples (a sample of probability 0 adds no flow)."""
+    w = W.hclt(6, 4, 2, 9, 171, n_cats=4)
+    x = w.x.copy(); x[2, 1] = w.n_cats + 2; x[5, 0] = -3
+    ll, lp, flow, tf, gf = orc.backward(w, w.theta, w.tables, x)
+    assert ll[2] == -np.inf and ll[5] == -np.inf and np.all(flow[2, :] == 0.0) and np.all(flow[5, :] == 0.0)
+    wide = w.with_batch(np.where(x < 0, w.n_cats + 3, x))                # the negative value becomes another zero category
+    wide.n_cats = w.n_cats + 4
+    wide.tables = np.concatenate([w.tables, np.zeros((w.n_tables, 4, w.K), dtype=np.float32)], axis=1)
+    ll2, lp2, flow2, tf2, gf2 = orc.backward(wide, wide.theta, wide.tables, wide.x)
+    assert np.array_equal(ll, ll2) and np.array_equal(lp, lp2) and np.array_equal(flow, flow2) and np.array_equal(tf, tf2)
+    assert np.array_equal(gf, gf2[:, :w.n_cats]) and np.all(gf2[:, w.n_cats:] == 0.0)
+    keep = np.array([b for b in range(w.B) if b not in (2, 5)])
+    ll3, _, _, tf3, gf3 = orc.backward(w, w.theta, w.tables, x[keep])
+    assert np.array_equal(ll[keep], ll3) and np.allclose(tf, tf3, rtol=1e-13) and np.allclose(gf, gf3, rtol=1e-13)
