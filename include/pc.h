@@ -54,11 +54,16 @@ typedef enum {
  * sum blocks are fully connected to each of their child blocks through one K x K parameter block
  * (Sec. 4.2: every block pair is fully connected or unconnected). */
 typedef struct {
-    int32_t K;                 /* node block size K_M = K_N (Sec. 4.1); any K >= 1, MFMA kernels need K % 32 == 0 */
+    int32_t K;                 /* node block size K_M = K_N (Sec. 4.1), 1 <= K <= 128 (larger: PC_ERR_ARG); the matrix-core
+                                  kernels serve K % 32 == 0, vector kernels every other K */
     int32_t n_blocks;
     int32_t root_block;        /* a sum block; its node 0 is the root n_r                        */
     const uint8_t *type;       /* [n_blocks] 0 input, 1 product, 2 sum                           */
-    const int32_t *n_real;     /* [n_blocks] real nodes in the block (placeholders after, Sec. 4.1 footnote) */
+    const int32_t *n_real;     /* [n_blocks] real nodes in the block, 1..K; slots n_real..K-1 are placeholders (Sec. 4.1
+                                  footnote) of probability 0: the caller keeps their theta rows and table columns at 0.  A
+                                  product node over a placeholder slot of any child has probability 0 as well, so a
+                                  product block has no more useful nodes than its smallest child; equality of the
+                                  counts is not required */
     const int64_t *child_ptr;  /* [n_blocks+1] CSR offsets into child / param_blk                */
     const int32_t *child;      /* [n_edges] child block ids                                      */
     const int32_t *param_blk;  /* [n_edges] parameter block id of a sum edge (equal ids = tied parameters,

@@ -75,25 +75,65 @@ __global__ void k_scatter_parents(const int32_t *__restrict__ child, int32_t n_e
     tp[pptr[c] + atomicAdd(cursor + c, 1)] = e;
 }
 
-// per block: sort its incoming edges by (layer of the source, source id); count the runs of equal layer
+// per block: sort its incoming edges by (layer of the source, source id); count the runs of equal layer.
+// Keys are distinct (a block pair has one edge), so the result does not depend on the order the scatter left.
+// Short lists: insertion sort; long ones (a child block of a wide small-K layer has some thousand parents): an
+// in-place heap sort, n log n key look-ups instead of n^2 / 4.
+__device__ __forceinline__ int64_t parent_key(const int32_t *__restrict__ src, const int32_t *__restrict__ layer_of, int32_t e)
+{
+    const int32_t s = src[e];
+    return ((int64_t)layer_of[s] << 32) | (uint32_t)s;
+}
+
+__device__ void sift_down(int32_t *__restrict__ a, int32_t root, int32_t end, const int32_t *__restrict__ src,
+                          const int32_t *__restrict__ layer_of)
+{
+    const int32_t moving = a[root];
+    const int64_t key = parent_key(src, layer_of, moving);
+    for (;;) {
+        int32_t kid = 2 * root + 1;
+        if (kid >= end) break;
+        int64_t kk = parent_key(src, layer_of, a[kid]);
+        if (kid + 1 < end) {
+            const int64_t k2 = parent_key(src, layer_of, a[kid + 1]);
+            if (k2 > kk) { kk = k2; ++kid; }
+        }
+        if (kk <= key) break;
+        a[root] = a[kid];
+        root = kid;
+    }
+    a[root] = moving;
+}
+
 __global__ void k_sort_parent_lists(const int32_t *__restrict__ pptr, int32_t n, const int32_t *__restrict__ src,
                                     const int32_t *__restrict__ layer_of, int32_t *__restrict__ tp,
                                     int32_t *__restrict__ n_runs)
 {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= n) return;
-    const int32_t lo = pptr[c], hi = pptr[c + 1];
-    for (int32_t i = lo + 1; i < hi; ++i) {                          // insertion sort, lists are short
-        const int32_t e = tp[i];
-        const int64_t key = ((int64_t)layer_of[src[e]] << 32) | (uint32_t)src[e];
-        int32_t j = i - 1;
-        while (j >= lo) {
-            const int32_t f = tp[j];
-            if ((((int64_t)layer_of[src[f]] << 32) | (uint32_t)src[f]) <= key) break;
-            tp[j + 1] = f;
-            --j;
+    const int32_t lo = pptr[c], hi = pptr[c + 1], len = hi - lo;
+    if (len <= 24) {
+        for (int32_t i = lo + 1; i < hi; ++i) {
+            const int32_t e = tp[i];
+            const int64_t key = parent_key(src, layer_of, e);
+            int32_t j = i - 1;
+            while (j >= lo) {
+                const int32_t f = tp[j];
+                if (parent_key(src, layer_of, f) <= key) break;
+                tp[j + 1] = f;
+                --j;
+            }
+            tp[j + 1] = e;
         }
-        tp[j + 1] = e;
+    } else {
+        int32_t *a = tp + lo;
+        for (int32_t r = len / 2 - 1; r >= 0; --r) sift_down(a, r, len, src, layer_of);
+        for (int32_t end = len - 1; end > 0; --end) {
+            const int32_t top = a[0];
+            a[0] = a[end];
+            a[end] = top;
+            sift_down(a, 0, end, src, layer_of);
+        }
     }
     int32_t runs = 0;
     for (int32_t i = lo; i < hi; ++i)

@@ -561,9 +561,27 @@ def test_sum_block_without_parents_gets_zero_flow():
 
 
 def test_out_of_range_category_has_probability_zero():
-    w = W.reduced(1, B=8)
-    x = w.x.copy(); x[2, 1] = w.n_cats + 5; x[5, 0] = -3
-    c = pcb.Circuit(w)
-    c.set_batch(x)
-    ll = c.forward().cpu().numpy()
-    assert np.isneginf(ll[2]) and np.isneginf(ll[5]) and np.isfinite(ll[0])
+    for w in (W.reduced(1, B=8), W.reduced(4, B=40), W.reduced(5, B=33)):       # direct, sorted and histogram table flows
+        x = w.x.copy(); x[2, 1] = w.n_cats + 5; x[5, 0] = -3
+        print(f"case out-of-range {w.name}", flush=True)
+        got, ref = check_all(w.with_batch(x))
+        ll = got["ll"]
+        assert np.isneginf(ll[2]) and np.isneginf(ll[5]) and np.isfinite(ll[0])
+        assert np.all(got["flow"][2] == 0.0) and np.all(got["flow"][5] == 0.0)
+
+
+def test_parameter_flows_repeat_bit_for_bit_where_no_pairs_are_split():
+    """Parameter flows are written by exactly one workgroup per parameter block, in a fixed order, unless the launcher
+    deals the tied pairs of a block over several waves or workgroups (fewer than 128 parameter blocks with at least two
+    tied pairs each: small tied models).  Untied circuits and large tied models are therefore reproducible to the bit;
+    so are log-probabilities and node flows everywhere."""
+    cases = [W.reduced(2, B=100),                                        # untied, K = 32
+             W.reduced(5, B=64),                                         # untied, block-sparse, K = 32
+             W.hmm(4, 1024, 50, 64, 64, 57, tokens="zipf"),               # tied, 257 parameter blocks of 64 x 64
+             W.hmm(3, 2048, 50, 128, 256, 58, tokens="zipf")]             # tied, 257 parameter blocks of 128 x 128
+    for w in cases:
+        print(f"case bit-repeat {w.name}", flush=True)
+        a, b = gpu_run(w), gpu_run(w)
+        for key in ("ll", "lp", "flow", "theta_flow"):
+            assert np.array_equal(a[key], b[key], equal_nan=True), f"{w.name}: {key} differs between two runs"
+        a["circuit"].close(); b["circuit"].close()
