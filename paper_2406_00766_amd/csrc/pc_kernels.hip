@@ -1409,15 +1409,15 @@ __global__ __launch_bounds__(256) void k_split_p(const float *__restrict__ X, co
 // itself is 10 us, the kernel is bound by the 64 bytes per clock at which a CU's L1 feeds the four SIMDs (a 64 x 32
 // tile needs 1 KiB of operands per MFMA), which only larger register tiles or operand sharing through LDS would lift --
 // at this batch size both leave too few tiles to fill the chip.
-template <int K, int D, bool BWD>
-__global__ __launch_bounds__(256, 2) void k_sum_bf16(const uint4 *__restrict__ Th, const uint4 *__restrict__ Tl,
-                                                     const uint4 *__restrict__ Ph, const uint4 *__restrict__ Pl,
-                                                     float *__restrict__ l, float *__restrict__ R,
-                                                     const float *__restrict__ nfmax, float *__restrict__ F, const GroupSet gs,
-                                                     int64_t Bs)
+template <int K, int D, bool BWD, int CT>
+__global__ __launch_bounds__(256, CT == 1 ? 2 : 1) void k_sum_bf16(const uint4 *__restrict__ Th, const uint4 *__restrict__ Tl,
+                                                                   const uint4 *__restrict__ Ph, const uint4 *__restrict__ Pl,
+                                                                   float *__restrict__ l, float *__restrict__ R,
+                                                                   const float *__restrict__ nfmax, float *__restrict__ F,
+                                                                   const GroupSet gs, int64_t Bs)
 {
     constexpr int NKS = K / 16, NRT = K / 32, SUB = K / 64;
-    constexpr int XCH = 2 * 16 * 64 + 64;                               // one partial accumulator tile and its reference
+    constexpr int XCH = (2 * 16 * 64 + 64) * CT;                        // one partial accumulator tile and its references
     static_assert(NKS % D == 0, "the ring must divide a block's slices");
     __shared__ float lds[3 * XCH];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1425,30 +1425,37 @@ __global__ __launch_bounds__(256, 2) void k_sum_bf16(const uint4 *__restrict__ T
     const GroupRow gr = locate_row<false>(gs, blockIdx.x / SUB);
     const int r = gr.r, sub = blockIdx.x % SUB;
     const int n_ct = (int)(Bs / 32);
-    const int ct = blockIdx.y;
-    const int64_t col = (int64_t)ct * 32 + l32;
+    const int ct0 = blockIdx.y * CT;
+    const int64_t col0 = (int64_t)ct0 * 32 + l32;                       // column of tile c: col0 + 32 c
     const int32_t *row_nbr = gr.nbr + (int64_t)r * gr.width, *row_par = gr.par + (int64_t)r * gr.width;
     const int32_t id = gr.ids[r];
     const int32_t fl = gr.aux[r];
     const int cnt = fl >> 8;
-    const float Rown = BWD ? R[(int64_t)(id / K) * Bs + col] : 0.0f;
-
-    floatx16 acc[2], blk[2];
+    float Rown[CT];
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[rt][e] = 0.0f;
-    float m = PC_NEG_INF, cm = PC_NEG_INF;                              // reference of the accumulator, of the current block
+    for (int c = 0; c < CT; ++c) Rown[c] = BWD ? R[(int64_t)(id / K) * Bs + col0 + 32 * c] : 0.0f;
 
-    struct Ops { uint4 ah[2], al[2], bh, bl; };
+    floatx16 acc[2][CT], blk[2][CT];
+    float m[CT], cm[CT];                                                // reference of the accumulator, of the current block
+#pragma unroll
+    for (int c = 0; c < CT; ++c) {
+        m[c] = PC_NEG_INF;
+        cm[c] = PC_NEG_INF;
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[rt][c][e] = 0.0f;
+    }
+
+    struct Ops { uint4 ah[2], al[2], bh[CT], bl[CT]; };
     const int n_my = cnt > wave ? (cnt - wave + 3) / 4 : 0;             // neighbour blocks wave, wave + 4, ...
     auto load_slice = [&](int32_t ns, int32_t ps, int ks, Ops &o) {
         const int64_t ta = (((int64_t)(ps / (K * K)) * NRT + 2 * sub) * NKS + ks) * 64 + lane;   // rt advances by NKS tiles
-        const int64_t tb = ((int64_t)(ns / 16 + ks) * n_ct + ct) * 64 + lane;
+        const int64_t tb = ((int64_t)(ns / 16 + ks) * n_ct + ct0) * 64 + lane;
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt) { o.ah[rt] = Th[ta + (int64_t)rt * NKS * 64]; o.al[rt] = Tl[ta + (int64_t)rt * NKS * 64]; }
-        o.bh = Ph[tb];
-        o.bl = Pl[tb];
+#pragma unroll
+        for (int c = 0; c < CT; ++c) { o.bh[c] = Ph[tb + 64 * c]; o.bl[c] = Pl[tb + 64 * c]; }
     };
     // The loop over the wave's neighbour blocks is straight-line inside (every slot of the ring is refilled
     // unconditionally: past the last block the refill repeats that block and is never used), so that the compiler can
@@ -1464,40 +1471,47 @@ __global__ __launch_bounds__(256, 2) void k_sum_bf16(const uint4 *__restrict__ T
     for (int bi = 0; bi < n_my; ++bi) {
         const int jn = wave + 4 * (bi + 1 < n_my ? bi + 1 : bi);
         const int32_t ns_nxt = row_nbr[jn], ps_nxt = row_par[jn];
-        {
-            const float Rn = R[(int64_t)(ns_cur / K) * Bs + col];       // finite
-            cm = BWD ? nfmax[(int64_t)(ns_cur / K) * Bs + col] + (Rown - Rn) : Rn;
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            const float Rn = R[(int64_t)(ns_cur / K) * Bs + col0 + 32 * c];   // finite
+            cm[c] = BWD ? nfmax[(int64_t)(ns_cur / K) * Bs + col0 + 32 * c] + (Rown[c] - Rn) : Rn;
         }
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            Ops &c = o[ks % D];
-            const bf16x8 bh = __builtin_bit_cast(bf16x8, c.bh), bl = __builtin_bit_cast(bf16x8, c.bl);
+            Ops &cur = o[ks % D];
+            if (ks == 0) {
 #pragma unroll
-            for (int rt = 0; rt < 2; ++rt) {
-                const bf16x8 ah = __builtin_bit_cast(bf16x8, c.ah[rt]), al = __builtin_bit_cast(bf16x8, c.al[rt]);
-                floatx16 t = blk[rt];
-                if (ks == 0) {
+                for (int c = 0; c < CT; ++c)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) t[e] = 0.0f;
-                }
-                t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, t, 0, 0, 0);          // small products first
-                t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, t, 0, 0, 0);
-                t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, t, 0, 0, 0);
-                blk[rt] = t;
+                    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) blk[rt][c][e] = 0.0f;
             }
-            if (ks + D < NKS) load_slice(ns_cur, ps_cur, ks + D, c);
-            else load_slice(ns_nxt, ps_nxt, ks + D - NKS, c);
+            // three products per tile, small ones first; the tiles take turns so that no MFMA waits for the one before
+#pragma unroll
+            for (int step = 0; step < 3; ++step)
+#pragma unroll
+                for (int c = 0; c < CT; ++c)
+#pragma unroll
+                    for (int rt = 0; rt < 2; ++rt) {
+                        const bf16x8 a = __builtin_bit_cast(bf16x8, step == 0 ? cur.al[rt] : cur.ah[rt]);
+                        const bf16x8 b = __builtin_bit_cast(bf16x8, step == 1 ? cur.bl[c] : cur.bh[c]);
+                        blk[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, blk[rt][c], 0, 0, 0);
+                    }
+            if (ks + D < NKS) load_slice(ns_cur, ps_cur, ks + D, cur);
+            else load_slice(ns_nxt, ps_nxt, ks + D - NKS, cur);
             __builtin_amdgcn_sched_barrier(0);                          // keeps the refill here, D - 1 slices ahead of its use
         }
         // the block's partial sums join the row's accumulator, both brought to the larger reference
-        {
-            const float mn = fmaxf(m, cm);
-            const float sa = m > PC_NEG_INF ? __expf(m - mn) : 0.0f, sb = cm > PC_NEG_INF ? __expf(cm - mn) : 0.0f;
-            m = mn;
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            const float mn = fmaxf(m[c], cm[c]);
+            const float sa = m[c] > PC_NEG_INF ? __expf(m[c] - mn) : 0.0f, sb = cm[c] > PC_NEG_INF ? __expf(cm[c] - mn) : 0.0f;
+            m[c] = mn;
 #pragma unroll
             for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[rt][e] = acc[rt][e] * sa + blk[rt][e] * sb;
+                for (int e = 0; e < 16; ++e) acc[rt][c][e] = acc[rt][c][e] * sa + blk[rt][c][e] * sb;
         }
         ns_cur = ns_nxt;
         ps_cur = ps_nxt;
@@ -1507,56 +1521,67 @@ __global__ __launch_bounds__(256, 2) void k_sum_bf16(const uint4 *__restrict__ T
     float *buf = lds + (wave - 1) * XCH;
     if (wave != 0) {
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
+        for (int c = 0; c < CT; ++c) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) buf[(rt * 16 + e) * 64 + lane] = acc[rt][e];
-        buf[2 * 16 * 64 + lane] = m;
+            for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) buf[((c * 2 + rt) * 16 + e) * 64 + lane] = acc[rt][c][e];
+            buf[2 * CT * 16 * 64 + c * 64 + lane] = m[c];
+        }
     }
     __syncthreads();
     if (wave != 0) return;
 #pragma unroll 1
     for (int w = 0; w < 3; ++w) {
         const float *ob = lds + w * XCH;
-        const float mo = ob[2 * 16 * 64 + lane];                        // -inf: that wave had no block (its sums are 0)
-        const float mn = fmaxf(m, mo);
-        const float sa = m > PC_NEG_INF ? __expf(m - mn) : 0.0f, sb = mo > PC_NEG_INF ? __expf(mo - mn) : 0.0f;
-        m = mn;
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
+        for (int c = 0; c < CT; ++c) {
+            const float mo = ob[2 * CT * 16 * 64 + c * 64 + lane];      // -inf: that wave had no block (its sums are 0)
+            const float mn = fmaxf(m[c], mo);
+            const float sa = m[c] > PC_NEG_INF ? __expf(m[c] - mn) : 0.0f, sb = mo > PC_NEG_INF ? __expf(mo - mn) : 0.0f;
+            m[c] = mn;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[rt][e] = acc[rt][e] * sa + ob[(rt * 16 + e) * 64 + lane] * sb;
+            for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[rt][c][e] = acc[rt][c][e] * sa + ob[((c * 2 + rt) * 16 + e) * 64 + lane] * sb;
+        }
     }
-    if (!BWD && sub == 0 && half == 0) R[(int64_t)(id / K) * Bs + col] = m;
     const bool first = (fl & 2) != 0;                                   // backward: the first layer that feeds the block stores
-    // backward: the rows' own log-probabilities (and, where this layer accumulates, the flows so far) are all requested
-    // before the first of them is used -- a load inside the per-element branch would be waited for on its own, 32 times
-    floatx16 lown[2], fold[2];
-    if (BWD) {
+#pragma unroll
+    for (int c = 0; c < CT; ++c) {
+        const int64_t col = col0 + 32 * c;
+        if (!BWD && sub == 0 && half == 0) R[(int64_t)(id / K) * Bs + col] = m[c];
+        // backward: the rows' own log-probabilities (and, where this layer accumulates, the flows so far) are all
+        // requested before the first of them is used -- a load inside the per-element branch would be waited for on its
+        // own, 32 times
+        floatx16 lown[2], fold[2];
+        if (BWD) {
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int64_t at = (int64_t)(id + sub * 64 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4)) * Bs + col;
+                    lown[rt][e] = l[at];
+                    fold[rt][e] = first ? 0.0f : F[at];
+                }
+        }
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int64_t at = (int64_t)(id + sub * 64 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4)) * Bs + col;
-                lown[rt][e] = l[at];
-                fold[rt][e] = first ? 0.0f : F[at];
+                const int row = sub * 64 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                const int64_t at = (int64_t)(id + row) * Bs + col;
+                if (!BWD) {
+                    // ln(sum) - PC_UP, the logarithm taken of sum / 2^24 (see the fp32 kernel)
+                    l[at] = fmaf(__builtin_amdgcn_logf(acc[rt][c][e] * 0x1p-24f), 0.6931471805599453f, 16.635532333f - PC_UP);
+                } else {
+                    // exp(ln(sum) + (m - PC_UP) + l_row); sum = 0 or l_row = -inf gives exp2(-inf) = 0
+                    const float lg = __builtin_amdgcn_logf(acc[rt][c][e]);
+                    const float add = __builtin_amdgcn_exp2f(lg + (lown[rt][e] + (m[c] - PC_UP)) * PC_LOG2E);
+                    F[at] = fold[rt][e] + (m[c] > PC_NEG_INF ? add : 0.0f);
+                }
             }
     }
-#pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int row = sub * 64 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
-            const int64_t at = (int64_t)(id + row) * Bs + col;
-            if (!BWD) {
-                // ln(sum) - PC_UP, the logarithm taken of sum / 2^24 (see the fp32 kernel)
-                l[at] = fmaf(__builtin_amdgcn_logf(acc[rt][e] * 0x1p-24f), 0.6931471805599453f, 16.635532333f - PC_UP);
-            } else {
-                // exp(ln(sum) + (m - PC_UP) + l_row); sum = 0 or l_row = -inf gives exp2(-inf) = 0
-                const float lg = __builtin_amdgcn_logf(acc[rt][e]);
-                const float add = __builtin_amdgcn_exp2f(lg + (lown[rt][e] + (m - PC_UP)) * PC_LOG2E);
-                F[at] = fold[rt][e] + (m > PC_NEG_INF ? add : 0.0f);
-            }
-        }
 }
 
 // Backward to the parameters (role of Alg. 3), organised by PARAMETER BLOCK instead of by layer: one launch
@@ -2586,10 +2611,21 @@ void launch_sum_bf16(const void *Th, const void *Tl, const void *Ph, const void 
 {
     Timed timed(bwd ? KC_SUM_BWD_CHILD : KC_SUM_FWD, s);
     if (g_prof) g_prof->bf16_launches[bwd ? KC_SUM_BWD_CHILD : KC_SUM_FWD] += 1;
-    const dim3 grid((unsigned)(set_rows(gs) * (K / 64)), (unsigned)(Bs / 32));
+    // 64 x 64 tiles per wave (two thirds of the operand bytes per MFMA) where they still give every CU a workgroup
+    static const int ring = getenv("PC_BF16_D") ? atoi(getenv("PC_BF16_D")) : 2;
+    static const int force_ct = getenv("PC_BF16_CT") ? atoi(getenv("PC_BF16_CT")) : 0;
+    const int64_t tiles64 = (int64_t)set_rows(gs) * (K / 64) * (Bs / 64);
+    const bool wide = force_ct ? force_ct == 2 && Bs % 64 == 0 : Bs % 64 == 0 && tiles64 >= 200;
+    const dim3 grid((unsigned)(set_rows(gs) * (K / 64)), (unsigned)(Bs / (wide ? 64 : 32)));
 #define PC_BF16_SUM(KK, BB)                                                                                            \
-    hipLaunchKernelGGL((k_sum_bf16<KK, 2, BB>), grid, dim3(256), 0, s, (const uint4 *)Th, (const uint4 *)Tl, (const uint4 *)Ph, \
-                       (const uint4 *)Pl, l, R, nfmax, F, gs, Bs)
+    do {                                                                                                               \
+        if (wide && ring == 4) hipLaunchKernelGGL((k_sum_bf16<KK, 4, BB, 2>), grid, dim3(256), 0, s, (const uint4 *)Th, (const uint4 *)Tl, \
+                                     (const uint4 *)Ph, (const uint4 *)Pl, l, R, nfmax, F, gs, Bs);                     \
+        else if (wide) hipLaunchKernelGGL((k_sum_bf16<KK, 2, BB, 2>), grid, dim3(256), 0, s, (const uint4 *)Th, (const uint4 *)Tl, \
+                                     (const uint4 *)Ph, (const uint4 *)Pl, l, R, nfmax, F, gs, Bs);                     \
+        else hipLaunchKernelGGL((k_sum_bf16<KK, 2, BB, 1>), grid, dim3(256), 0, s, (const uint4 *)Th, (const uint4 *)Tl, \
+                                (const uint4 *)Ph, (const uint4 *)Pl, l, R, nfmax, F, gs, Bs);                          \
+    } while (0)
     if (K == 64) { if (bwd) PC_BF16_SUM(64, true); else PC_BF16_SUM(64, false); }
     else { if (bwd) PC_BF16_SUM(128, true); else PC_BF16_SUM(128, false); }
 #undef PC_BF16_SUM
