@@ -481,14 +481,17 @@ __global__ __launch_bounds__(256) void k_prod_fwd(const float *__restrict__ l, f
                 tr[u] = (on && rg == 0) ? *reinterpret_cast<const float4 *>(R + (int64_t)(ch[u] / K) * Bs + b)
                                         : make_float4(0.f, 0.f, 0.f, 0.f);
             }
+            // the U values of a round are added in fp32, the rounds in ACC (double for rows of many children: a running
+            // fp32 sum of a hundred residuals loses more than the flows' tolerance allows, a sum of U does not)
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
+            for (int i = 0; i < RPT; ++i) {
+                float4 part = t[0][i];
 #pragma unroll
-                for (int i = 0; i < RPT; ++i) {
-                    s[i].x += (ACC)t[u][i].x; s[i].y += (ACC)t[u][i].y; s[i].z += (ACC)t[u][i].z; s[i].w += (ACC)t[u][i].w;
-                }
-                rsum.x += tr[u].x; rsum.y += tr[u].y; rsum.z += tr[u].z; rsum.w += tr[u].w;
+                for (int u = 1; u < U; ++u) { part.x += t[u][i].x; part.y += t[u][i].y; part.z += t[u][i].z; part.w += t[u][i].w; }
+                s[i].x += (ACC)part.x; s[i].y += (ACC)part.y; s[i].z += (ACC)part.z; s[i].w += (ACC)part.w;
             }
+#pragma unroll
+            for (int u = 0; u < U; ++u) { rsum.x += tr[u].x; rsum.y += tr[u].y; rsum.z += tr[u].z; rsum.w += tr[u].w; }
         }
 #pragma unroll
         for (int i = 0; i < RPT; ++i)
