@@ -1400,18 +1400,19 @@ __global__ __launch_bounds__(256) void k_split_p(const float *__restrict__ X, co
 
 // Sum layer on the planes, forward (rows = sum blocks, neighbours = their product children) and backward to the
 // children (rows = product blocks, neighbours = their sum parents, theta planes transposed).  Workgroup = 4 waves that
-// share one output tile of 64 rows x 32 columns and take the row's neighbour blocks in turn (a split of the reduction;
-// merged through LDS at the end).  Per 16-node slice a wave fetches 2 + 2 theta tiles and 1 + 1 value tiles (hi and lo
-// planes, 16 bytes per lane each, 1 KiB per wave load) and issues 6 MFMAs; the operands of D slices are in flight at
-// any time (a ring of D register sets that runs across the neighbour blocks).
+// share one output tile of 64 rows x 32 CT columns and take the row's neighbour blocks in turn (a split of the
+// reduction; merged through LDS at the end).  Per 16-node slice a wave fetches 2 + 2 theta tiles and CT + CT value tiles
+// (hi and lo planes, 16 bytes per lane each, 1 KiB per wave load) and issues 6 CT MFMAs; the operands of D slices are
+// in flight at any time (a ring of D register sets that runs across the neighbour blocks).
 //   forward : block scale = R_c (integer reference of the child block); result l = ln(sum) - PC_UP relative to the
 //             largest reference, which becomes the row's own
 //   backward: block scale = nfmax_s + (R_row - R_s) (column maximum of the parent's log_nf, brought to the row's
 //             reference); result F += exp(ln(sum) + scale - PC_UP + l_row)
-// Measured on 4096 x 4096 layers at B = 256: 41 us per layer against 80 us on the fp32 matrix cores; the matrix work
-// itself is 10 us, the kernel is bound by the 64 bytes per clock at which a CU's L1 feeds the four SIMDs (a 64 x 32
-// tile needs 1 KiB of operands per MFMA), which only larger register tiles or operand sharing through LDS would lift --
-// at this batch size both leave too few tiles to fill the chip.
+// Measured on 4096 x 4096 layers at B = 256: 40 us per layer with CT = 1 and 32-34 us with CT = 2 (one workgroup per
+// CU, one wave per SIMD) against 80 us on the fp32 matrix cores; the matrix work itself is 10 us.  The rest is the
+// rate at which a CU's vector memory pipeline delivers the 1 KiB operand loads (a 128-byte line per 4.8 cycles,
+// whatever the ring depth; CT = 2 needs two thirds of the bytes per MFMA) on top of some 20 us that do not depend on
+// the traffic (launch, row headers, the per-block folds, the merge, the epilogue).
 template <int K, int D, bool BWD, int CT>
 __global__ __launch_bounds__(256, CT == 1 ? 2 : 1) void k_sum_bf16(const uint4 *__restrict__ Th, const uint4 *__restrict__ Tl,
                                                                    const uint4 *__restrict__ Ph, const uint4 *__restrict__ Pl,
@@ -2614,17 +2615,15 @@ void launch_sum_bf16(const void *Th, const void *Tl, const void *Ph, const void 
 {
     Timed timed(bwd ? KC_SUM_BWD_CHILD : KC_SUM_FWD, s);
     if (g_prof) g_prof->bf16_launches[bwd ? KC_SUM_BWD_CHILD : KC_SUM_FWD] += 1;
-    // 64 x 64 tiles per wave (two thirds of the operand bytes per MFMA) where they still give every CU a workgroup
-    static const int ring = getenv("PC_BF16_D") ? atoi(getenv("PC_BF16_D")) : 2;
+    // 64 x 64 tiles per wave (two thirds of the operand bytes per MFMA) where they still give every CU a workgroup;
+    // PC_BF16_CT=1 / 2 forces one form (measurements)
     static const int force_ct = getenv("PC_BF16_CT") ? atoi(getenv("PC_BF16_CT")) : 0;
     const int64_t tiles64 = (int64_t)set_rows(gs) * (K / 64) * (Bs / 64);
-    const bool wide = force_ct ? force_ct == 2 && Bs % 64 == 0 : Bs % 64 == 0 && tiles64 >= 200;
+    const bool wide = Bs % 64 == 0 && (force_ct ? force_ct == 2 : tiles64 >= 200);
     const dim3 grid((unsigned)(set_rows(gs) * (K / 64)), (unsigned)(Bs / (wide ? 64 : 32)));
 #define PC_BF16_SUM(KK, BB)                                                                                            \
     do {                                                                                                               \
-        if (wide && ring == 4) hipLaunchKernelGGL((k_sum_bf16<KK, 4, BB, 2>), grid, dim3(256), 0, s, (const uint4 *)Th, (const uint4 *)Tl, \
-                                     (const uint4 *)Ph, (const uint4 *)Pl, l, R, nfmax, F, gs, Bs);                     \
-        else if (wide) hipLaunchKernelGGL((k_sum_bf16<KK, 2, BB, 2>), grid, dim3(256), 0, s, (const uint4 *)Th, (const uint4 *)Tl, \
+        if (wide) hipLaunchKernelGGL((k_sum_bf16<KK, 2, BB, 2>), grid, dim3(256), 0, s, (const uint4 *)Th, (const uint4 *)Tl, \
                                      (const uint4 *)Ph, (const uint4 *)Pl, l, R, nfmax, F, gs, Bs);                     \
         else hipLaunchKernelGGL((k_sum_bf16<KK, 2, BB, 1>), grid, dim3(256), 0, s, (const uint4 *)Th, (const uint4 *)Tl, \
                                 (const uint4 *)Ph, (const uint4 *)Pl, l, R, nfmax, F, gs, Bs);                          \

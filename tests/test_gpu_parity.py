@@ -166,8 +166,7 @@ def test_block_sparse_sum_layer(n_sets, M, K, keep, B):
     lambda: W.hmm(3, 2048, 40, 128, 40, 46),
     # more than 1024 categories: per-sample atomics
     lambda: W.hmm(5, 64, 1500, 32, 130, 44, tokens="zipf"),
-    # rows of 2048 children and at least 64 output tiles: the bf16-split kernels (K = 128 with a ragged third column
-    # tile, K = 64), Dirichlet(0.1) rows as in the large HMM configuration
+    # K = 128 / 64 layers just under the size from which the bf16-split kernels take over (ragged third column tile)
     lambda: W.hmm(3, 2048, 40, 128, 90, 52, alpha_trans=0.1, alpha_emis=0.1),
     lambda: W.hmm(3, 2048, 40, 64, 70, 53, alpha_trans=0.1, alpha_emis=0.1),
 ])
@@ -177,6 +176,40 @@ def test_kernel_variants_selected_by_shape(make):
     rng = np.random.default_rng(5)
     mask = (rng.random(w.x.shape) < 0.15).astype(np.uint8)
     check_all(w, mask)
+
+
+def bf16_sum_launches(w):
+    """(forward, backward) sum-layer launches of one pass that ran as bf16-split products."""
+    c = pcb.Circuit(w)
+    c.set_batch(w.x)
+    pcb.pc_profile_enable(c.handle, True)
+    c.forward(); c.backward()
+    torch.cuda.synchronize()
+    prof = pcb.pc_profile_read(c.handle, with_bf16=True)
+    pcb.pc_profile_enable(c.handle, False)
+    c.close()
+    return prof["sum_fwd"][2], prof["sum_bwd_child"][2]
+
+
+@pytest.mark.parametrize("make,reps,tiles", [
+    # rows of 2048 children (Dirichlet(0.1) rows as in the large HMM configuration) in the three shapes of the bf16-split
+    # sum kernels: 64 x 32 tiles per wave (K = 128; K = 64 with a ragged third 32-column tile) and 64 x 64 tiles (from
+    # 200 such tiles on)
+    (lambda: W.hmm(3, 2048, 40, 128, 64, 52, alpha_trans=0.1, alpha_emis=0.1), 4, "64x32"),
+    (lambda: W.hmm(3, 4096, 40, 64, 45, 56, alpha_trans=0.1, alpha_emis=0.1), 2, "64x32"),
+    (lambda: W.hmm(3, 2048, 40, 64, 64, 53, alpha_trans=0.1, alpha_emis=0.1), 7, "64x64"),
+    (lambda: W.hmm(3, 2048, 40, 128, 64, 59, alpha_trans=0.1, alpha_emis=0.1), 7, "64x64"),
+])
+def test_bf16_split_sum_kernels(make, reps, tiles):
+    w = make()
+    print(f"case bf16 {w.name} x {reps} ({tiles} tiles)", flush=True)
+    wt = w.with_batch(np.tile(w.x, (reps, 1)))
+    Bs = (wt.B + 31) // 32 * 32
+    n_tiles64 = (2048 if "H2048" in w.name else 4096) // 64 * (Bs // 64)
+    assert (Bs % 64 == 0 and n_tiles64 >= 200) == (tiles == "64x64")       # the shape the launcher will pick
+    fwd, bwd = bf16_sum_launches(wt)
+    assert fwd == 2 and bwd == 2, "the transition layers did not take the bf16-split kernels"
+    check_repeated(w, reps)
 
 
 def check_repeated(w, reps, mask=None):
