@@ -1401,7 +1401,8 @@ __global__ __launch_bounds__(256) void k_split_p(const float *__restrict__ X, co
 // Sum layer on the planes, forward (rows = sum blocks, neighbours = their product children) and backward to the
 // children (rows = product blocks, neighbours = their sum parents, theta planes transposed).  Workgroup = 4 waves that
 // share one output tile of 64 rows x 32 CT columns and take the row's neighbour blocks in turn (a split of the
-// reduction; merged through LDS at the end).  Per 16-node slice a wave fetches 2 + 2 theta tiles and CT + CT value tiles
+// reduction); at the end the tile's 32 x 32 parts are dealt to the waves, which merge the four partial sums through
+// LDS and write the results.  Per 16-node slice a wave fetches 2 + 2 theta tiles and CT + CT value tiles
 // (hi and lo planes, 16 bytes per lane each, 1 KiB per wave load) and issues 6 CT MFMAs; the operands of D slices are
 // in flight at any time (a ring of D register sets that runs across the neighbour blocks).
 //   forward : block scale = R_c (integer reference of the child block); result l = ln(sum) - PC_UP relative to the
@@ -1421,9 +1422,8 @@ __global__ __launch_bounds__(256, CT == 1 ? 2 : 1) void k_sum_bf16(const uint4 *
                                                                    const GroupSet gs, int64_t Bs)
 {
     constexpr int NKS = K / 16, NRT = K / 32, SUB = K / 64;
-    constexpr int XCH = (2 * 16 * 64 + 64) * CT;                        // one partial accumulator tile and its references
     static_assert(NKS % D == 0, "the ring must divide a block's slices");
-    __shared__ float lds[3 * XCH];
+    __shared__ float lds[2 * CT * 3 * 1024 + 4 * CT * 64];              // partial tiles of the merge and the waves' references
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
     const GroupRow gr = locate_row<false>(gs, blockIdx.x / SUB);
@@ -1521,70 +1521,75 @@ __global__ __launch_bounds__(256, CT == 1 ? 2 : 1) void k_sum_bf16(const uint4 *
         ps_cur = ps_nxt;
     }
 
-    // merge the four partial tiles
-    float *buf = lds + (wave - 1) * XCH;
-    if (wave != 0) {
-#pragma unroll
-        for (int c = 0; c < CT; ++c) {
-#pragma unroll
-            for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) buf[((c * 2 + rt) * 16 + e) * 64 + lane] = acc[rt][c][e];
-            buf[2 * CT * 16 * 64 + c * 64 + lane] = m[c];
-        }
-    }
-    __syncthreads();
-    if (wave != 0) return;
-#pragma unroll 1
-    for (int w = 0; w < 3; ++w) {
-        const float *ob = lds + w * XCH;
-#pragma unroll
-        for (int c = 0; c < CT; ++c) {
-            const float mo = ob[2 * CT * 16 * 64 + c * 64 + lane];      // -inf: that wave had no block (its sums are 0)
-            const float mn = fmaxf(m[c], mo);
-            const float sa = m[c] > PC_NEG_INF ? __expf(m[c] - mn) : 0.0f, sb = mo > PC_NEG_INF ? __expf(mo - mn) : 0.0f;
-            m[c] = mn;
-#pragma unroll
-            for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[rt][c][e] = acc[rt][c][e] * sa + ob[((c * 2 + rt) * 16 + e) * 64 + lane] * sb;
-        }
-    }
-    const bool first = (fl & 2) != 0;                                   // backward: the first layer that feeds the block stores
+    // Merge and results: the 2 CT tiles of 32 x 32 outputs are dealt to the waves, tile u = 2 c + rt to wave u; every
+    // wave leaves its partial sums of the tiles it does not own in LDS (three sets per tile) and its references.
+    constexpr int NU = 2 * CT;
+    float *mref = lds + NU * 3 * 1024;
 #pragma unroll
     for (int c = 0; c < CT; ++c) {
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+            const int u = c * 2 + rt;
+            if (wave != u) {
+                float *dst = lds + (u * 3 + (wave < u ? wave : wave - 1)) * 1024;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) dst[e * 64 + lane] = acc[rt][c][e];
+            }
+        }
+        mref[(wave * CT + c) * 64 + lane] = m[c];
+    }
+    __syncthreads();
+    const bool first = (fl & 2) != 0;                                   // backward: the first layer that feeds the block stores
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+        if (wave != u) continue;                                        // uniform: a wave takes one of the branches
+        const int c = u / 2, rt = u % 2;
         const int64_t col = col0 + 32 * c;
-        if (!BWD && sub == 0 && half == 0) R[(int64_t)(id / K) * Bs + col] = m[c];
         // backward: the rows' own log-probabilities (and, where this layer accumulates, the flows so far) are all
         // requested before the first of them is used -- a load inside the per-element branch would be waited for on its
-        // own, 32 times
-        floatx16 lown[2], fold[2];
+        // own, 16 times
+        floatx16 lown, fold;
         if (BWD) {
 #pragma unroll
-            for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int64_t at = (int64_t)(id + sub * 64 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4)) * Bs + col;
-                    lown[rt][e] = l[at];
-                    fold[rt][e] = first ? 0.0f : F[at];
-                }
-        }
-#pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int row = sub * 64 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
-                const int64_t at = (int64_t)(id + row) * Bs + col;
-                if (!BWD) {
-                    // ln(sum) - PC_UP, the logarithm taken of sum / 2^24 (see the fp32 kernel)
-                    l[at] = fmaf(__builtin_amdgcn_logf(acc[rt][c][e] * 0x1p-24f), 0.6931471805599453f, 16.635532333f - PC_UP);
-                } else {
-                    // exp(ln(sum) + (m - PC_UP) + l_row); sum = 0 or l_row = -inf gives exp2(-inf) = 0
-                    const float lg = __builtin_amdgcn_logf(acc[rt][c][e]);
-                    const float add = __builtin_amdgcn_exp2f(lg + (lown[rt][e] + (m[c] - PC_UP)) * PC_LOG2E);
-                    F[at] = fold[rt][e] + (m[c] > PC_NEG_INF ? add : 0.0f);
-                }
+                const int64_t at = (int64_t)(id + sub * 64 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4)) * Bs + col;
+                lown[e] = l[at];
+                fold[e] = first ? 0.0f : F[at];
             }
+        }
+        float mw[4], mt = PC_NEG_INF;                                   // the four waves' references of this column; -inf: no block
+#pragma unroll
+        for (int w = 0; w < 4; ++w) { mw[w] = mref[(w * CT + c) * 64 + lane]; mt = fmaxf(mt, mw[w]); }
+        floatx16 tot;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) tot[e] = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float sc = mw[w] > PC_NEG_INF ? __expf(mw[w] - mt) : 0.0f;
+            if (w == u) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) tot[e] += acc[rt][c][e] * sc;
+            } else {
+                const float *src = lds + (u * 3 + (w < u ? w : w - 1)) * 1024;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) tot[e] += src[e * 64 + lane] * sc;
+            }
+        }
+        if (!BWD && sub == 0 && rt == 0 && half == 0) R[(int64_t)(id / K) * Bs + col] = mt;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int row = sub * 64 + rt * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+            const int64_t at = (int64_t)(id + row) * Bs + col;
+            if (!BWD) {
+                // ln(sum) - PC_UP, the logarithm taken of sum / 2^24 (see the fp32 kernel)
+                l[at] = fmaf(__builtin_amdgcn_logf(tot[e] * 0x1p-24f), 0.6931471805599453f, 16.635532333f - PC_UP);
+            } else {
+                // exp(ln(sum) + (m - PC_UP) + l_row); sum = 0 or l_row = -inf gives exp2(-inf) = 0
+                const float lg = __builtin_amdgcn_logf(tot[e]);
+                const float add = __builtin_amdgcn_exp2f(lg + (lown[e] + (mt - PC_UP)) * PC_LOG2E);
+                F[at] = fold[e] + (mt > PC_NEG_INF ? add : 0.0f);
+            }
+        }
     }
 }
 
