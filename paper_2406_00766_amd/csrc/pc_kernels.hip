@@ -388,20 +388,25 @@ __device__ inline void bf16_split2(float a, float b, uint32_t &hi, uint32_t &lo)
 // One 1 KiB tile of the value planes read by the bf16 sum kernels (see there): exp(X + sh) of 16 node rows x 32 columns,
 // split into hi and lo bf16 values; lane (j = lane % 32, h = lane / 32) owns rows 8 h .. 8 h + 7 of column j.  `sh` is
 // the lane's shift (per column), -inf for a column without flow.  row0 = first node row of the slice.
-__device__ inline void split_value_tile(const float *__restrict__ X, float sh, int64_t row0, int ct, int n_ct, int64_t Bs,
+// `src` points at the lane's column in the slice's first row (global rows, or a tile in LDS), `ld` is its row stride.
+__device__ inline void split_value_rows(const float *src, int64_t ld, float sh, int64_t row0, int ct, int n_ct,
                                         uint4 *__restrict__ Ph, uint4 *__restrict__ Pl, int lane)
 {
-    const int j = lane & 31, h = lane >> 5;
-    const int64_t col = (int64_t)ct * 32 + j;
+    const int h = lane >> 5;
     float v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = __expf(X[(row0 + 8 * h + e) * Bs + col] + sh);
+    for (int e = 0; e < 8; ++e) v[e] = __expf(src[(8 * h + e) * ld] + sh);
     uint32_t hi[4], lo[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) bf16_split2(v[2 * e], v[2 * e + 1], hi[e], lo[e]);
     const int64_t tile = (row0 / 16) * n_ct + ct;
     Ph[tile * 64 + lane] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
     Pl[tile * 64 + lane] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+}
+__device__ inline void split_value_tile(const float *__restrict__ X, float sh, int64_t row0, int ct, int n_ct, int64_t Bs,
+                                        uint4 *__restrict__ Ph, uint4 *__restrict__ Pl, int lane)
+{
+    split_value_rows(X + row0 * Bs + (int64_t)ct * 32 + (lane & 31), Bs, sh, row0, ct, n_ct, Ph, Pl, lane);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -502,10 +507,11 @@ __global__ __launch_bounds__(256) void k_prod_fwd(const float *__restrict__ l, f
     }
     block_col_max<CL>(mx, red, wave, cl);
     if (!PLANES && !in) return;
-    if (in) {
-        float sh[4];
+    float sh4[4];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) sh[v] = mx[v] > PC_NEG_INF ? rintf(mx[v]) : 0.0f;
+    for (int v = 0; v < 4; ++v) sh4[v] = mx[v] > PC_NEG_INF ? rintf(mx[v]) : 0.0f;
+    if (in) {
+        const float (&sh)[4] = sh4;
         if (rg == 0)
             *reinterpret_cast<float4 *>(R + (int64_t)(id / K) * Bs + b) = make_float4(rsum.x + sh[0], rsum.y + sh[1], rsum.z + sh[2], rsum.w + sh[3]);
 #pragma unroll
@@ -519,14 +525,28 @@ __global__ __launch_bounds__(256) void k_prod_fwd(const float *__restrict__ l, f
     }
     if (PLANES) {
         // the block's tile again as bf16 operand planes for a sum layer that runs on the bf16 matrix cores (this saves
-        // the launch of k_split_p): the rows just stored are read back through L2 once every store has landed
-        __threadfence_block();
+        // the launch of k_split_p), taken from a copy of the tile in LDS: a lane of the plane layout owns eight rows of one
+        // column, a thread here four columns of RPT rows
+        constexpr int LDT = 4 * CL + 1;
+        __shared__ float ptile[PLANES ? 128 * LDT : 1];
+        if (in) {
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) {
+                const int k = rg + RG * i;
+                if (k < K) {
+                    float *dst = ptile + k * LDT + cl * 4;
+                    dst[0] = (float)(s[i].x - (ACC)sh4[0]); dst[1] = (float)(s[i].y - (ACC)sh4[1]);
+                    dst[2] = (float)(s[i].z - (ACC)sh4[2]); dst[3] = (float)(s[i].w - (ACC)sh4[3]);
+                }
+            }
+        }
         __syncthreads();
         const int n_ct = (int)(Bs / 32), lane = threadIdx.x & 63;
         constexpr int CTW = CL / 8;                                     // 32-column tiles of the workgroup
         for (int it = wave; it < (K / 16) * CTW; it += 4) {
-            const int ks = it / CTW, ct = (int)blockIdx.y * CTW + it % CTW;
-            if (ct < n_ct) split_value_tile(lout, PC_UP, (int64_t)id + 16 * ks, ct, n_ct, Bs, Ph, Pl, lane);
+            const int ks = it / CTW, cw = it % CTW, ct = (int)blockIdx.y * CTW + cw;
+            if (ct < n_ct)
+                split_value_rows(ptile + 16 * ks * LDT + cw * 32 + (lane & 31), LDT, PC_UP, (int64_t)id + 16 * ks, ct, n_ct, Ph, Pl, lane);
         }
     }
 }
@@ -595,6 +615,7 @@ __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, f
     }
     if (!final_flow) return;
     float mx[4] = {PC_NEG_INF, PC_NEG_INF, PC_NEG_INF, PC_NEG_INF};
+    float4 nfv[PLANES ? RPT : 1];
     if (in) {
 #pragma unroll
         for (int i = 0; i < RPT; ++i) {
@@ -606,6 +627,7 @@ __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, f
                 nf.z = (f[i].z > 0.0f && lv[i].z > PC_NEG_INF) ? __logf(f[i].z) - lv[i].z : PC_NEG_INF;
                 nf.w = (f[i].w > 0.0f && lv[i].w > PC_NEG_INF) ? __logf(f[i].w) - lv[i].w : PC_NEG_INF;
                 *reinterpret_cast<float4 *>(N + (int64_t)(id + k) * Bs + b) = nf;
+                if (PLANES) nfv[i] = nf;
                 mx[0] = fmaxf(mx[0], nf.x); mx[1] = fmaxf(mx[1], nf.y); mx[2] = fmaxf(mx[2], nf.z); mx[3] = fmaxf(mx[3], nf.w);
             }
         }
@@ -614,16 +636,33 @@ __global__ __launch_bounds__(256) void k_prod_bwd(const float *__restrict__ l, f
     if (in && rg == 0) *reinterpret_cast<float4 *>(nfmax + (int64_t)(id / K) * Bs + b) = make_float4(mx[0], mx[1], mx[2], mx[3]);
     if (PLANES) {
         // exp(log_nf - column maximum + PC_UP) of the block as bf16 operand planes for a sum layer whose backward pass
-        // runs on the bf16 matrix cores (saves the launch of k_split_p); read back through L2 once the stores have landed
-        __threadfence_block();
+        // runs on the bf16 matrix cores (saves the launch of k_split_p), taken from a copy of the tile in LDS (row K: the
+        // column maxima)
+        constexpr int LDT = 4 * CL + 1;
+        __shared__ float ptile[PLANES ? 129 * LDT : 1];
+        if (in) {
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) {
+                const int k = rg + RG * i;
+                if (k < K) {
+                    float *dst = ptile + k * LDT + cl * 4;
+                    dst[0] = nfv[i].x; dst[1] = nfv[i].y; dst[2] = nfv[i].z; dst[3] = nfv[i].w;
+                }
+            }
+            if (rg == 0) {
+                float *dst = ptile + 128 * LDT + cl * 4;
+                dst[0] = mx[0]; dst[1] = mx[1]; dst[2] = mx[2]; dst[3] = mx[3];
+            }
+        }
         __syncthreads();
         const int n_ct = (int)(Bs / 32), lane = threadIdx.x & 63;
         constexpr int CTW = CL / 8;                                     // 32-column tiles of the workgroup
         for (int it = wave; it < (K / 16) * CTW; it += 4) {
-            const int ks = it / CTW, ct = (int)blockIdx.y * CTW + it % CTW;
+            const int ks = it / CTW, cw = it % CTW, ct = (int)blockIdx.y * CTW + cw;
             if (ct >= n_ct) continue;
-            const float top = nfmax[(int64_t)(id / K) * Bs + (int64_t)ct * 32 + (lane & 31)];
-            split_value_tile(N, top > PC_NEG_INF ? PC_UP - top : PC_NEG_INF, (int64_t)id + 16 * ks, ct, n_ct, Bs, Ph, Pl, lane);
+            const float top = ptile[128 * LDT + cw * 32 + (lane & 31)];
+            split_value_rows(ptile + 16 * ks * LDT + cw * 32 + (lane & 31), LDT, top > PC_NEG_INF ? PC_UP - top : PC_NEG_INF,
+                             (int64_t)id + 16 * ks, ct, n_ct, Ph, Pl, lane);
         }
     }
 }
