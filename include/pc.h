@@ -22,6 +22,13 @@
  *   - tables[t][c][k]: probability of category c under node k of an input block that uses table t
  *     (category-major so that one (sample, variable) lookup reads K contiguous floats; the paper
  *     gives no input-layer layout).
+ *   - Precision: fp32 data and fp32 accumulation everywhere.  Sum layers of K = 64 / 128 whose rows reduce over at least
+ *     2048 child nodes, and parameter flows reduced over at least 4096 samples per parameter block, take each product
+ *     as three bf16 MFMAs on operands split into a bf16 pair (hi + lo; the dropped lo x lo term is 2^-16 relative).
+ *   - Environment switches, read once per process, for measurements and cross-checks (results stay within the same
+ *     tolerances): PC_BF16=0 keeps every contraction on the fp32 matrix cores; PC_BF16_CT=1|2 forces the 64 x 32 or
+ *     64 x 64 tile form of the bf16 sum kernels; PC_FORCE_GENERIC=1 (read by pc_compile) routes every block size
+ *     through the one-thread-per-output kernels.
  */
 #ifndef PC_H_
 #define PC_H_
