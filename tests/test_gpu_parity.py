@@ -603,6 +603,24 @@ def test_out_of_range_category_has_probability_zero():
         assert np.all(got["flow"][2] == 0.0) and np.all(got["flow"][5] == 0.0)
 
 
+@pytest.mark.parametrize("make", [
+    lambda: W.hmm(7, 64, 3000, 32, 300, 61, tokens="zipf"),             # two slabs (256 + 64 columns), K = 32: two node slices
+    lambda: W.hmm(5, 32, 2000, 16, 70, 62, tokens="zipf"),              # K = 16, one slice, small-block kernels elsewhere
+    lambda: W.hmm(4, 256, 5000, 128, 33, 63, tokens="zipf"),            # K = 128, a few samples
+    lambda: W.hclt(9, 64, 64, 90, 64, n_cats=1200),                     # untied tables: one input block per table
+])
+def test_large_vocabulary_table_flows(make):
+    """More than 1024 categories (per-sample adds into the table rows), with masked and out-of-range samples, a ragged
+    second slab of columns, tied and untied tables."""
+    w = make()
+    print(f"case large vocabulary {w.name}", flush=True)
+    rng = np.random.default_rng(6)
+    mask = (rng.random(w.x.shape) < 0.2).astype(np.uint8)
+    x = w.x.copy(); x[1, 0] = w.n_cats + 3; x[w.B - 1, w.n_vars - 1] = -7
+    wx = w.with_batch(x)
+    check_all(wx, mask)
+
+
 def test_parameter_flows_repeat_bit_for_bit_where_no_pairs_are_split():
     """Parameter flows are written by exactly one workgroup per parameter block, in a fixed order, unless the launcher
     deals the tied pairs of a block over several waves or workgroups (fewer than 128 parameter blocks with at least two
