@@ -1331,18 +1331,6 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
     const __amdgpu_buffer_rsrc_t ro =
         __builtin_amdgcn_make_buffer_rsrc((void *)(out + (int64_t)(id + sub * TM) * Bs), 0, PC_BUF_RANGE, PC_BUF_FLAGS);
     const float mb = (m - PC_UP) * PC_LOG2E;
-    // backward, a block that earlier layers of the sweep have fed already: its flows so far are all requested before the
-    // first is used (a load inside the per-element branch is waited for on its own, once per element)
-    floatx16 fold[BWD ? RT : 1];
-    if (BWD && !first) {
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int so = __builtin_amdgcn_readfirstlane((int)((int64_t)(rt * 32 + 8 * (e / 4) + (e % 4)) * Bs * 4));
-                fold[rt][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ro, ooff, so, 0));
-            }
-    }
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
@@ -1354,8 +1342,12 @@ __global__ __launch_bounds__(256, 2) void k_sum_mfma(const float *__restrict__ t
                 const float lc = lown[rt][e];
                 // exp(ln a + (m - PC_UP) + lc); a = 0 or lc = -inf gives exp2(-inf) = 0
                 const float add = __builtin_amdgcn_exp2f(lg + fmaf(lc, PC_LOG2E, mb));
-                const float out_v = first ? add : fold[rt][e] + add;
-                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, out_v), ro, ooff, so, 0);
+                if (first) {
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, add), ro, ooff, so, 0);
+                } else if (add > 0.0f) {
+                    const float old = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ro, ooff, so, 0));
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, old + add), ro, ooff, so, 0);
+                }
             } else {
                 // ln a + (m - PC_UP), with the logarithm taken of a / 2^24: the accumulator of a live column is around
                 // e^PC_UP, and a base-2 logarithm near 0 is far more accurate in absolute terms than one near 29 --
