@@ -506,11 +506,17 @@ def test_em_on_tied_hmm_matches_oracle_and_improves_likelihood():
     assert ll1 >= ll0
 
 
-def test_forward_and_backward_replayed_from_a_captured_graph():
+@pytest.mark.parametrize("make", [
+    lambda: W.reduced(2),
+    # the bf16-split path: plane splits, product kernels that write planes, bf16 sum kernels (256 samples: 64 x 32 tiles)
+    lambda: W.hmm(3, 2048, 40, 128, 256, 65, alpha_trans=0.1, alpha_emis=0.1),
+])
+def test_forward_and_backward_replayed_from_a_captured_graph(make):
     """pc_forward / pc_backward only enqueue kernels, so a caller may capture them into a HIP graph.  The graph is
     replayed several times with eager work and synchronisations in between; every replay must reproduce the eager
     result (log-likelihoods and parameter flows bit for bit: no atomics on those paths)."""
-    w = W.reduced(2)
+    w = make()
+    print(f"case graph {w.name}", flush=True)
     c = pcb.Circuit(w)
     c.set_batch(w.x)
     c.forward(); c.backward()
